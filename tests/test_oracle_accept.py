@@ -1,0 +1,411 @@
+"""Pins for the oracle's acceptance rule (CPU only).
+
+The rule is randomised; the oracle is deterministic in the uniforms it is handed.  The exact
+pins below recover, by bisection on the oracle's own decisions, the measure of uniforms that
+leads to each outcome, and compare the resulting output distribution with what the rule must
+produce: the target row itself for the strict rule (the property of the speculative sampling
+rule the paper builds on, section 2.1), the softened target of section 2.3 when a relaxation
+is forced.  The Monte-Carlo pins do the same statistically on larger cases.
+"""
+import itertools
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import dsd_oracle as O
+from paper_2511_11733_amd import workloads as W
+
+pytestmark = pytest.mark.filterwarnings("ignore")
+
+
+def rand_dist(rng, V, sharp=1.0):
+    z = rng.standard_normal(V) * sharp
+    e = np.exp(z - z.max())
+    return e / e.sum()
+
+
+def logits_of(p):
+    return np.log(p)
+
+
+def run1(logit_rows, q_rows, toks, u, prm=None, parent=None, tau_override=None):
+    """One sequence through the oracle."""
+    prm = prm or O.AcceptParams()
+    lo = np.asarray(logit_rows, dtype=np.float64)[None]
+    q = np.asarray(q_rows, dtype=np.float64)[None]
+    t = np.asarray(toks, dtype=np.int32)[None]
+    uu = np.asarray(u, dtype=np.float64)[None]
+    to = None if tau_override is None else np.asarray(tau_override, dtype=np.float64)[None]
+    return O.accept(lo, q, t, parent, uu, prm, to)
+
+
+def sup_where(pred, lo=0.0, hi=1.0, it=60):
+    """sup{u in [lo,hi): pred(u)} for a predicate that is true then false."""
+    if not pred(lo):
+        return lo
+    if pred(np.nextafter(hi, 0)):
+        return hi
+    for _ in range(it):
+        mid = 0.5 * (lo + hi)
+        if pred(mid):
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def emitted_distribution_k1(pt0, pt1, q0, prm=None, tau_override=None):
+    """Exact distribution of the first emitted token and, given acceptance, of the second, for a
+    one-token draft, from the oracle's decisions only."""
+    V = len(pt0)
+    rows = [logits_of(pt0), logits_of(pt1)]
+    qrows = [q0, np.full(V, 1.0 / V)]
+    first = np.zeros(V)
+    second_given_acc = np.zeros((V, V))
+    for y in range(V):
+        if q0[y] == 0:
+            continue
+        A = sup_where(lambda u: run1(rows, qrows, [y], [0.5, u], prm, None, tau_override).accepted_len[0] == 1)
+        first[y] += q0[y] * A
+        # token drawn as a function of u0: a non-decreasing step function
+        for accepted, uacc, wgt in ((1, 0.0, None), (0, np.nextafter(1.0, 0), q0[y] * (1 - A))):
+            if accepted and A == 0:
+                continue
+            if not accepted and A >= 1:
+                continue
+            cdf = np.zeros(V)
+            for v in range(V):
+                cdf[v] = sup_where(lambda u0: run1(rows, qrows, [y], [u0, uacc], prm, None,
+                                                   tau_override).next_token[0] <= v)
+            pm = np.diff(np.concatenate([[0.0], cdf]))
+            if accepted:
+                second_given_acc[y] = pm
+            else:
+                first += wgt * pm
+    return first, second_given_acc
+
+
+# ------------------------------------------------------------------ exact pins, strict rule
+@pytest.mark.parametrize("V,seed", [(3, 0), (6, 1), (16, 2)])
+def test_strict_rule_is_lossless_exact_k1(V, seed):
+    rng = np.random.default_rng(seed)
+    pt0, pt1, q0 = rand_dist(rng, V, 1.5), rand_dist(rng, V, 1.5), rand_dist(rng, V, 1.5)
+    first, second = emitted_distribution_k1(pt0, pt1, q0)
+    np.testing.assert_allclose(first, pt0, atol=1e-12)           # k=1 is ordinary sampling
+    for y in range(V):
+        np.testing.assert_allclose(second[y], pt1, atol=1e-12)   # bonus token from the next target row
+
+
+def test_strict_rule_with_zero_mass_tokens():
+    pt0 = np.array([0.5, 0.0, 0.3, 0.2])
+    q0 = np.array([0.0, 0.4, 0.6, 0.0])
+    pt1 = np.array([0.25, 0.25, 0.25, 0.25])
+    first, _ = emitted_distribution_k1(np.maximum(pt0, 1e-300), pt1, q0)
+    np.testing.assert_allclose(first, pt0, atol=1e-12)
+
+
+def test_accept_threshold_is_p_over_q():
+    pt = np.array([0.1, 0.2, 0.3, 0.4])
+    q = np.array([0.4, 0.3, 0.2, 0.1])
+    for y, thr in enumerate([0.25, 2.0 / 3.0, 1.0, 1.0]):
+        A = sup_where(lambda u: run1([logits_of(pt)] * 2, [q, q], [y], [0.5, u]).accepted_len[0] == 1)
+        assert abs(A - thr) < 1e-12
+    # residual after rejecting token 0: (p - q)+ = [0, 0, .1, .3] / .4
+    r = run1([logits_of(pt)] * 2, [q, q], [0], [0.2, 0.9])
+    assert r.accepted_len[0] == 0 and r.next_token[0] == 2
+    r = run1([logits_of(pt)] * 2, [q, q], [0], [0.26, 0.9])
+    assert r.next_token[0] == 3
+
+
+def test_k2_joint_prefix_exact():
+    """Two drafted tokens, V=4: P(first = v) = P_t(v | root); given the first was accepted,
+    the second emitted token follows the target row after it."""
+    rng = np.random.default_rng(7)
+    V = 4
+    pt0 = rand_dist(rng, V)
+    q0 = rand_dist(rng, V)
+    pt_after = [rand_dist(rng, V) for _ in range(V)]     # target row after first token y1
+    q_after = [rand_dist(rng, V) for _ in range(V)]
+    pt_last = rand_dist(rng, V)
+    first = np.zeros(V)
+    for y1 in range(V):
+        rows = [logits_of(pt0), logits_of(pt_after[y1]), logits_of(pt_last)]
+        qr = [q0, q_after[y1], np.full(V, 0.25)]
+        A1 = sup_where(lambda u: run1(rows, qr, [y1, 0], [0.5, u, 0.5]).accepted_len[0] >= 1)
+        assert abs(A1 - min(1, pt0[y1] / q0[y1])) < 1e-12
+        first[y1] += q0[y1] * A1
+        # rejected at node 1: residual draw
+        if A1 < 1:
+            cdf = [sup_where(lambda u0: run1(rows, qr, [y1, 0], [u0, 0.999999, 0.5]).next_token[0] <= v)
+                   for v in range(V)]
+            first += q0[y1] * (1 - A1) * np.diff([0.0] + cdf)
+        # accepted at node 1: second emitted token
+        second = np.zeros(V)
+        for y2 in range(V):
+            A2 = sup_where(lambda u: run1(rows, qr, [y1, y2], [0.5, 0.0, u]).accepted_len[0] == 2)
+            second[y2] += q_after[y1][y2] * A2
+            if A2 < 1:
+                cdf = [sup_where(lambda u0: run1(rows, qr, [y1, y2], [u0, 0.0, 0.999999]).next_token[0] <= v)
+                       for v in range(V)]
+                second += q_after[y1][y2] * (1 - A2) * np.diff([0.0] + cdf)
+        np.testing.assert_allclose(second, pt_after[y1], atol=1e-12)
+    np.testing.assert_allclose(first, pt0, atol=1e-12)
+
+
+def test_draft_equal_target_accepts_everything():
+    rng = np.random.default_rng(3)
+    B, k, V = 5, 6, 11
+    lo = rng.standard_normal((B, k + 1, V))
+    q = np.stack([[O.softmax_row(lo[b, i], 1.0) for i in range(k + 1)] for b in range(B)])
+    toks = rng.integers(0, V, size=(B, k))
+    u = rng.random((B, k + 1))
+    u[:, 1:] = np.nextafter(1.0, 0)          # the hardest uniforms
+    r = O.accept(lo, q, toks, None, u, O.AcceptParams())
+    assert (r.accepted_len == k).all()
+    assert (r.accepted_path == np.arange(1, k + 1)).all()
+
+
+# ------------------------------------------------------------------ Monte Carlo pins
+def mc_case(seed, N, k, V, prm, same_rows=False):
+    rng = np.random.default_rng(seed)
+    if same_rows:
+        pt = np.tile(rand_dist(rng, V), (k + 1, 1))
+        q = np.tile(rand_dist(rng, V), (k + 1, 1))
+    else:
+        pt = np.stack([rand_dist(rng, V) for _ in range(k + 1)])
+        q = np.stack([rand_dist(rng, V) for _ in range(k + 1)])
+    lo = np.broadcast_to(np.log(pt), (N, k + 1, V))
+    qq = np.broadcast_to(q, (N, k + 1, V))
+    toks = np.stack([[rng.choice(V, p=q[i]) for i in range(k)] for _ in range(N)])
+    u = rng.random((N, k + 1))
+    return pt, q, O.accept(lo, qq, toks, None, u, prm), toks
+
+
+def test_monte_carlo_emitted_tokens_follow_target():
+    """Position-wise rows (independent of earlier tokens): the j-th emitted token of a round,
+    when there is one, must follow target row j-1."""
+    N, k, V = 6000, 3, 8
+    pt, q, r, toks = mc_case(11, N, k, V, O.AcceptParams())
+    for j in range(k + 1):
+        have = r.accepted_len >= j
+        emitted = np.where(r.accepted_len[have] > j, toks[have][:, min(j, k - 1)], r.next_token[have])
+        cnt = np.bincount(emitted, minlength=V)
+        p = stats.chisquare(cnt, pt[j] * cnt.sum()).pvalue
+        assert p > 1e-4, (j, p)
+
+
+def test_expected_accepted_length_closed_form():
+    N, k, V = 6000, 5, 8
+    pt, q, r, _ = mc_case(12, N, k, V, O.AcceptParams(), same_rows=True)
+    alpha = np.minimum(pt[0], q[0]).sum()
+    want = alpha * (1 - alpha ** k) / (1 - alpha)
+    se = r.accepted_len.std() / np.sqrt(N)
+    assert abs(r.accepted_len.mean() - want) < 4 * se
+
+
+# ------------------------------------------------------------------ softened target, key rule
+def test_softened_target_closed_forms():
+    pt = np.array([0.5, 0.5])
+    q = np.array([0.8, 0.2])
+    np.testing.assert_allclose(O.softened_target(pt, q, 0.5), [2 / 3, 1 / 3], atol=1e-15)
+    rng = np.random.default_rng(0)
+    pt, q = rand_dist(rng, 9), rand_dist(rng, 9)
+    assert O.softened_target(pt, q, 0.0) is pt
+    np.testing.assert_allclose(O.softened_target(pt, q, 1.0), q, atol=1e-15)
+    for tau in (0.1, 0.3, 0.8):
+        s = O.softened_target(pt, q, tau)
+        assert abs(s.sum() - 1) < 1e-14
+        # log-linear interpolation: ln s - ((1-tau) ln pt + tau ln q) is one constant
+        c = np.log(s) - ((1 - tau) * np.log(pt) + tau * np.log(q))
+        assert np.ptp(c) < 1e-13
+    # x^0 = 1 also for x = 0
+    np.testing.assert_allclose(O.softened_target(np.array([0.0, 1.0]), np.array([0.5, 0.5]), 1.0), [0.5, 0.5])
+    np.testing.assert_allclose(O.softened_target(np.array([0.0, 1.0]), np.array([0.5, 0.5]), 0.5), [0.0, 1.0])
+
+
+def test_tau_zero_and_one_limits_in_the_loop():
+    rng = np.random.default_rng(21)
+    B, k, V = 40, 4, 12
+    lo = rng.standard_normal((B, k + 1, V))
+    q = np.stack([[rand_dist(rng, V) for _ in range(k + 1)] for _ in range(B)])
+    toks = rng.integers(0, V, size=(B, k))
+    u = rng.random((B, k + 1))
+    strict = O.accept(lo, q, toks, None, u, O.AcceptParams())
+    # tau = 0 through the adaptive path (no token is key) is the strict rule, bit for bit
+    a0 = O.accept(lo, q, toks, None, u, O.AcceptParams(tau=0.0, lambda1=np.inf, lambda2=np.inf, lambda3=-1))
+    assert (a0.accepted_len == strict.accepted_len).all() and (a0.next_token == strict.next_token).all()
+    # tau = 1: the softened target is the draft row, every token passes
+    a1 = O.accept(lo, q, toks, None, u, O.AcceptParams(tau=1.0))
+    assert (a1.accepted_len == k).all()
+    assert not a1.key.any()
+    # relaxation can only lengthen spans of non-key tokens when p < q ... check monotone on average
+    a3 = O.accept(lo, q, toks, None, u, O.AcceptParams(tau=0.3))
+    assert a3.accepted_len.mean() >= strict.accepted_len.mean()
+
+
+def test_forced_relaxation_emits_softened_target_exact():
+    rng = np.random.default_rng(5)
+    V, tau = 6, 0.35
+    pt0, pt1, q0 = rand_dist(rng, V, 1.5), rand_dist(rng, V), rand_dist(rng, V, 1.5)
+    first, second = emitted_distribution_k1(pt0, pt1, q0, O.AcceptParams(tau=0.9), tau_override=[tau])
+    np.testing.assert_allclose(first, O.softened_target(pt0, q0, tau), atol=1e-12)
+    for y in range(V):
+        np.testing.assert_allclose(second[y], pt1, atol=1e-12)    # bonus row is never softened
+
+
+def test_norm_match_and_top_m():
+    pt = np.array([0.4, 0.3, 0.2, 0.1])
+    q = np.array([0.1, 0.4, 0.3, 0.2])
+    assert O.top_m_ids(pt, 2).tolist() == [0, 1]
+    assert O.top_m_ids(q, 2).tolist() == [1, 2]
+    assert O.norm_match(pt, q, 2) == 0.5
+    assert O.norm_match(pt, pt, 3) == 1.0
+    assert O.norm_match(pt, pt[::-1].copy(), 2) == 0.0
+    # equal values: the lower id wins the last place
+    assert O.top_m_ids(np.array([0.2, 0.3, 0.3, 0.2]), 3).tolist() == [1, 2, 0]
+
+
+def test_key_rule_is_an_or_of_three_and_forces_strict():
+    pt = np.array([0.05, 0.6, 0.2, 0.15])
+    q = np.array([0.5, 0.1, 0.15, 0.25])
+    lo = [logits_of(pt)] * 2
+    qq = [q, q]
+    y = 0                       # H_t = -ln .05 = 3.0, H_d = -ln .5 = .69 ; |p-q| = .45 ; NormMatch(M=2) = .0
+    base = dict(tau=0.5, top_m=2)
+    none = O.AcceptParams(lambda1=1.0, lambda2=0.5, lambda3=0.0, **base)
+    assert not run1(lo, qq, [y], [0.5, 0.5], none).key[0, 0]
+    only1 = O.AcceptParams(lambda1=0.2, lambda2=0.5, lambda3=0.0, **base)      # .69 > .2*3.0
+    only2 = O.AcceptParams(lambda1=1.0, lambda2=0.4, lambda3=0.0, **base)      # .45 > .4
+    only3 = O.AcceptParams(lambda1=1.0, lambda2=0.5, lambda3=0.25, **base)     # 0 < .25
+    strict = run1(lo, qq, [y], [0.5, 0.12])
+    for prm in (only1, only2, only3):
+        r = run1(lo, qq, [y], [0.5, 0.12], prm)
+        assert r.key[0, 0] and r.tau_used[0, 0] == 0.0
+        assert r.accepted_len[0] == strict.accepted_len[0] and r.next_token[0] == strict.next_token[0]
+        assert abs(r.ratio[0, 0] - 0.1) < 1e-15
+    r = run1(lo, qq, [y], [0.5, 0.12], none)
+    st = O.softened_target(pt, q, 0.5)
+    assert abs(r.ratio[0, 0] - st[0] / q[0]) < 1e-15 and r.tau_used[0, 0] == 0.5
+    assert r.accepted_len[0] == 1 and strict.accepted_len[0] == 0      # .12 < ratio~.41 but .12 > .1
+
+
+def test_temperature_scales_logits():
+    rng = np.random.default_rng(2)
+    lo = rng.standard_normal((2, 8))
+    q = np.stack([rand_dist(rng, 8)] * 2)
+    a = run1(lo, q, [3], [0.3, 0.4], O.AcceptParams(temperature=0.5))
+    b = run1(lo * 2.0, q, [3], [0.3, 0.4], O.AcceptParams(temperature=1.0))
+    assert a.ratio[0, 0] == pytest.approx(b.ratio[0, 0], rel=1e-14) and a.next_token[0] == b.next_token[0]
+
+
+# ------------------------------------------------------------------ trees
+def forced_case(parent, pattern, V=5, seed=0):
+    """Rows where every drafted token has p/q = 1/4, and uniforms that force each node's own
+    test to the given pattern."""
+    k = len(parent)
+    pt = np.full(V, 1.0 / V)
+    q = np.full(V, 0.05 / (V - 1))
+    q[1] = 0.95                 # wait: ratio for token 1 = .2/.95
+    rows = [logits_of(pt)] * (k + 1)
+    qr = [q] * (k + 1)
+    toks = [1] * k
+    u = [0.37] + [0.0 if a else 0.9 for a in pattern]
+    return rows, qr, toks, u
+
+
+def longest_path_by_enumeration(parent, pattern):
+    k = len(parent)
+    best, best_depth = 0, 0
+    for i in range(1, k + 1):
+        path = []
+        n = i
+        while n:
+            path.append(n)
+            n = int(parent[n - 1])
+        if all(pattern[p - 1] for p in path) and len(path) > best_depth:
+            best, best_depth = i, len(path)
+    return best, best_depth
+
+
+@pytest.mark.parametrize("parent", [[0, 0, 1, 1, 2], [0, 1, 1, 2, 4], [0, 0, 0, 2, 4]])
+def test_tree_longest_path_brute_force(parent):
+    k = len(parent)
+    for pattern in itertools.product([False, True], repeat=k):
+        rows, qr, toks, u = forced_case(parent, pattern)
+        r = run1(rows, qr, toks, u, O.AcceptParams(), parent=parent)
+        assert r.node_accept[0].tolist() == list(pattern)
+        best, depth = longest_path_by_enumeration(parent, pattern)
+        assert r.accepted_len[0] == depth
+        path = [p for p in r.accepted_path[0] if p > 0]
+        assert (path[-1] if path else 0) == best
+        # the path is a real root-to-node path
+        for a, b in zip([0] + path[:-1], path):
+            assert parent[b - 1] == a
+        # FIRST_ACCEPTED descends greedily by lowest id
+        f = run1(rows, qr, toks, u, O.AcceptParams(tree_mode=O.TREE_FIRST_ACCEPTED), parent=parent)
+        v, want = 0, []
+        while True:
+            nxt = [c for c in range(1, k + 1) if parent[c - 1] == v and pattern[c - 1]]
+            if not nxt:
+                break
+            v = nxt[0]
+            want.append(v)
+        assert [p for p in f.accepted_path[0] if p > 0] == want
+
+
+def test_degenerate_tree_is_the_chain():
+    rng = np.random.default_rng(9)
+    B, k, V = 30, 5, 10
+    lo = rng.standard_normal((B, k + 1, V))
+    q = np.stack([[rand_dist(rng, V) for _ in range(k + 1)] for _ in range(B)])
+    toks = rng.integers(0, V, size=(B, k))
+    u = rng.random((B, k + 1))
+    prm = O.AcceptParams(tau=0.2, lambda1=1.2, lambda2=0.2, lambda3=0.3, top_m=3)
+    c = O.accept(lo, q, toks, None, u, prm)
+    for mode in (O.TREE_LONGEST, O.TREE_FIRST_ACCEPTED):
+        prm.tree_mode = mode
+        t = O.accept(lo, q, toks, list(range(k)), u, prm)
+        assert (t.accepted_len == c.accepted_len).all() and (t.next_token == c.next_token).all()
+        assert (t.accepted_path == c.accepted_path).all()
+    # leading accepts, then stop at the first rejection even if later nodes would pass
+    lead = np.array([int(np.argmin(np.append(c.node_accept[b], False))) for b in range(B)])
+    assert (c.accepted_len == lead).all()
+
+
+def test_tree_extra_token_rule():
+    """Leaf reached -> bonus from that leaf's target row; inner node -> residual against the
+    row of that node, with the relaxation of its lowest-id child."""
+    V = 6
+    rng = np.random.default_rng(4)
+    parent = [0, 0, 1]
+    rows = [logits_of(rand_dist(rng, V)) for _ in range(4)]
+    qr = [rand_dist(rng, V) for _ in range(4)]
+    # drafted tokens whose own test can fail: p/q < 1 in the parent's row
+    pt = [O.softmax_row(r, 1.0) for r in rows]
+    o0 = np.argsort(pt[0] / qr[0])
+    toks = [int(o0[0]), int(o0[1]), int(np.argmin(pt[1] / qr[1]))]
+    assert pt[0][toks[1]] < qr[0][toks[1]]
+    # accept node 2 only (a leaf): bonus from row 2
+    r = run1(rows, qr, toks, [0.61, 0.999999, 0.0, 0.999999], parent=parent)
+    assert r.accepted_path[0].tolist()[:1] == [2] and r.accepted_len[0] == 1
+    want, _ = O.inverse_cdf(O.softmax_row(rows[2], 1.0), 0.61)
+    assert r.next_token[0] == want
+    # accept node 1, reject its child 3: residual of row 1 against q_1
+    r = run1(rows, qr, toks, [0.61, 0.0, 0.999999, 0.999999], parent=parent)
+    assert r.accepted_len[0] == 1 and r.accepted_path[0, 0] == 1
+    res = np.maximum(O.softmax_row(rows[1], 1.0) - qr[1], 0)
+    want, _ = O.inverse_cdf(res, 0.61)
+    assert r.next_token[0] == want
+
+
+def test_synthetic_draft_acceptance_rate_matches_closed_form():
+    """Soft check of the workload recipe: draft logits = target logits + N(0, s^2) over a large
+    flat vocabulary accepts a token with probability about 2*Phi(-s/2)."""
+    rng = np.random.default_rng(0)
+    V, s = 20000, 0.5
+    lo = rng.standard_normal(V) * 1.28
+    pt = O.softmax_row(lo, 1.0)
+    q = O.softmax_row(lo + s * rng.standard_normal(V), 1.0)
+    alpha = np.minimum(pt, q).sum()
+    assert abs(alpha - 2 * stats.norm.cdf(-s / 2)) < 0.01
