@@ -1,0 +1,189 @@
+/*
+ * libdsd -- the verification step of Decentralized Speculative Decoding on one MI355X.
+ *
+ * One node of a decentralized deployment hosts a contiguous block of the target model's
+ * layers (paper section 2.2) and, once per round, scores all k drafted tokens in a single
+ * forward pass (section 2.1).  The last node turns hidden states into logits and runs the
+ * acceptance loop of Algorithm 1 with the key-token rule and the softened target of
+ * section 2.3.  This header is the whole boundary of the library.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every call returns 0 (DSD_OK) or a negative dsd_status; the message of the
+ *     last failure on the calling thread is available from dsd_last_error().  Nothing aborts or
+ *     throws across the boundary.  A call that fails validation launches nothing.
+ *   - "device" pointers are HIP device memory owned by the caller, on the device the context
+ *     was created for; "host" pointers are ordinary host memory.  The library never frees or
+ *     keeps a caller's pointer beyond the call, except where stated.
+ *   - All work is enqueued on the context's HIP stream, in order.  Calls do not synchronise
+ *     unless stated; outputs are valid once the caller has synchronised that stream.
+ *   - Row-major everywhere.  B = sequences, k = drafted rows per sequence (nodes of the draft
+ *     tree, numbered 1..k with parents before children; 0 is the root = committed context),
+ *     d = d_model, V = vocabulary.
+ */
+#ifndef DSD_H
+#define DSD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dsd_ctx dsd_ctx;         /* device, stream, workspace            */
+typedef struct dsd_weights dsd_weights; /* the node's layer block, library-owned */
+typedef struct dsd_kv dsd_kv;           /* the node's KV cache, library-owned    */
+
+enum dsd_status {
+    DSD_OK = 0,
+    DSD_EINVAL = -1,       /* NULL or out-of-range argument                     */
+    DSD_ESHAPE = -2,       /* sizes that do not fit the model / cache / limits  */
+    DSD_ENOMEM = -3,       /* device allocation failed                          */
+    DSD_EHIP = -4,         /* a HIP runtime call failed                         */
+    DSD_EUNSUPPORTED = -5  /* a combination this build has no kernel for        */
+};
+
+enum dsd_dtype { DSD_F32 = 0, DSD_BF16 = 1 };
+enum dsd_tree_mode { DSD_TREE_LONGEST = 0, DSD_TREE_FIRST_ACCEPTED = 1 };
+
+#define DSD_MAX_K 64      /* drafted rows per sequence (tree masks are 64-bit rows) */
+#define DSD_MAX_TOP_M 16  /* support size of NormMatch                             */
+
+/* The node's share of the target model: a block of Llama-style decoder layers (pre-norm
+ * RMSNorm, rotary embedding pairing element i with i + head_dim/2, grouped-query attention,
+ * SwiGLU FFN, no biases), optionally preceded by the token embedding (first node) and
+ * followed by the final RMSNorm + LM head (last node).  The paper names the model families
+ * only (section 3.1). */
+typedef struct dsd_model_desc {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;   /* divides n_q_heads */
+    int32_t head_dim;     /* 64 or 128 */
+    int32_t d_ffn;
+    int32_t vocab;        /* used when has_embed or has_head */
+    int32_t dtype;        /* dsd_dtype of weights, hidden states and KV cache */
+    int32_t has_embed;
+    int32_t has_head;
+    float rope_theta;
+    float rms_eps;
+} dsd_model_desc;
+
+/* Thresholds of the key-token rule and the relaxation of section 2.3.
+ * A drafted token y with parent row p is a key token when any of
+ *     -ln q_p(y) > lambda1 * -ln P_t(y)      (cross-entropy contrast, product form)
+ *     |P_t(y) - q_p(y)| > lambda2
+ *     NormMatch(p) < lambda3                 (share of the top_m ids of P_t found in the top_m ids of q_p)
+ * holds.  Key tokens are verified against P_t, the others against
+ * P~ = P_t^(1-tau) q_p^tau renormalised over the vocabulary.  tau = 0 is the strict rule. */
+typedef struct dsd_accept_params {
+    double lambda1, lambda2, lambda3;
+    double tau;          /* in [0,1] */
+    double temperature;  /* > 0; P_t = softmax(logits / temperature) */
+    int32_t top_m;       /* 1..DSD_MAX_TOP_M */
+    int32_t tree_mode;   /* dsd_tree_mode */
+    const float* tau_override; /* device [B,k] or NULL: tau of node i whatever the key rule says */
+} dsd_accept_params;
+
+/* Optional per-node outputs of dsd_accept (device pointers, each may be NULL). */
+typedef struct dsd_accept_stats {
+    int32_t* key_flags;   /* [B,k] 1 if node i is a key token            */
+    int32_t* node_accept; /* [B,k] 1 if node i passed its own test       */
+    double* ratio;        /* [B,k] P~(y)/q(y) (inf when q(y)=0<P~(y))    */
+    double* norm_match;   /* [B,k] NormMatch of node i's parent row      */
+} dsd_accept_stats;
+
+/* Message of the last failing call on this thread ("" if none).  Never NULL. */
+const char* dsd_last_error(void);
+
+/* Context for HIP device `device`; hip_stream is a hipStream_t (NULL = the default stream).
+ * The context owns a workspace that grows on demand (allocation happens inside the first
+ * call that needs more, which then synchronises).  dsd_destroy frees it. */
+int dsd_create(int device, void* hip_stream, dsd_ctx** out);
+int dsd_destroy(dsd_ctx* ctx);
+int dsd_set_stream(dsd_ctx* ctx, void* hip_stream);
+
+/* Takes the layer block.  `tensors` is a host array of n_tensors device pointers in this order:
+ *   [embed V x d]                                              if has_embed
+ *   per layer: g1[d], Wq[Hq*hd x d], Wk[Hkv*hd x d], Wv[Hkv*hd x d], Wo[d x Hq*hd],
+ *              g2[d], Wg[F x d], Wu[F x d], Wd[d x F]
+ *   [gf[d], Wlm[V x d]]                                        if has_head
+ * every matrix stored [out_features x in_features], all in desc->dtype.  The library copies
+ * (and for bf16 re-tiles) them into buffers of its own and synchronises before returning;
+ * the caller may free its tensors afterwards. */
+int dsd_weights_create(dsd_ctx* ctx, const dsd_model_desc* desc, const void* const* tensors,
+                       int n_tensors, dsd_weights** out);
+int dsd_weights_destroy(dsd_ctx* ctx, dsd_weights* w);
+
+/* KV cache for max_batch sequences of up to max_slots positions (committed + drafted) in
+ * every layer of the block.  Lengths start at 0.  The storage layout is the library's. */
+int dsd_kv_create(dsd_ctx* ctx, const dsd_model_desc* desc, int max_batch, int max_slots, dsd_kv** out);
+int dsd_kv_destroy(dsd_ctx* ctx, dsd_kv* kv);
+
+/* Loads positions [0, n_slots) of one layer from device arrays k, v of shape
+ * [B, Hkv, n_slots, hd] (desc dtype; keys already rotated).  Does not change lengths. */
+int dsd_kv_import(dsd_ctx* ctx, dsd_kv* kv, int layer, const void* k, const void* v, int B, int n_slots);
+/* Reads positions [first_slot, first_slot + n_slots) of one layer back into device arrays of
+ * shape [B, Hkv, n_slots, hd] (desc dtype). */
+int dsd_kv_export(dsd_ctx* ctx, const dsd_kv* kv, int layer, int first_slot, int n_slots, int B,
+                  void* k_out, void* v_out);
+/* Sets / reads the committed length of sequences 0..B-1 (host arrays).  get synchronises. */
+int dsd_kv_set_len(dsd_ctx* ctx, dsd_kv* kv, const int32_t* host_len, int B);
+int dsd_kv_get_len(dsd_ctx* ctx, const dsd_kv* kv, int32_t* host_len, int B);
+
+/* The verification pass of one node over k drafted rows per sequence (section 2.1: one
+ * forward pass over the window; section 2.2: on this node's layer block).
+ *   hidden_in    device [B,k,d] in desc dtype: rows handed over by the previous node;
+ *                NULL on the first node, where rows are the embeddings of draft_tokens
+ *   draft_tokens device int32 [B,k], read only when hidden_in is NULL
+ *   tree_mask    device uint64 [k]: bit s-1 of row t-1 set iff node s is node t or an ancestor
+ *                of node t; NULL = chain (row t sees rows 1..t)
+ *   depth        device int32 [k]: position offset of each row (chain: 0..k-1); NULL = chain
+ *   hidden_out   device [B,k,d] in desc dtype, rows after the last layer of the block
+ *                (before the final norm); may be NULL when logits are requested
+ *   logits       device float [B rows of k x V], sequence b starting at logits + b*logits_seq_stride
+ *                elements (0 = k*V); only when has_head, else must be NULL.  A caller that keeps
+ *                the root row in the same buffer passes logits + V and stride (k+1)*V.
+ * Row t of sequence b sits at position len[b] + depth[t]; its rotated key and its value are
+ * written to cache slot len[b] + t of every layer; it attends to slots [0, len[b]) and to the
+ * drafted rows its mask allows.  Lengths are not advanced: see dsd_kv_commit.
+ * Errors: DSD_ESHAPE if B > max_batch, k > DSD_MAX_K or max(len) + k > max_slots. */
+int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
+                     const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth,
+                     int B, int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
+
+/* Algorithm 1, lines 2-16, for B sequences.
+ *   logits       device float [B,k+1,V]: row 0 follows the committed context, row i follows node i
+ *   draft_probs  device float [B,k+1,V]: row p is the draft distribution the children of node p
+ *                were drawn from (rows of leaves are not read); used as given
+ *   draft_tokens device int32 [B,k]: token of node i
+ *   parent       device int32 [k], values in 0..k with parent[i-1] < i; NULL = chain
+ *   uniforms     device float [B,k+1] in [0,1): u_i decides node i, u_0 draws the extra token
+ * Node i passes when u_i * q(y_i) < P(y_i), P being P_t for key tokens and P~ otherwise (the
+ * min(1, p/q) rule of the speculative sampling work cited in section 2.1).  The accepted path
+ * is the leading run of passes (chain), or per tree_mode the deepest fully passed root-to-node
+ * path (ties to the lower node id) / the greedy descent through lowest-id passing children.
+ * The additional token (Algorithm 1 line 16): if the path's last node has no children it is
+ * drawn from P_t of that node's row; otherwise from the normalised positive part of P - q of
+ * that row, P as used for its lowest-id child (if that is all zero, from P); drawn by inverse
+ * CDF in token-id order with u_0.
+ *   accepted_len  device int32 [B]
+ *   next_token    device int32 [B]
+ *   accepted_path device int32 [B,k] node ids of the path, -1 padded; may be NULL
+ *   stats         optional, may be NULL
+ * All vocabulary-wide reductions run in fp64; no probability row is written to memory. */
+int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+               const int32_t* parent, const float* uniforms, const dsd_accept_params* params,
+               int B, int k, int V, int32_t* accepted_len, int32_t* next_token,
+               int32_t* accepted_path, const dsd_accept_stats* stats);
+
+/* Advances every sequence by its accepted tokens (section 2.1: x_{1:i+k} = x_{1:i} (+) y_{i+1:i+k}):
+ * in every layer the K/V rows that the last dsd_stage_verify wrote for the path's nodes become
+ * slots len[b] .. len[b]+a-1, and len[b] += a.  accepted_len / accepted_path are device arrays
+ * as written by dsd_accept ([B], [B,k]); accepted_path NULL = chain (first a rows, nothing moves). */
+int dsd_kv_commit(dsd_ctx* ctx, dsd_kv* kv, const int32_t* accepted_len, const int32_t* accepted_path,
+                  int B, int k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSD_H */

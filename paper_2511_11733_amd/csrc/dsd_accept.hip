@@ -1,0 +1,505 @@
+// Acceptance loop of Algorithm 1 (lines 2-16) with the key-token rule and the softened target
+// of section 2.3, for B sequences at once.
+//
+// The vocabulary is cut into slices of SLICE ids; every vocabulary-wide quantity is reduced per
+// slice by one workgroup (wavefront shuffles + one LDS hop), the few per-slice partials are
+// merged by a small second kernel, and only those partials ever reach memory: no probability
+// row is materialised.  All arithmetic is fp64 (MI355X runs fp64 vector math at full rate), so
+// the integer outputs follow an fp64 reference except at exact ties.
+//
+//   row_stats   per (sequence, row, slice): max and sum-exp of logits/T, top-M candidates of the
+//               logits row and of the draft row
+//   row_merge   per (sequence, row): log-sum-exp, NormMatch
+//   node_soft   per (sequence, node, slice): key test -> tau_i; partial of
+//               Z~ = sum_v P_t(v)^(1-tau_i) q(v)^tau_i   (skipped when tau_i = 0)
+//   decide      per sequence: every node's test u*q(y) < P(y), accepted path, what to draw from
+//   draw_parts  per (sequence, slice): partial mass of the distribution the extra token comes from
+//   draw_pick   per sequence: inverse CDF in token-id order
+#include "dsd_internal.h"
+
+#define WAVE 64
+#define SLICE 2048
+#define TPB 256
+#define EPT (SLICE / TPB)
+#define MAXM DSD_MAX_TOP_M
+
+typedef unsigned long long u64;
+
+// order-preserving key: larger value first, then lower id
+__device__ inline u64 rank_key(float v, int id) {
+    unsigned u = __float_as_uint(v);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((u64)u << 32) | (u64)(0xFFFFFFFFu - (unsigned)id);
+}
+__device__ inline int key_id(u64 key) { return (int)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull)); }
+
+__device__ inline double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ inline double wave_max_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+__device__ inline u64 wave_max_u(u64 v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        u64 t = __shfl_xor(v, o, WAVE);
+        v = t > v ? t : v;
+    }
+    return v;
+}
+// block reductions over TPB threads; sh has TPB/WAVE entries; result broadcast to all threads
+__device__ inline double block_sum_d(double v, double* sh) {
+    v = wave_sum_d(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sh[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int i = 0; i < TPB / WAVE; ++i) r += sh[i];
+    return r;
+}
+__device__ inline double block_max_d(double v, double* sh) {
+    v = wave_max_d(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sh[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    double r = sh[0];
+#pragma unroll
+    for (int i = 1; i < TPB / WAVE; ++i) r = fmax(r, sh[i]);
+    return r;
+}
+__device__ inline u64 block_max_u(u64 v, u64* sh) {
+    v = wave_max_u(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sh[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    u64 r = sh[0];
+#pragma unroll
+    for (int i = 1; i < TPB / WAVE; ++i) r = sh[i] > r ? sh[i] : r;
+    return r;
+}
+
+// P_t(v)^(1-tau) * q(v)^tau from ln P_t(v) and q(v), with x^0 = 1 for every x
+__device__ inline double soft_weight(double ln_pt, double q, double tau) {
+    const double a = 1.0 - tau;
+    double e = (a == 0.0) ? 0.0 : a * ln_pt;
+    if (tau != 0.0) {
+        if (q <= 0.0) return 0.0;
+        e += tau * log(q);
+    }
+    return exp(e);
+}
+
+struct AcceptWs {
+    double* part_m;     // [B][R][S]
+    double* part_s;     // [B][R][S]
+    u64* part_top_t;    // [B][R][S][MAXM]
+    u64* part_top_q;    // [B][R][S][MAXM]
+    double* row_lse;    // [B][R]
+    double* row_nm;     // [B][R]
+    double* node_tau;   // [B][k]
+    double* node_lnpt;  // [B][k]  ln P_t(y)
+    double* node_q;     // [B][k]  q(y)
+    int32_t* node_key;  // [B][k]
+    double* part_z;     // [B][k][S]
+    int32_t* draw_row;  // [B]
+    int32_t* draw_mode; // [B] 0 = target row (bonus), 1 = positive part of P - q
+    double* draw_tau;   // [B]
+    double* draw_z;     // [B]   Z~ of the softened target used for the draw
+    double* part_res;   // [B][S]
+    double* part_fb;    // [B][S]  mass of P itself (used when the positive part is all zero)
+};
+
+__global__ void __launch_bounds__(TPB)
+row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp, AcceptWs ws, int R, int V, int S,
+                 double inv_temp, int top_m) {
+    __shared__ double shd[TPB / WAVE];
+    __shared__ u64 shu[TPB / WAVE];
+    const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+    const size_t row = ((size_t)b * R + r) * V;
+    const int base = s * SLICE;
+    float lv[EPT], qv[EPT];
+    double mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = base + threadIdx.x + j * TPB;
+        const bool in = i < V;
+        lv[j] = in ? logits[row + i] : -INFINITY;
+        qv[j] = in ? qp[row + i] : -INFINITY;
+        if (in) mx = fmax(mx, (double)lv[j] * inv_temp);
+    }
+    mx = block_max_d(mx, shd);
+    double sum = 0.0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = base + threadIdx.x + j * TPB;
+        if (i < V) sum += exp((double)lv[j] * inv_temp - mx);
+    }
+    sum = block_sum_d(sum, shd);
+    const size_t pidx = ((size_t)b * R + r) * S + s;
+    if (threadIdx.x == 0) {
+        ws.part_m[pidx] = mx;
+        ws.part_s[pidx] = sum;
+    }
+    // top_m candidates of this slice, for the logits row and for the draft row
+    for (int which = 0; which < 2; ++which) {
+        unsigned taken = 0;
+        u64* out = (which == 0 ? ws.part_top_t : ws.part_top_q) + pidx * MAXM;
+        for (int round = 0; round < top_m; ++round) {
+            u64 best = 0;
+            int bj = -1;
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const int i = base + threadIdx.x + j * TPB;
+                if (i < V && !((taken >> j) & 1u)) {
+                    const u64 key = rank_key(which == 0 ? lv[j] : qv[j], i);
+                    if (key > best) {
+                        best = key;
+                        bj = j;
+                    }
+                }
+            }
+            const u64 win = block_max_u(best, shu);
+            if (win == best && bj >= 0) taken |= 1u << bj;   // ids are unique, so one owner
+            if (threadIdx.x == 0) out[round] = win;          // 0 when the slice ran out of ids
+        }
+    }
+}
+
+__global__ void __launch_bounds__(WAVE)
+row_merge_kernel(AcceptWs ws, int R, int S, int top_m) {
+    const int r = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x;
+    const size_t ridx = (size_t)b * R + r;
+    double m = -INFINITY;
+    for (int s = lane; s < S; s += WAVE) m = fmax(m, ws.part_m[ridx * S + s]);
+    m = wave_max_d(m);
+    double sum = 0.0;
+    for (int s = lane; s < S; s += WAVE) sum += ws.part_s[ridx * S + s] * exp(ws.part_m[ridx * S + s] - m);
+    sum = wave_sum_d(sum);
+    // merge the per-slice candidate lists: top_m rounds of a wave-wide maximum
+    int idt[MAXM], idq[MAXM];
+    for (int which = 0; which < 2; ++which) {
+        const u64* cand = (which == 0 ? ws.part_top_t : ws.part_top_q) + ridx * S * MAXM;
+        const int n = S * MAXM;
+        u64 last = ~0ull;           // keys are distinct: select strictly below the previous winner
+        for (int round = 0; round < top_m; ++round) {
+            u64 best = 0;
+            for (int i = lane; i < n; i += WAVE) {
+                if ((i % MAXM) >= top_m) continue;
+                const u64 key = cand[i];
+                if (key < last && key > best) best = key;
+            }
+            best = wave_max_u(best);
+            last = best;
+            (which == 0 ? idt : idq)[round] = key_id(best);
+        }
+    }
+    if (lane == 0) {
+        int common = 0;
+        for (int i = 0; i < top_m; ++i)
+            for (int j = 0; j < top_m; ++j) common += (idt[i] == idq[j]) ? 1 : 0;
+        ws.row_lse[ridx] = m + log(sum);
+        ws.row_nm[ridx] = (double)common / (double)top_m;
+    }
+}
+
+__global__ void __launch_bounds__(TPB)
+node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const int32_t* __restrict__ tokens,
+                 const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params prm, int k, int V, int S,
+                 double inv_temp) {
+    __shared__ double shd[TPB / WAVE];
+    const int s = blockIdx.x, node = blockIdx.y + 1, b = blockIdx.z;
+    const int R = k + 1;
+    int p = parent ? parent[node - 1] : node - 1;
+    p = p < 0 ? 0 : (p > node - 1 ? node - 1 : p);
+    int y = tokens[(size_t)b * k + node - 1];
+    y = y < 0 ? 0 : (y >= V ? V - 1 : y);
+    const size_t row = ((size_t)b * R + p) * V;
+    const double lse = ws.row_lse[(size_t)b * R + p];
+    const double ln_pt = (double)logits[row + y] * inv_temp - lse;
+    const double pt_y = exp(ln_pt);
+    const double q_y = (double)qp[row + y];
+    // key-token rule: any of the three criteria
+    const double h_t = -ln_pt, h_d = -log(q_y);
+    const bool key = (h_d > prm.lambda1 * h_t) || (fabs(pt_y - q_y) > prm.lambda2) ||
+                     (ws.row_nm[(size_t)b * R + p] < prm.lambda3);
+    double tau = key ? 0.0 : prm.tau;
+    if (prm.tau_override) tau = (double)prm.tau_override[(size_t)b * k + node - 1];
+    tau = tau < 0.0 ? 0.0 : (tau > 1.0 ? 1.0 : tau);
+    const size_t nidx = (size_t)b * k + node - 1;
+    if (s == 0 && threadIdx.x == 0) {
+        ws.node_tau[nidx] = tau;
+        ws.node_lnpt[nidx] = ln_pt;
+        ws.node_q[nidx] = q_y;
+        ws.node_key[nidx] = key ? 1 : 0;
+    }
+    if (tau == 0.0) return;     // P~ = P_t, Z~ = 1
+    double z = 0.0;
+    const int base = s * SLICE;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = base + threadIdx.x + j * TPB;
+        if (i < V) z += soft_weight((double)logits[row + i] * inv_temp - lse, (double)qp[row + i], tau);
+    }
+    z = block_sum_d(z, shd);
+    if (threadIdx.x == 0) ws.part_z[nidx * S + s] = z;
+}
+
+__global__ void decide_kernel(const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws,
+                              dsd_accept_params prm, int B, int k, int S, int32_t* __restrict__ accepted_len,
+                              int32_t* __restrict__ accepted_path, dsd_accept_stats st) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;   // one thread per sequence
+    if (b >= B) return;
+    const int R = k + 1;
+    int par[DSD_MAX_K + 1], dep[DSD_MAX_K + 1];
+    bool ok[DSD_MAX_K + 1], acc[DSD_MAX_K + 1];
+    double zt[DSD_MAX_K + 1];
+    par[0] = 0; dep[0] = 0; ok[0] = true; acc[0] = true; zt[0] = 1.0;
+    for (int i = 1; i <= k; ++i) {
+        int p = parent ? parent[i - 1] : i - 1;
+        p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
+        par[i] = p;
+        dep[i] = dep[p] + 1;
+        const size_t nidx = (size_t)b * k + i - 1;
+        const double tau = ws.node_tau[nidx];
+        double z = 1.0;
+        if (tau != 0.0) {
+            z = 0.0;
+            for (int s = 0; s < S; ++s) z += ws.part_z[nidx * S + s];
+        }
+        zt[i] = z;
+        const double q_y = ws.node_q[nidx];
+        const double p_y = soft_weight(ws.node_lnpt[nidx], q_y, tau) / z;
+        const double u = (double)uniforms[(size_t)b * R + i];
+        acc[i] = u * q_y < p_y;
+        ok[i] = acc[i] && ok[p];
+        if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
+        if (st.node_accept) st.node_accept[nidx] = acc[i] ? 1 : 0;
+        if (st.ratio) st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
+        if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
+    }
+    int vstar = 0;
+    if (prm.tree_mode == DSD_TREE_FIRST_ACCEPTED) {
+        for (;;) {
+            int nxt = 0;
+            for (int c = vstar + 1; c <= k; ++c)
+                if (par[c] == vstar && acc[c]) { nxt = c; break; }
+            if (!nxt) break;
+            vstar = nxt;
+        }
+    } else {
+        for (int i = 1; i <= k; ++i)
+            if (ok[i] && dep[i] > dep[vstar]) vstar = i;
+    }
+    const int a = dep[vstar];
+    accepted_len[b] = a;
+    if (accepted_path) {
+        for (int j = 0; j < k; ++j) accepted_path[(size_t)b * k + j] = -1;
+        for (int n = vstar, j = a - 1; n != 0; n = par[n], --j) accepted_path[(size_t)b * k + j] = n;
+    }
+    int child = 0;
+    for (int c = vstar + 1; c <= k; ++c)
+        if (par[c] == vstar) { child = c; break; }
+    ws.draw_row[b] = vstar;
+    if (!child) {
+        ws.draw_mode[b] = 0;
+        ws.draw_tau[b] = 0.0;
+        ws.draw_z[b] = 1.0;
+    } else {
+        ws.draw_mode[b] = 1;
+        ws.draw_tau[b] = ws.node_tau[(size_t)b * k + child - 1];
+        ws.draw_z[b] = zt[child];
+    }
+}
+
+// weight of id i in the distribution the extra token is drawn from; also P itself
+__device__ inline void draw_weight(const float* __restrict__ logits, const float* __restrict__ qp, size_t row, int i,
+                                   double inv_temp, double lse, int mode, double tau, double z, double* w,
+                                   double* p) {
+    const double ln_pt = (double)logits[row + i] * inv_temp - lse;
+    if (mode == 0) {
+        *p = exp(ln_pt);
+        *w = *p;
+    } else {
+        const double q = (double)qp[row + i];
+        *p = soft_weight(ln_pt, q, tau) / z;
+        *w = fmax(*p - q, 0.0);
+    }
+}
+
+__global__ void __launch_bounds__(TPB)
+draw_parts_kernel(const float* __restrict__ logits, const float* __restrict__ qp, AcceptWs ws, int R, int V, int S,
+                  double inv_temp) {
+    __shared__ double shd[TPB / WAVE];
+    const int s = blockIdx.x, b = blockIdx.y;
+    const int r = ws.draw_row[b], mode = ws.draw_mode[b];
+    const double tau = ws.draw_tau[b], z = ws.draw_z[b];
+    const size_t row = ((size_t)b * R + r) * V;
+    const double lse = ws.row_lse[(size_t)b * R + r];
+    double sw = 0.0, sp = 0.0;
+    const int base = s * SLICE;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = base + threadIdx.x + j * TPB;
+        if (i < V) {
+            double w, p;
+            draw_weight(logits, qp, row, i, inv_temp, lse, mode, tau, z, &w, &p);
+            sw += w;
+            sp += p;
+        }
+    }
+    sw = block_sum_d(sw, shd);
+    sp = block_sum_d(sp, shd);
+    if (threadIdx.x == 0) {
+        ws.part_res[(size_t)b * S + s] = sw;
+        ws.part_fb[(size_t)b * S + s] = sp;
+    }
+}
+
+__global__ void __launch_bounds__(TPB)
+draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const float* __restrict__ uniforms,
+                 AcceptWs ws, int R, int V, int S, double inv_temp, int32_t* __restrict__ next_token) {
+    __shared__ double pre[TPB + 1];
+    __shared__ int sh_slice, sh_fallback, sh_best[TPB / WAVE], sh_last[TPB / WAVE];
+    __shared__ double sh_before, sh_target;
+    const int b = blockIdx.x;
+    const int r = ws.draw_row[b], mode = ws.draw_mode[b];
+    const double tau = ws.draw_tau[b], z = ws.draw_z[b];
+    const size_t row = ((size_t)b * R + r) * V;
+    const double lse = ws.row_lse[(size_t)b * R + r];
+    if (threadIdx.x == 0) {
+        const double* part = ws.part_res + (size_t)b * S;
+        double total = 0.0;
+        for (int s = 0; s < S; ++s) total += part[s];
+        int fb = 0;
+        if (!(total > 0.0)) {      // positive part empty: draw from P itself
+            fb = 1;
+            part = ws.part_fb + (size_t)b * S;
+            total = 0.0;
+            for (int s = 0; s < S; ++s) total += part[s];
+        }
+        const double target = (double)uniforms[(size_t)b * R] * total;
+        double cum = 0.0;
+        int pick = -1, last_pos = 0;
+        for (int s = 0; s < S; ++s) {
+            if (part[s] > 0.0) last_pos = s;
+            if (pick < 0 && cum + part[s] > target) {
+                pick = s;
+                sh_before = cum;
+            }
+            cum += part[s];
+        }
+        if (pick < 0) {            // rounding left no crossing: last id with positive weight
+            pick = last_pos;
+            sh_before = -1.0;      // marks "take the last positive id of the slice"
+        }
+        sh_slice = pick;
+        sh_fallback = fb;
+        sh_target = target;
+    }
+    __syncthreads();
+    const int s = sh_slice, fb = sh_fallback;
+    const double target = sh_target, before = sh_before;
+    // thread t owns ids [base + t*EPT, base + (t+1)*EPT), in id order
+    const int base = s * SLICE + threadIdx.x * EPT;
+    double w[EPT], loc = 0.0;
+    int lastpos = -1;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = base + j;
+        w[j] = 0.0;
+        if (i < V) {
+            double ww, pp;
+            draw_weight(logits, qp, row, i, inv_temp, lse, mode, tau, z, &ww, &pp);
+            w[j] = fb ? pp : ww;
+            if (w[j] > 0.0) lastpos = i;
+        }
+        loc += w[j];
+    }
+    pre[threadIdx.x + 1] = loc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        pre[0] = before < 0.0 ? 0.0 : before;
+        for (int t = 1; t <= TPB; ++t) pre[t] += pre[t - 1];
+    }
+    __syncthreads();
+    int found = 0x7FFFFFFF;
+    if (before >= 0.0) {
+        double c = pre[threadIdx.x];
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            c += w[j];
+            if (c > target && base + j < V && found == 0x7FFFFFFF) found = base + j;
+        }
+    }
+    // block minimum of `found`, block maximum of `lastpos`
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        found = min(found, __shfl_xor(found, o, WAVE));
+        lastpos = max(lastpos, __shfl_xor(lastpos, o, WAVE));
+    }
+    if ((threadIdx.x & (WAVE - 1)) == 0) {
+        sh_best[threadIdx.x / WAVE] = found;
+        sh_last[threadIdx.x / WAVE] = lastpos;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int f = 0x7FFFFFFF, l = -1;
+        for (int i = 0; i < TPB / WAVE; ++i) {
+            f = min(f, sh_best[i]);
+            l = max(l, sh_last[i]);
+        }
+        int tok = (f != 0x7FFFFFFF) ? f : l;
+        if (tok < 0) tok = min(V - 1, s * SLICE);
+        next_token[b] = tok;
+    }
+}
+
+int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+                  const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k, int V,
+                  int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path, const dsd_accept_stats* stats) {
+    const int R = k + 1;
+    const int S = (V + SLICE - 1) / SLICE;
+    const size_t BR = (size_t)B * R, BK = (size_t)B * k;
+    size_t need = (BR * S * 2 + BR * 2 + BK * 3 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
+                  BR * S * MAXM * 8 * 2 + (BK + 2 * (size_t)B) * 4 + 32 * 256;
+    DSD_TRY(dsd_ws_reserve(ctx, need));
+    WsBump bump{ctx->ws, 0};
+    AcceptWs ws;
+    ws.part_m = bump.take<double>(BR * S);
+    ws.part_s = bump.take<double>(BR * S);
+    ws.part_top_t = bump.take<u64>(BR * S * MAXM);
+    ws.part_top_q = bump.take<u64>(BR * S * MAXM);
+    ws.row_lse = bump.take<double>(BR);
+    ws.row_nm = bump.take<double>(BR);
+    ws.node_tau = bump.take<double>(BK);
+    ws.node_lnpt = bump.take<double>(BK);
+    ws.node_q = bump.take<double>(BK);
+    ws.node_key = bump.take<int32_t>(BK);
+    ws.part_z = bump.take<double>(BK * S);
+    ws.draw_row = bump.take<int32_t>(B);
+    ws.draw_mode = bump.take<int32_t>(B);
+    ws.draw_tau = bump.take<double>(B);
+    ws.draw_z = bump.take<double>(B);
+    ws.part_res = bump.take<double>((size_t)B * S);
+    ws.part_fb = bump.take<double>((size_t)B * S);
+    if (bump.off > ctx->ws_bytes) DSD_FAIL(DSD_ENOMEM, "accept workspace estimate too small");
+    hipStream_t s = ctx->stream;
+    const double inv_temp = 1.0 / prm->temperature;
+    dsd_accept_stats st = {nullptr, nullptr, nullptr, nullptr};
+    if (stats) st = *stats;
+    if (B > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
+    row_stats_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp, prm->top_m);
+    row_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->top_m);
+    node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, *prm, k, V, S, inv_temp);
+    decide_kernel<<<(B + 63) / 64, 64, 0, s>>>(parent, uniforms, ws, *prm, B, k, S, accepted_len, accepted_path, st);
+    draw_parts_kernel<<<dim3(S, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
+    draw_pick_kernel<<<B, TPB, 0, s>>>(logits, draft_probs, uniforms, ws, R, V, S, inv_temp, next_token);
+    DSD_HIP(hipGetLastError());
+    return DSD_OK;
+}

@@ -1,0 +1,148 @@
+// Internal declarations shared by the translation units of libdsd (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "dsd.h"
+
+// ----------------------------------------------------------------------------- errors
+void dsd_set_error(const char* fmt, ...);
+#define DSD_FAIL(code, ...)          \
+    do {                             \
+        dsd_set_error(__VA_ARGS__);  \
+        return (code);               \
+    } while (0)
+#define DSD_HIP(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) DSD_FAIL(DSD_EHIP, "%s: %s", #expr, hipGetErrorString(e_));  \
+    } while (0)
+#define DSD_TRY(expr)          \
+    do {                       \
+        int rc_ = (expr);      \
+        if (rc_ != DSD_OK) return rc_; \
+    } while (0)
+
+// ----------------------------------------------------------------------------- bf16 bits
+typedef unsigned short bf16_t;  // storage only
+
+__host__ __device__ inline float bf16_to_f32(bf16_t b) {
+    union { unsigned u; float f; } c;
+    c.u = ((unsigned)b) << 16;
+    return c.f;
+}
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {  // round to nearest even
+    union { unsigned u; float f; } c;
+    c.f = f;
+    unsigned u = c.u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ inline float ld_f32(const T* p);
+template <> __device__ inline float ld_f32<float>(const float* p) { return *p; }
+template <> __device__ inline float ld_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ inline void st_f32(T* p, float v);
+template <> __device__ inline void st_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ inline void st_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ----------------------------------------------------------------------------- KV cache layout
+// Per layer, sequence and kv head:
+//   K : [S][hd]                      slot-major, a row is one rotated key
+//   V : [S/64][hd][64]               transposed in blocks of 64 slots, and inside every group of
+//                                    32 slots the slots are stored in the order in which the
+//                                    attention kernel's score tiles hand them to the P*V product
+//                                    (see v_slot_perm), so that a lane's 8 values are contiguous.
+// S (slots per sequence) is a multiple of 64.
+struct KvGeom {
+    int Hkv, hd, S, Bmax;
+    size_t head_elems;   // S * hd
+    size_t layer_elems;  // Bmax * Hkv * S * hd
+};
+__host__ __device__ inline int v_slot_perm(int s64) {
+    int grp = s64 >> 5, kk = s64 & 31;
+    int tile = kk >> 4, r = kk & 15;
+    return (grp << 5) + ((r >> 2) << 3) + (r & 3) + (tile << 2);
+}
+__host__ __device__ inline size_t kv_k_off(const KvGeom& g, int b, int h, int slot, int e) {
+    return ((size_t)(b * g.Hkv + h) * g.S + slot) * g.hd + e;
+}
+__host__ __device__ inline size_t kv_v_off(const KvGeom& g, int b, int h, int slot, int e) {
+    return (size_t)(b * g.Hkv + h) * g.head_elems + (size_t)(slot >> 6) * (g.hd * 64) + (size_t)e * 64 +
+           v_slot_perm(slot & 63);
+}
+
+// ----------------------------------------------------------------------------- handles
+struct dsd_ctx {
+    int device;
+    hipStream_t stream;
+    char* ws;
+    size_t ws_bytes;
+    bool force_simple;  // DSD_PATH=simple: run the generic kernels also for bf16 models
+};
+
+struct LayerW {
+    // plain copies (generic path), in the model dtype
+    void *g1, *wq, *wk, *wv, *wo, *g2, *wg, *wu, *wd;
+    // MFMA-tiled copies (bf16 fast path)
+    void *qkv_t, *wo_t, *gu_t, *wd_t;
+};
+
+struct dsd_weights {
+    dsd_model_desc desc;
+    bool tiled;  // true: *_t members valid (bf16 fast path); false: plain members valid
+    void* embed;
+    void* gf;
+    void* lm;
+    void* lm_t;
+    std::vector<LayerW> layers;
+    std::vector<void*> allocs;
+};
+
+struct dsd_kv {
+    dsd_model_desc desc;
+    KvGeom geom;
+    void* k;           // [L] layers of geom.layer_elems
+    void* v;
+    int32_t* len_dev;  // [Bmax] committed lengths (the truth)
+    std::vector<int32_t> len_bound;  // host upper bounds, used to size grids and validate
+    int last_k;        // rows written by the last dsd_stage_verify
+};
+
+inline size_t dsd_elem_size(int dtype) { return dtype == DSD_BF16 ? 2 : 4; }
+int dsd_ws_reserve(dsd_ctx* ctx, size_t bytes);
+
+// A bump allocator over the context workspace (256-byte aligned pieces).
+struct WsBump {
+    char* base;
+    size_t off;
+    template <typename T> T* take(size_t n) {
+        T* p = (T*)(base + off);
+        off += (n * sizeof(T) + 255) & ~(size_t)255;
+        return p;
+    }
+};
+
+// ----------------------------------------------------------------------------- launchers
+// generic path (dsd_simple.hip)
+int simple_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
+                        const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B,
+                        int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
+// bf16 MFMA path (dsd_stage_bf16.hip)
+int mfma_supported(const dsd_model_desc* d);
+int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors);
+int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
+                      const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B,
+                      int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
+// KV utilities (dsd_kv.hip)
+int kv_import_launch(dsd_ctx* ctx, dsd_kv* kv, int layer, const void* k, const void* v, int B, int n_slots);
+int kv_export_launch(dsd_ctx* ctx, const dsd_kv* kv, int layer, int first, int n, int B, void* k, void* v);
+int kv_commit_launch(dsd_ctx* ctx, dsd_kv* kv, const int32_t* acc_len, const int32_t* acc_path, int B, int k);
+// accept (dsd_accept.hip)
+int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+                  const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k,
+                  int V, int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path,
+                  const dsd_accept_stats* stats);

@@ -1,0 +1,140 @@
+"""GPU parity of dsd_accept against the oracle on synthetic rows: ragged vocabulary sizes that span
+one to many slices, chains and trees, strict / adaptive / forced relaxation, and the degenerate
+cases (everything accepted, first token rejected, zero-mass draft entries)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsd_oracle as O
+from paper_2511_11733_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def make_rows(seed, B, k, V, parent=None, spread=1.28, noise=0.5, zero_frac=0.0):
+    rng = np.random.default_rng(seed)
+    lg = (rng.standard_normal((B, k + 1, V)) * spread).astype(np.float32)
+    dl = lg.astype(np.float64) + noise * rng.standard_normal((B, k + 1, V))
+    q = np.exp(dl - dl.max(-1, keepdims=True))
+    if zero_frac > 0:
+        q[rng.random(q.shape) < zero_frac] = 0.0
+    q = (q / q.sum(-1, keepdims=True)).astype(np.float32)
+    par = list(range(k)) if parent is None else [int(p) for p in parent]
+    toks = np.zeros((B, k), dtype=np.int32)
+    for b in range(B):
+        used = {}
+        for i in range(1, k + 1):
+            p = par[i - 1]
+            qq = q[b, p].astype(np.float64).copy()
+            for t in used.get(p, []):          # siblings are drawn without replacement
+                qq[t] = 0.0
+            t = int(rng.choice(V, p=qq / qq.sum()))
+            used.setdefault(p, []).append(t)
+            toks[b, i - 1] = t
+    u = rng.random((B, k + 1)).astype(np.float32)
+    return lg, q, toks, u
+
+
+def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None):
+    ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm),
+                   None if tau_override is None else tau_override.astype(np.float64))
+    g = H.gpu_accept(ctx, torch.from_numpy(lg).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm,
+                     tau_override)
+    excused, near = H.compare_accept(g, ora, what)
+    fin = np.isfinite(ora.ratio)
+    np.testing.assert_allclose(g["ratio"][fin], ora.ratio[fin], rtol=1e-9, err_msg=what)
+    np.testing.assert_array_equal(g["norm_match"], ora.norm_match, err_msg=what)
+    return ora, g, excused, near
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return H.D.Context(0)
+
+
+@pytest.mark.parametrize("V", [17, 2048, 2049, 5000, 128256])
+def test_chain_strict_and_adaptive(ctx, V):
+    B, k = (6, 5) if V > 10000 else (24, 5)
+    lg, q, toks, u = make_rows(V, B, k, V)
+    ora, g, ex, near = run_case(ctx, lg, q, toks, None, u, dict(tau=0.0), f"strict V={V}")
+    assert 0 < ora.accepted_len.mean() < k
+    # thresholds at the quartiles of this batch, so both branches of the key rule are taken
+    with np.errstate(divide="ignore"):
+        pt = np.stack([[O.softmax_row(lg[b, i], 1.0) for i in range(k + 1)] for b in range(B)])
+    bi, ii = np.meshgrid(np.arange(B), np.arange(k), indexing="ij")
+    pty, qy = pt[bi, ii, toks], q.astype(np.float64)[bi, ii, toks]
+    l1 = float(np.quantile(np.log(qy) / np.log(pty), 0.75))
+    l2 = float(np.quantile(np.abs(pty - qy), 0.75))
+    prm = dict(tau=0.2, lambda1=l1, lambda2=l2, lambda3=0.2, top_m=min(8, V))
+    ora, g, ex, near = run_case(ctx, lg, q, toks, None, u, prm, f"adaptive V={V}")
+    assert 0.1 < ora.key.mean() < 0.9
+    print(f"V={V}: key fraction {ora.key.mean():.2f}, mean accepted {ora.accepted_len.mean():.2f}, near ties {near}, excused {ex}")
+
+
+def test_top_m_limits_and_temperature(ctx):
+    lg, q, toks, u = make_rows(5, 8, 3, 3000)
+    for top_m in (1, 16):
+        run_case(ctx, lg, q, toks, None, u, dict(tau=0.3, lambda3=0.5, top_m=top_m), f"top_m={top_m}")
+    run_case(ctx, lg, q, toks, None, u, dict(tau=0.3, temperature=0.7), "temperature")
+
+
+def test_degenerate_cases(ctx):
+    lg, q, toks, u = make_rows(9, 8, 4, 4100)
+    # everything accepted -> bonus token from the last row
+    u0 = u.copy(); u0[:, 1:] = 0.0
+    ora, *_ = run_case(ctx, lg, q, toks, None, u0, dict(tau=0.0), "all accepted")
+    assert (ora.accepted_len == 4).all()
+    # first token rejected
+    u1 = u.copy(); u1[:, 1] = np.float32(1 - 2 ** -24)
+    q1 = q.copy()
+    for b in range(8):
+        q1[b, 0, toks[b, 0]] = 0.9            # make p/q tiny for the first token
+    ora, *_ = run_case(ctx, lg, q1, toks, None, u1, dict(tau=0.0), "first rejected")
+    assert (ora.accepted_len == 0).all()
+    # tau = 1 accepts everything; draft == target accepts everything
+    ora, *_ = run_case(ctx, lg, q, toks, None, u, dict(tau=1.0), "tau=1")
+    assert (ora.accepted_len == 4).all()
+    qt = np.stack([[O.softmax_row(lg[b, i], 1.0) for i in range(5)] for b in range(8)]).astype(np.float32)
+    run_case(ctx, lg, qt, toks, None, u, dict(tau=0.0), "draft == target (fp32-rounded)")
+    # draft rows with exact zeros (top-k style drafts)
+    lgz, qz, tz, uz = make_rows(10, 8, 4, 3000, zero_frac=0.6)
+    run_case(ctx, lgz, qz, tz, None, uz, dict(tau=0.25), "zero-mass draft entries")
+    # k = 1
+    lg1, q1, t1, u1 = make_rows(11, 16, 1, 777)
+    run_case(ctx, lg1, q1, t1, None, u1, dict(tau=0.0), "k=1")
+
+
+def test_forced_relaxation_per_node(ctx):
+    lg, q, toks, u = make_rows(12, 12, 6, 2500)
+    to = np.random.default_rng(0).choice([0.0, 0.1, 0.5, 1.0], size=(12, 6)).astype(np.float32)
+    run_case(ctx, lg, q, toks, None, u, dict(tau=0.9), "tau_override", tau_override=to)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_trees(ctx, mode):
+    parent = W.ranked_tree_parents()
+    k = len(parent)
+    lg, q, toks, u = make_rows(13, 6, k, 6000, parent=parent)
+    ora, g, ex, near = run_case(ctx, lg, q, toks, parent, u, dict(tau=0.2, lambda3=0.3, tree_mode=mode), f"tree mode {mode}")
+    assert ora.accepted_len.max() >= 2
+    small = [0, 0, 1, 1, 2]
+    lg, q, toks, u = make_rows(14, 40, 5, 300, parent=small)
+    run_case(ctx, lg, q, toks, small, u, dict(tau=0.0, tree_mode=mode), f"small tree mode {mode}")
+
+
+def test_k_max_chain(ctx):
+    lg, q, toks, u = make_rows(15, 2, 64, 1000, noise=0.1)
+    ora, *_ = run_case(ctx, lg, q, toks, None, u, dict(tau=0.3), "k=64")
+    assert ora.accepted_len.max() > 8
+
+
+def test_argument_errors(ctx):
+    t = torch.zeros((1, 2, 10), dtype=torch.float32, device="cuda:0")
+    i = torch.zeros((1, 1), dtype=torch.int32, device="cuda:0")
+    with pytest.raises(H.D.DsdError):
+        H.D.dsd_accept(ctx, t, t, i, None, t, H.D.accept_params(top_m=17), 1, 1, 10, i, i)
+    with pytest.raises(H.D.DsdError):
+        H.D.dsd_accept(ctx, t, t, i, None, t, H.D.accept_params(tau=1.5), 1, 1, 10, i, i)
+    with pytest.raises(H.D.DsdError):
+        H.D.dsd_accept(ctx, t, t, i, None, t, H.D.accept_params(), 1, 65, 10, i, i)
