@@ -1,9 +1,594 @@
-// bf16 MFMA path of the verification pass (placeholder until the kernels land).
+// bf16 path of the verification pass (section 2.1: one forward pass over the k drafted rows, on
+// this node's block of layers, section 2.2), written for gfx950 matrix cores.
+//
+// The pass is bound by streaming the block's weights and the KV cache from HBM once; the k*B
+// activation rows are tiny.  Hence:
+//   * weights are re-tiled once (dsd_weights_create) into the exact operand order of
+//     v_mfma_f32_16x16x32_bf16, so that every wavefront load is one contiguous KiB;
+//   * a GEMM workgroup owns one (or a pair of) 16-column tiles and splits K over its waves,
+//     partial tiles meet in LDS, and the epilogue is fused: RMSNorm scale, rotary embedding +
+//     KV-cache append, SiLU*up, residual add, or fp32 logits;
+//   * RMSNorm never makes a pass of its own: x*g is applied while the A operand is loaded, the
+//     sum of squares is accumulated from those same loads, and 1/rms scales the output rows;
+//   * attention computes S^T = K Q^T so that the scores a lane holds are exactly the P^T operand
+//     of O^T = V^T P^T; V is cached transposed for that product (see KvGeom).
 #include "dsd_internal.h"
 
-int mfma_supported(const dsd_model_desc*) { return 0; }
-int mfma_weights_tile(dsd_ctx*, dsd_weights*, const void* const*) { DSD_FAIL(DSD_EUNSUPPORTED, "bf16 MFMA path not built"); }
-int mfma_stage_verify(dsd_ctx*, const dsd_weights*, dsd_kv*, const void*, const int32_t*, const uint64_t*,
-                      const int32_t*, int, int, void*, float*, int64_t) {
-    DSD_FAIL(DSD_EUNSUPPORTED, "bf16 MFMA path not built");
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+#define WAVE 64
+
+__device__ inline unsigned pack_bf16(float a, float b) {
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+__device__ inline bf16x8 pack8(const float* f) {
+    uint4 u = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
+    return __builtin_bit_cast(bf16x8, u);
+}
+__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    // D[4*(lane/16)+i][lane%16] += sum_k A[lane%16][8*(lane/16)+k] * B[8*(lane/16)+k][lane%16]
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// ============================================================================ weight tiling
+// dst fragment (nt, ks): lane l holds W[nt*16 + l%16][ks*32 + (l/16)*8 .. +8]
+__global__ void tile_weights_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K,
+                                    size_t dst_tile_off) {
+    const int KS = K / 32;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)(N / 16) * KS * 64;
+    if (idx >= total) return;
+    const int l = (int)(idx & 63);
+    const size_t f = idx >> 6;
+    const int ks = (int)(f % KS);
+    const size_t nt = f / KS;
+    const size_t s = (nt * 16 + (l & 15)) * (size_t)K + (size_t)ks * 32 + (l >> 4) * 8;
+    dst[dst_tile_off * KS * 64 + idx] = *(const uint4*)(src + s);
+}
+
+int mfma_supported(const dsd_model_desc* d) {
+    return d->dtype == DSD_BF16 && d->head_dim == 128 && d->d_model % 32 == 0 && d->d_ffn % 32 == 0 &&
+           d->d_model % 16 == 0 && d->d_ffn % 16 == 0 && (!d->has_head || d->vocab % 16 == 0) && !d->has_embed;
+}
+
+static int tile_into(dsd_ctx* ctx, void* dst, size_t dst_tile_off, const void* src, int N, int K) {
+    const size_t total = (size_t)(N / 16) * (K / 32) * 64;
+    tile_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, ctx->stream>>>((uint4*)dst, (const bf16_t*)src, N, K,
+                                                                              dst_tile_off);
+    DSD_HIP(hipGetLastError());
+    return DSD_OK;
+}
+
+static int dev_alloc(dsd_weights* w, size_t bytes, void** out) {
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) DSD_FAIL(DSD_ENOMEM, "weight buffer of %zu bytes", bytes);
+    w->allocs.push_back(p);
+    *out = p;
+    return DSD_OK;
+}
+
+int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors) {
+    const dsd_model_desc& D = w->desc;
+    const int d = D.d_model, qd = D.n_q_heads * D.head_dim, kd = D.n_kv_heads * D.head_dim, F = D.d_ffn;
+    int t = D.has_embed ? 1 : 0;
+    for (int l = 0; l < D.n_layers; ++l) {
+        LayerW& L = w->layers[l];
+        const void* const* T = tensors + t;
+        t += 9;
+        DSD_TRY(dev_alloc(w, (size_t)d * 2, &L.g1));
+        DSD_HIP(hipMemcpyAsync(L.g1, T[0], (size_t)d * 2, hipMemcpyDeviceToDevice, ctx->stream));
+        DSD_TRY(dev_alloc(w, (size_t)d * 2, &L.g2));
+        DSD_HIP(hipMemcpyAsync(L.g2, T[5], (size_t)d * 2, hipMemcpyDeviceToDevice, ctx->stream));
+        DSD_TRY(dev_alloc(w, (size_t)(qd + 2 * kd) * d * 2, &L.qkv_t));
+        DSD_TRY(tile_into(ctx, L.qkv_t, 0, T[1], qd, d));
+        DSD_TRY(tile_into(ctx, L.qkv_t, qd / 16, T[2], kd, d));
+        DSD_TRY(tile_into(ctx, L.qkv_t, (qd + kd) / 16, T[3], kd, d));
+        DSD_TRY(dev_alloc(w, (size_t)d * qd * 2, &L.wo_t));
+        DSD_TRY(tile_into(ctx, L.wo_t, 0, T[4], d, qd));
+        DSD_TRY(dev_alloc(w, (size_t)2 * F * d * 2, &L.gu_t));
+        DSD_TRY(tile_into(ctx, L.gu_t, 0, T[6], F, d));
+        DSD_TRY(tile_into(ctx, L.gu_t, F / 16, T[7], F, d));
+        DSD_TRY(dev_alloc(w, (size_t)d * F * 2, &L.wd_t));
+        DSD_TRY(tile_into(ctx, L.wd_t, 0, T[8], d, F));
+    }
+    if (D.has_head) {
+        DSD_TRY(dev_alloc(w, (size_t)d * 2, &w->gf));
+        DSD_HIP(hipMemcpyAsync(w->gf, tensors[t], (size_t)d * 2, hipMemcpyDeviceToDevice, ctx->stream));
+        DSD_TRY(dev_alloc(w, (size_t)D.vocab * d * 2, &w->lm_t));
+        DSD_TRY(tile_into(ctx, w->lm_t, 0, tensors[t + 1], D.vocab, d));
+    }
+    return DSD_OK;
+}
+
+// ============================================================================ skinny GEMM
+enum { A_F32_GAIN = 0, A_BF16 = 1 };
+enum { EPI_QKV = 0, EPI_SWIGLU = 1, EPI_RESID = 2, EPI_LOGITS = 3 };
+
+struct GemmArgs {
+    const uint4* Wt;      // tiled weights
+    int KS;               // K / 32
+    int M;                // rows in use
+    // A operand
+    const float* x;       // [M][K] fp32 residual stream          (A_F32_GAIN)
+    const bf16_t* gain;   // [K]                                   (A_F32_GAIN)
+    const bf16_t* a;      // [M][K] bf16                           (A_BF16)
+    float eps;
+    // epilogues
+    float* xout;          // EPI_RESID: [M][N] fp32, updated in place
+    int N;
+    bf16_t* hout;         // EPI_SWIGLU: [M][F]
+    int up_tile_off;      // EPI_SWIGLU: F/16
+    float* logits;        // EPI_LOGITS
+    int rows_per_seq;
+    int64_t seq_stride;
+    // EPI_QKV
+    bf16_t* q;            // [M][Hq*hd]
+    bf16_t* kc;           // this layer's K cache
+    bf16_t* vc;           // this layer's V cache
+    KvGeom g;
+    const int32_t* len;
+    const int32_t* depth;
+    int k;
+    int Hq;
+    float theta;
+};
+
+template <int MT, int NT, int AMODE, int EPI, int NW>
+__global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = NW;
+    const int c = lane & 15, g = lane >> 4;
+    int tile[NT];
+    if (EPI == EPI_QKV) {               // column tiles (t, t+4) of one head: the rotary pair
+        tile[0] = (blockIdx.x >> 2) * 8 + (blockIdx.x & 3);
+        if (NT > 1) tile[NT - 1] = tile[0] + 4;
+    } else if (EPI == EPI_SWIGLU) {     // gate tile and the matching up tile
+        tile[0] = blockIdx.x;
+        if (NT > 1) tile[NT - 1] = blockIdx.x + p.up_tile_off;
+    } else {
+        for (int i = 0; i < NT; ++i) tile[i] = blockIdx.x * NT + i;
+    }
+    const int K = p.KS * 32;
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float ssq[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
+
+    const uint4* wt[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wt[nt] = p.Wt + (size_t)tile[nt] * p.KS * 64 + lane;
+
+#pragma unroll 4
+    for (int ks = wave; ks < p.KS; ks += nw) {
+        bf16x8 bfrag[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bfrag[nt] = __builtin_bit_cast(bf16x8, wt[nt][(size_t)ks * 64]);
+        const int kb = ks * 32 + g * 8;
+        bf16x8 afrag[MT];
+        if (AMODE == A_F32_GAIN) {
+            const uint4 gu = *(const uint4*)(p.gain + kb);
+            float gf[8];
+            const unsigned gw[4] = {gu.x, gu.y, gu.z, gu.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                gf[2 * i] = __uint_as_float(gw[i] << 16);
+                gf[2 * i + 1] = __uint_as_float(gw[i] & 0xFFFF0000u);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int row = mt * 16 + c;
+                float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (row < p.M) {
+                    const float4 v0 = *(const float4*)(p.x + (size_t)row * K + kb);
+                    const float4 v1 = *(const float4*)(p.x + (size_t)row * K + kb + 4);
+                    v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+                    v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    ssq[mt] += v[i] * v[i];
+                    v[i] *= gf[i];
+                }
+                afrag[mt] = pack8(v);
+            }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int row = mt * 16 + c;
+                uint4 u = {0u, 0u, 0u, 0u};
+                if (row < p.M) u = *(const uint4*)(p.a + (size_t)row * K + kb);
+                afrag[mt] = __builtin_bit_cast(bf16x8, u);
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16(afrag[mt], bfrag[nt], acc[mt][nt]);
+    }
+
+    // partial tiles (and partial sums of squares) of all waves meet in LDS
+    f32x4* red = (f32x4*)lds;                              // [nw][MT][NT][64]
+    float* ssr = lds + (size_t)nw * MT * NT * 64 * 4;      // [nw][MT][16]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) red[((wave * MT + mt) * NT + nt) * 64 + lane] = acc[mt][nt];
+        if (AMODE == A_F32_GAIN) {
+            float s = ssq[mt];
+            s += __shfl_xor(s, 16, WAVE);
+            s += __shfl_xor(s, 32, WAVE);
+            if (lane < 16) ssr[(wave * MT + mt) * 16 + lane] = s;
+        }
+    }
+    __syncthreads();
+
+    for (int mt = wave; mt < MT; mt += nw) {
+        f32x4 o[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            o[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int w = 0; w < nw; ++w) o[nt] += red[((w * MT + mt) * NT + nt) * 64 + lane];
+        }
+        float rstd[4] = {1.f, 1.f, 1.f, 1.f};
+        if (AMODE == A_F32_GAIN) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float s = 0.f;
+                for (int w = 0; w < nw; ++w) s += ssr[(w * MT + mt) * 16 + g * 4 + i];
+                rstd[i] = 1.0f / sqrtf(s / (float)K + p.eps);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = mt * 16 + g * 4 + i;      // output row of element i
+            if (m >= p.M) continue;
+            if (EPI == EPI_RESID) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    float* dst = p.xout + (size_t)m * p.N + tile[nt] * 16 + c;
+                    *dst += o[nt][i];
+                }
+            } else if (EPI == EPI_LOGITS) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    p.logits[(size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N +
+                             tile[nt] * 16 + c] = o[nt][i] * rstd[i];
+            } else if (EPI == EPI_SWIGLU) {
+                const float gate = o[0][i] * rstd[i], up = o[NT - 1][i] * rstd[i];
+                const float h = gate / (1.0f + __expf(-gate)) * up;
+                p.hout[(size_t)m * p.N + tile[0] * 16 + c] = f32_to_bf16(h);
+            } else {  // EPI_QKV
+                const int hd = 128, half = 64;
+                const int head = tile[0] >> 3;                 // 8 column tiles per head
+                const int e = (tile[0] & 7) * 16 + c;          // < 64: first element of the rotary pair
+                const float lo = o[0][i] * rstd[i], hi = o[NT - 1][i] * rstd[i];
+                const int b = m / p.k, t = m % p.k;
+                const int L = p.len[b];
+                const int slot = L + t;
+                if (head < p.Hq + p.g.Hkv) {
+                    const double pos = (double)(L + (p.depth ? p.depth[t] : t));
+                    const double inv = pow((double)p.theta, -2.0 * (double)e / (double)hd);
+                    double sn, cs;
+                    sincos(pos * inv, &sn, &cs);
+                    const float r0 = lo * (float)cs - hi * (float)sn;
+                    const float r1 = hi * (float)cs + lo * (float)sn;
+                    if (head < p.Hq) {
+                        bf16_t* dst = p.q + ((size_t)m * p.Hq + head) * hd;
+                        dst[e] = f32_to_bf16(r0);
+                        dst[e + half] = f32_to_bf16(r1);
+                    } else if (slot < p.g.S) {
+                        const int hk = head - p.Hq;
+                        p.kc[kv_k_off(p.g, b, hk, slot, e)] = f32_to_bf16(r0);
+                        p.kc[kv_k_off(p.g, b, hk, slot, e + half)] = f32_to_bf16(r1);
+                    }
+                } else if (slot < p.g.S) {
+                    const int hk = head - p.Hq - p.g.Hkv;
+                    p.vc[kv_v_off(p.g, b, hk, slot, e)] = f32_to_bf16(lo);
+                    p.vc[kv_v_off(p.g, b, hk, slot, e + half)] = f32_to_bf16(hi);
+                }
+            }
+        }
+    }
+}
+
+template <int MT, int NT, int AMODE, int EPI, int NW>
+static int launch_gemm(hipStream_t s, const GemmArgs& p, int n_blocks) {
+    const int nw = NW;
+    const size_t lds = (size_t)nw * MT * NT * 64 * 16 + (size_t)nw * MT * 16 * 4;
+    auto kern = gemm_skinny_kernel<MT, NT, AMODE, EPI, NW>;
+    if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    kern<<<n_blocks, nw * 64, lds, s>>>(p);
+    return DSD_OK;
+}
+
+template <int NT, int AMODE, int EPI>
+static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
+    const int mt = (p.M + 15) / 16;
+    switch (mt) {
+        case 1: return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
+        case 2: return launch_gemm<2, NT, AMODE, EPI, 16>(s, p, n_blocks);
+        case 3: return launch_gemm<3, NT, AMODE, EPI, 8>(s, p, n_blocks);
+        case 4: return launch_gemm<4, NT, AMODE, EPI, 8>(s, p, n_blocks);
+        case 5: case 6: return launch_gemm<6, NT, AMODE, EPI, 4>(s, p, n_blocks);
+        case 7: case 8: return launch_gemm<8, NT, AMODE, EPI, 4>(s, p, n_blocks);
+        default: DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: B*k = %d rows exceed 128", p.M);
+    }
+}
+
+// ============================================================================ attention
+// One wavefront owns a run of keys of one (sequence, kv head) and all its k*G query rows
+// (row r = t*G + head-in-group).  Partial (max, sum, O) per run go to scratch; attn_combine
+// merges the runs.
+struct AttnArgs {
+    const bf16_t* q;       // [M][Hq*hd]
+    const bf16_t* kc;
+    const bf16_t* vc;
+    KvGeom g;
+    const int32_t* len;
+    const uint64_t* mask;
+    int k, Hq, G;
+    int keys_per_wave;     // multiple of 32
+    int n_runs;            // runs per (sequence, kv head)
+    float* part_o;         // [B][Hkv][n_runs][rows_pad][128]
+    float* part_ml;        // [B][Hkv][n_runs][rows_pad][2]
+    int rows_pad;          // RT*16
+    float scale_log2e;
+};
+
+template <int RT>
+__global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int run = blockIdx.x * 4 + wave, hk = blockIdx.y, b = blockIdx.z;
+    if (run >= p.n_runs) return;
+    const int L = p.len[b];
+    const int nkeys = min(L + p.k, p.g.S);
+    const int rows = p.k * p.G;
+    const int j_begin = run * p.keys_per_wave;
+    const int j_end = min(j_begin + p.keys_per_wave, nkeys);
+    const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad;
+
+    // Q^T fragments: lane (row c of tile rt, k-group g) holds q[row][32j + 8g .. +8]
+    bf16x8 qf[RT][4];
+    uint64_t vis[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int r = rt * 16 + c;
+        const int t = r / p.G, hq = hk * p.G + r % p.G;
+        vis[rt] = 0;
+        if (r < rows) vis[rt] = p.mask ? p.mask[t] : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1ull));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint4 u = {0u, 0u, 0u, 0u};
+            if (r < rows) u = *(const uint4*)(p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8);
+            qf[rt][j] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+    f32x4 o[8][RT];
+#pragma unroll
+    for (int h = 0; h < 8; ++h)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) o[h][rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float mrow[RT], lrow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        mrow[rt] = -INFINITY;
+        lrow[rt] = 0.f;
+    }
+    const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
+    const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
+
+    for (int j0 = j_begin; j0 < j_end; j0 += 32) {
+        // S^T tiles: keys on the M side.  Lane (key c, group g) of tile tl holds K[j0+16*tl+c][32j+8g..]
+        f32x4 s[2][RT];
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl) {
+            bf16x8 kf[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                kf[j] = __builtin_bit_cast(bf16x8, *(const uint4*)(kbase + (size_t)(j0 + tl * 16 + c) * 128 + j * 32 + g * 8));
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a = mfma16(kf[j], qf[rt][j], a);
+                s[tl][rt] = a;
+            }
+        }
+        // V^T fragments: lane (feature 16*h + c, group g) holds 8 slots in the order the scores
+        // above are held: tile 0 keys 4g..4g+3, tile 1 keys 4g..4g+3
+        bf16x8 vf[8];
+        const bf16_t* vblk = vbase + (size_t)(j0 >> 6) * (128 * 64) + (j0 & 32) + g * 8;
+#pragma unroll
+        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, *(const uint4*)(vblk + (size_t)(h * 16 + c) * 64));
+
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            // mask + running maximum (lane c = query row; its 8 scores are keys 16*tl + 4g + i)
+            float mx = -INFINITY;
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int key = j0 + tl * 16 + g * 4 + i;
+                    bool ok = key < L;
+                    if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
+                    const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
+                    s[tl][rt][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+            const float mnew = fmaxf(mrow[rt], mx);
+            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            const float alpha = exp2f(mrow[rt] - muse);      // 0 when mrow was -inf
+            mrow[rt] = mnew;
+            float pv[8];
+            float ps = 0.f;
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float e = exp2f(s[tl][rt][i] - muse);
+                    pv[tl * 4 + i] = e;
+                    ps += e;
+                }
+            lrow[rt] = lrow[rt] * alpha + ps;
+            const bf16x8 pf = pack8(pv);
+#pragma unroll
+            for (int h = 0; h < 8; ++h) {
+                o[h][rt] *= alpha;
+                o[h][rt] = mfma16(vf[h], pf, o[h][rt]);
+            }
+        }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float l = lrow[rt];
+        l += __shfl_xor(l, 16, WAVE);
+        l += __shfl_xor(l, 32, WAVE);
+        const int r = rt * 16 + c;
+        if (g == 0) {
+            p.part_ml[(unit + r) * 2] = mrow[rt];
+            p.part_ml[(unit + r) * 2 + 1] = l;
+        }
+        // O^T tile h: lane holds features 16h + 4g + i of row c
+#pragma unroll
+        for (int h = 0; h < 8; ++h) *(f32x4*)(p.part_o + (unit + r) * 128 + h * 16 + g * 4) = o[h][rt];
+    }
+}
+
+// out[m][hq*128 + e] = sum_runs 2^(m_run - M) O_run[e] / sum_runs 2^(m_run - M) l_run
+__global__ void attn_combine_kernel(bf16_t* __restrict__ out, const float* __restrict__ part_o,
+                                    const float* __restrict__ part_ml, int n_runs, int rows_pad, int k, int G, int Hq,
+                                    int Hkv) {
+    const int r = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int e = threadIdx.x;   // 128 threads
+    const size_t u0 = (size_t)(b * Hkv + hk) * n_runs;
+    float M = -INFINITY;
+    for (int s = 0; s < n_runs; ++s) M = fmaxf(M, part_ml[((u0 + s) * rows_pad + r) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < n_runs; ++s) {
+        const size_t idx = (u0 + s) * rows_pad + r;
+        const float m = part_ml[idx * 2];
+        if (m == -INFINITY) continue;
+        const float w = exp2f(m - M);
+        den += w * part_ml[idx * 2 + 1];
+        num += w * part_o[idx * 128 + e];
+    }
+    const int t = r / G, hq = hk * G + r % G;
+    out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = f32_to_bf16(num / den);
+}
+
+// ============================================================================ small kernels
+__global__ void rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__ h, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = bf16_to_f32(h[i]);
+}
+__global__ void rows_out_kernel(bf16_t* __restrict__ h, const float* __restrict__ x, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) h[i] = f32_to_bf16(x[i]);
+}
+
+// ============================================================================ orchestration
+int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
+                      const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B, int k,
+                      void* hidden_out, float* logits, int64_t logits_seq_stride) {
+    (void)draft_tokens;
+    const dsd_model_desc& D = w->desc;
+    const KvGeom& g = kv->geom;
+    const int M = B * k, d = D.d_model, Hq = D.n_q_heads, Hkv = D.n_kv_heads, hd = D.head_dim, F = D.d_ffn;
+    const int G = Hq / Hkv, qd = Hq * hd;
+    if (M > 128) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: B*k = %d rows exceed 128", M);
+    if (!hidden_in) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: first-node (embedding) blocks run on the generic path");
+    const int rows = k * G;
+    int RT = (rows + 15) / 16;      // row tiles, rounded up to a size the kernel is built for
+    if (RT == 5) RT = 6;
+    if (RT == 7) RT = 8;
+    if (RT > 8) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 128", rows);
+
+    int max_len = 0;
+    for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
+    const int max_keys = std::min(max_len + k, g.S);
+    // runs of keys per wave: aim at about 8 waves per CU over the whole grid
+    const long units = (long)B * Hkv;
+    long kpw = ((long)max_keys * units + 2047) / 2048;
+    kpw = std::max(64L, (kpw + 31) / 32 * 32);
+    const int keys_per_wave = (int)kpw;
+    const int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
+    const int rows_pad = RT * 16;
+
+    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 2 * 2 + (size_t)M * F * 2 +
+                  (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
+    DSD_TRY(dsd_ws_reserve(ctx, need));
+    WsBump ws{ctx->ws, 0};
+    float* x = ws.take<float>((size_t)M * d);
+    bf16_t* q = ws.take<bf16_t>((size_t)M * qd);
+    bf16_t* att = ws.take<bf16_t>((size_t)M * qd);
+    bf16_t* h = ws.take<bf16_t>((size_t)M * F);
+    float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
+    float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
+    hipStream_t s = ctx->stream;
+
+    const size_t nx = (size_t)M * d;
+    rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
+
+    for (int l = 0; l < D.n_layers; ++l) {
+        const LayerW& W = w->layers[l];
+        bf16_t* kc = (bf16_t*)kv->k + (size_t)l * g.layer_elems;
+        bf16_t* vc = (bf16_t*)kv->v + (size_t)l * g.layer_elems;
+        GemmArgs a = GemmArgs();
+        a.M = M;
+        a.eps = D.rms_eps;
+        // q, k, v = rmsnorm(x; g1) Wqkv^T, rotary, cache append
+        a.Wt = (const uint4*)W.qkv_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)W.g1;
+        a.q = q; a.kc = kc; a.vc = vc; a.g = g; a.len = kv->len_dev; a.depth = depth; a.k = k; a.Hq = Hq;
+        a.theta = D.rope_theta;
+        DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
+        // attention
+        AttnArgs t;
+        t.q = q; t.kc = kc; t.vc = vc; t.g = g; t.len = kv->len_dev; t.mask = tree_mask; t.k = k; t.Hq = Hq; t.G = G;
+        t.keys_per_wave = keys_per_wave; t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
+        t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
+        dim3 ag((n_runs + 3) / 4, Hkv, B);
+        switch (RT) {
+            case 1: attn_partial_kernel<1><<<ag, 256, 0, s>>>(t); break;
+            case 2: attn_partial_kernel<2><<<ag, 256, 0, s>>>(t); break;
+            case 3: attn_partial_kernel<3><<<ag, 256, 0, s>>>(t); break;
+            case 4: attn_partial_kernel<4><<<ag, 256, 0, s>>>(t); break;
+            case 6: attn_partial_kernel<6><<<ag, 256, 0, s>>>(t); break;
+            default: attn_partial_kernel<8><<<ag, 256, 0, s>>>(t); break;
+        }
+        attn_combine_kernel<<<dim3(rows, Hkv, B), 128, 0, s>>>(att, part_o, part_ml, n_runs, t.rows_pad, k, G, Hq, Hkv);
+        // x += attn Wo^T
+        a = GemmArgs();
+        a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
+        DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+        // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
+        a = GemmArgs();
+        a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)W.gu_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)W.g2;
+        a.hout = h; a.N = F; a.up_tile_off = F / 16;
+        DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
+        // x += h Wd^T
+        a = GemmArgs();
+        a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
+        DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+    }
+    if (hidden_out) rows_out_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>((bf16_t*)hidden_out, x, nx);
+    if (logits) {
+        GemmArgs a = GemmArgs();
+        a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)w->lm_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)w->gf;
+        a.logits = logits; a.N = D.vocab; a.rows_per_seq = k; a.seq_stride = logits_seq_stride;
+        DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
+    }
+    DSD_HIP(hipGetLastError());
+    return DSD_OK;
 }

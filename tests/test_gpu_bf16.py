@@ -1,0 +1,108 @@
+"""GPU parity of the bf16 verification pass against the fp64 oracle on reduced copies of the
+benchmark workloads: same generators and value distributions, sizes the oracle finishes in
+seconds, several tiles plus ragged tails in every dimension that is tiled (rows, context,
+vocabulary), unequal context lengths, chain and tree masks."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsd_oracle as O
+from paper_2511_11733_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def mini(name, B, k, lens, tree=None, head=False, L=2, d=512, Hq=8, Hkv=2, F=1536, V=8000, seed=3):
+    base = W.CONFIGS["c3" if head else "c2"]
+    cfg = W.scaled(base, name=name, B=B, k=k, C=max(lens), seed=seed, L=L, d=d, Hq=Hq, Hkv=Hkv, F=F,
+                   V=V if head else 0, has_head=head)
+    m = cfg.model
+    w = W.make_weights(m, cfg.seed)
+    K, Vv = W.make_kv(cfg)
+    hid = W.make_hidden(cfg)
+    parent = None
+    if tree is not None:
+        parent = W.ranked_tree_parents(*tree)
+        assert len(parent) == k
+    return cfg, m, w, K, Vv, hid, parent, list(lens)
+
+
+def check(case, simple=False):
+    cfg, m, w, K, V, hid, parent, lens = case
+    ref = O.stage_forward(m, w.__getitem__, K, V, lens, hid, None, parent=parent)
+    if simple:
+        os.environ["DSD_PATH"] = "simple"
+    try:
+        st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
+    finally:
+        os.environ.pop("DSD_PATH", None)
+    st.import_kv(K, V, lens)
+    out, lg = st.verify(hidden=hid, parent=parent)
+    tol = H.TOL["bf16"]
+    nrms, worst = H.assert_close(H.to_np64(out), ref.hidden, tol, f"{cfg.name} hidden")
+    print(f"{cfg.name}: hidden normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}")
+    if m.has_head:
+        nrms, worst = H.assert_close(H.to_np64(lg), ref.logits, tol, f"{cfg.name} logits")
+        print(f"{cfg.name}: logits normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}")
+    for l in range(m.L):
+        for b in range(cfg.B):
+            gk, gv = st.new_rows(l, lens[b], cfg.k, cfg.B)
+            H.assert_close(gk[b], ref.new_k[l, b], tol, f"{cfg.name} appended K layer {l} seq {b}")
+            H.assert_close(gv[b], ref.new_v[l, b], tol, f"{cfg.name} appended V layer {l} seq {b}")
+    # the committed part of the cache is untouched
+    gk, gv = st.new_rows(0, 0, min(lens), cfg.B)
+    np.testing.assert_array_equal(gk, O.widen(K[0][:, :, :min(lens)]))
+    np.testing.assert_array_equal(gv, O.widen(V[0][:, :, :min(lens)]))
+    return st, ref
+
+
+def test_mid_stage_chain_ragged_lengths():
+    check(mini("mini_mid", B=3, k=5, lens=[300, 77, 130]))
+
+
+def test_mid_stage_chain_generic_kernels():
+    check(mini("mini_mid_generic", B=3, k=5, lens=[300, 77, 130]), simple=True)
+
+
+def test_final_stage_tree():
+    check(mini("mini_tree", B=2, k=10, lens=[129, 64], tree=((3, 2, 2), 10), head=True))
+
+
+def test_more_rows_four_row_tiles():
+    check(mini("mini_m64", B=8, k=8, lens=[200, 31, 64, 65, 1, 255, 256, 100], head=True, V=4112))
+
+
+def test_max_rows_tree_32_nodes():
+    check(mini("mini_m128", B=4, k=32, lens=[150, 90, 33, 64], tree=((4, 3, 2, 2, 1, 1), 32), head=True, L=1))
+
+
+def test_empty_context():
+    check(mini("mini_empty", B=2, k=6, lens=[0, 0]))
+
+
+def test_k1_plain_decode_step():
+    check(mini("mini_k1", B=5, k=1, lens=[40, 41, 63, 64, 65]))
+
+
+def test_wide_gqa_group_70b_like():
+    # 8 query heads per kv head as in the 70B-shaped workload: 6*8 = 48 query rows per kv head
+    check(mini("mini_70b", B=2, k=6, lens=[140, 200], Hq=16, Hkv=2, d=1024, F=2048))
+
+
+def test_shape_errors():
+    case = mini("mini_err", B=2, k=4, lens=[10, 10])
+    cfg, m, w, K, V, hid, parent, lens = case
+    st = H.GpuStage(m, w, 2, 16)
+    st.import_kv(K, V, lens)
+    with pytest.raises(H.D.DsdError):            # 13 + 4 rows exceed 16 slots
+        st.kv.set_len([13, 10])
+        st.verify(hidden=hid)
+    st.kv.set_len(lens)
+    with pytest.raises(H.D.DsdError):            # logits from a block without head
+        lg = torch.zeros((2, 4, 8), dtype=torch.float32, device="cuda:0")
+        H.D.dsd_stage_verify(st.ctx, st.w, st.kv, st._cast(hid), None, None, None, 2, 4, None, lg)
+    with pytest.raises(H.D.DsdError):            # batch larger than the cache
+        H.D.dsd_stage_verify(st.ctx, st.w, st.kv, st._cast(hid), None, None, None, 3, 4, st._cast(hid), None)
