@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSD verify step on one MI355X.
+
+A step is one pass of the whole hot path of the named workload: `dsd_stage_verify` over the
+k drafted rows of every sequence (plus `dsd_accept` on final-stage workloads), inputs already
+resident in HBM.  The default workload is the Llama-3-8B-shaped middle stage (8 of 32 layers,
+batch 1, context 2048, k = 5 chain draft, bf16), the configuration the headline metric is
+quoted on.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(cfg):
+    """HBM bytes one step has to move: every weight of the block once, every cached K/V element
+    once, the appended K/V rows, hidden states in and out, fp32 logits out (final stage)."""
+    m = cfg.model
+    es = 2 if m.dtype == "bf16" else 4
+    qd, kd = m.Hq * m.hd, m.Hkv * m.hd
+    per_layer = {
+        "qkv": (qd + 2 * kd) * m.d * es + m.d * es,
+        "oproj": m.d * qd * es,
+        "gateup": 2 * m.F * m.d * es + m.d * es,
+        "down": m.d * m.F * es,
+        "attn": 2 * cfg.B * kd * cfg.C * es,
+    }
+    M = cfg.B * cfg.k
+    total = m.L * sum(per_layer.values())
+    total += m.L * 2 * M * kd * es            # appended K/V rows
+    total += 2 * M * m.d * es                 # hidden in + out
+    head = 0
+    if m.has_head:
+        head = m.V * m.d * es + m.d * es + M * m.V * 4
+        total += head
+    accept = 2 * cfg.B * (cfg.k + 1) * m.V * 4 if m.has_head else 0
+    return total, per_layer, head, accept
+
+
+def cpu_baseline(cfg, weights, K, V, hid, parent, sample_layers):
+    """The oracle, as it stands, on the host cores, on a bounded sample of the same workload: the
+    first `sample_layers` layers of the block for all B*k rows; scaled to tokens/s of a full step."""
+    from threadpoolctl import threadpool_info
+
+    from oracle import dsd_oracle as O
+    from paper_2511_11733_amd import workloads as W
+
+    sample_layers = sample_layers or cfg.model.L
+    m = W.scaled(cfg, L=sample_layers, has_head=False, V=0).model
+    reps, dt = 0, 0.0
+    while reps < 3 and dt < 10.0:          # about 10-30 s of CPU work
+        t0 = time.perf_counter()
+        O.stage_forward(m, weights.__getitem__, K[:sample_layers], V[:sample_layers], [cfg.C] * cfg.B, hid, None,
+                        parent=parent)
+        dt += time.perf_counter() - t0
+        reps += 1
+    full = dt / reps * cfg.model.L / sample_layers
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": cfg.B * cfg.k / full, "unit": "tok/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{sample_layers} of {cfg.model.L} layers of the same step (all {cfg.B * cfg.k} rows, context "
+                      f"{cfg.C}), {reps} repetition(s), {dt:.1f} s measured, scaled by layers; numpy fp64 with multithreaded BLAS matmuls",
+            "seconds_measured": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c2", help="workload: c2 (default), c3, c4, c5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=0, help="0 = all layers of the block")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the verify step of ONE node); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2511_11733_amd import dsd as D
+    from paper_2511_11733_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    m = cfg.model
+    assert m.dtype == "bf16", "bench workloads are the bf16 configurations"
+    dev = "cuda:0"
+
+    t_gen = time.perf_counter()
+    weights = W.make_weights(m, cfg.seed, threads=16)
+    K, V = W.make_kv(cfg, threads=16)
+    hid = W.make_hidden(cfg)
+    parent = W.ranked_tree_parents() if cfg.tree else None
+    t_gen = time.perf_counter() - t_gen
+
+    def dev_bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    stream = torch.cuda.Stream()
+    ctx = D.Context(0, stream)
+    desc = D.model_desc(m)
+    tens = [dev_bf16(weights[name]) for name, _, _ in W.weight_specs(m)]
+    w = D.Weights(ctx, desc, tens)
+    del tens
+    torch.cuda.empty_cache()
+    kv = D.KVCache(ctx, desc, cfg.B, cfg.C + cfg.k)
+    for l in range(m.L):
+        kv.import_layer(l, dev_bf16(K[l]), dev_bf16(V[l]))
+    kv.set_len([cfg.C] * cfg.B)
+    h_in = dev_bf16(hid)
+    h_out = torch.empty_like(h_in)
+    B, k = cfg.B, cfg.k
+    mask = depth = par_dev = None
+    if parent is not None:
+        mask = torch.from_numpy(W.tree_mask_bits(parent).view(np.int64)).to(dev)
+        depth = torch.from_numpy(W.tree_depths(parent)).to(dev)
+        par_dev = torch.from_numpy(parent).to(dev)
+    logits = probs = toks = unif = alen = nxt = path = prm = None
+    if m.has_head:
+        # [B, k+1, V]: row 0 is the root row (produced once, untimed, by a 1-row pass on a pending
+        # row), rows 1..k are written by the timed k-row pass
+        logits = torch.zeros((B, k + 1, m.V), dtype=torch.float32, device=dev)
+        alen = torch.zeros(B, dtype=torch.int32, device=dev)
+        nxt = torch.zeros(B, dtype=torch.int32, device=dev)
+        path = torch.zeros((B, k), dtype=torch.int32, device=dev)
+        prm = D.accept_params(lambda1=1.05, lambda2=2e-5, lambda3=0.3, tau=cfg.tau, top_m=cfg.top_m)
+
+    def stage():
+        D.dsd_stage_verify(ctx, w, kv, h_in, None, mask, depth, B, k, h_out, logits,
+                           (k + 1) * m.V if m.has_head else 0, m.V if m.has_head else 0)
+
+    def step():
+        stage()
+        if m.has_head:
+            D.dsd_accept(ctx, logits, probs, toks, par_dev, unif, prm, B, k, m.V, alen, nxt, path)
+
+    with torch.cuda.stream(stream):
+        if m.has_head:
+            stage()
+            stream.synchronize()
+            logits[:, 0] = logits[:, 1]          # stand-in root row (timing only)
+            noise = torch.from_numpy(W.make_draft_noise(cfg, k + 1, m.V)).to(dev)
+            probs = torch.softmax(logits + noise, dim=-1).contiguous()
+            del noise
+            par_list = list(range(k)) if parent is None else [int(p) for p in parent]
+            toks = torch.stack([torch.multinomial(probs[:, par_list[i]], 1)[:, 0] for i in range(k)], dim=1).to(torch.int32).contiguous()
+            unif = torch.from_numpy(W.make_uniforms(cfg, k + 1)).to(dev)
+        for _ in range(args.warmup):
+            step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms = (t1 - t0) * 1e3 / args.steps
+
+        # per-kernel-class durations from HIP events on the library's stream: a second pass over the
+        # same K steps (the events cost a little per launch, so the timed region above runs without)
+        ctx.profile_enable(True)
+        for _ in range(args.steps):
+            step()
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
+
+    total_bytes, per_layer, head_bytes, accept_bytes = algorithmic_bytes(cfg)
+    kern = {kc: (t / n if n else 0.0) for kc, (t, n) in prof.items()}
+    dominant = "gateup"
+    dom_bytes = per_layer["gateup"]
+    dom_ms = kern[dominant]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel<.., A_F32_GAIN, EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "traffic": None, "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+                "measured": "hip events on the library stream, second pass of the same steps"}
+    out = {
+        "metric": "verified_tokens_per_s", "value": B * k / (ms * 1e-3), "unit": "tok/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {m.name} L={m.L} d={m.d} heads={m.Hq}/{m.Hkv} F={m.F} V={m.V} "
+                               f"B={B} C={cfg.C} k={k} {'tree' if cfg.tree else 'chain'}"},
+        "verify_step_latency_ms": ms,
+        "stage_algorithmic_GB": total_bytes / 1e9,
+        "stage_achieved_GBps": (total_bytes + accept_bytes) / (ms * 1e-3) / 1e9,
+        "stage_frac_of_hbm_peak": (total_bytes + accept_bytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "kernel_avg_ms": {kc: round(v, 5) for kc, v in kern.items() if v},
+        "kernel_launches_per_step": {kc: n // args.steps for kc, (t, n) in prof.items() if n},
+        "input_generation_s": round(t_gen, 1),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, K, V, hid, parent, args.cpu_sample_layers)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -183,6 +183,26 @@ int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, cons
 int dsd_kv_commit(dsd_ctx* ctx, dsd_kv* kv, const int32_t* accepted_len, const int32_t* accepted_path,
                   int B, int k);
 
+/* Diagnostics: time per kernel class.  While enabled, every kernel launch of dsd_stage_verify and
+ * dsd_accept is bracketed by a pair of HIP events on the context's stream (this serialises
+ * nothing but costs a little per launch, so leave it off when timing whole calls).
+ * dsd_profile_read synchronises the stream, adds up the event pairs recorded since the last
+ * read into ms_total[DSD_KC_COUNT] / launches[DSD_KC_COUNT] (host arrays) and forgets them. */
+enum dsd_kernel_class {
+    DSD_KC_QKV = 0,      /* RMSNorm + QKV projection + rotary + cache append */
+    DSD_KC_ATTN,         /* k-query attention over the cache                 */
+    DSD_KC_ATTN_COMBINE, /* merge of the key runs                            */
+    DSD_KC_OPROJ,        /* output projection + residual                     */
+    DSD_KC_GATEUP,       /* RMSNorm + gate/up projection + SiLU*up           */
+    DSD_KC_DOWN,         /* down projection + residual                       */
+    DSD_KC_HEAD,         /* final RMSNorm + LM head                          */
+    DSD_KC_ACCEPT,       /* all kernels of dsd_accept                        */
+    DSD_KC_OTHER,        /* row load / store                                 */
+    DSD_KC_COUNT
+};
+int dsd_profile_enable(dsd_ctx* ctx, int on);
+int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

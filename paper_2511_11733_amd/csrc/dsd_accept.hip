@@ -494,6 +494,7 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     dsd_accept_stats st = {nullptr, nullptr, nullptr, nullptr};
     if (stats) st = *stats;
     if (B > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
+    ProfScope ps(ctx, DSD_KC_ACCEPT);
     row_stats_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp, prm->top_m);
     row_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->top_m);
     node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, *prm, k, V, S, inv_temp);

@@ -22,6 +22,8 @@ void dsd_set_error(const char* fmt, ...) {
 extern "C" const char* dsd_last_error(void) { return g_err; }
 
 // ----------------------------------------------------------------------------- context
+static void prof_drop(dsd_ctx* ctx);
+
 extern "C" int dsd_create(int device, void* hip_stream, dsd_ctx** out) {
     if (!out) DSD_FAIL(DSD_EINVAL, "dsd_create: out is NULL");
     int n = 0;
@@ -41,6 +43,7 @@ extern "C" int dsd_create(int device, void* hip_stream, dsd_ctx** out) {
     c->ws_bytes = 0;
     const char* p = getenv("DSD_PATH");
     c->force_simple = p && strcmp(p, "simple") == 0;
+    c->prof_on = false;
     *out = c;
     return DSD_OK;
 }
@@ -49,8 +52,43 @@ extern "C" int dsd_destroy(dsd_ctx* ctx) {
     if (!ctx) return DSD_OK;
     hipSetDevice(ctx->device);
     hipStreamSynchronize(ctx->stream);
+    prof_drop(ctx);
     if (ctx->ws) hipFree(ctx->ws);
     delete ctx;
+    return DSD_OK;
+}
+
+static void prof_drop(dsd_ctx* ctx) {
+    for (auto& r : ctx->prof) {
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
+    }
+    ctx->prof.clear();
+}
+
+extern "C" int dsd_profile_enable(dsd_ctx* ctx, int on) {
+    if (!ctx) DSD_FAIL(DSD_EINVAL, "dsd_profile_enable: ctx is NULL");
+    DSD_HIP(hipStreamSynchronize(ctx->stream));
+    prof_drop(ctx);
+    ctx->prof_on = on != 0;
+    return DSD_OK;
+}
+
+extern "C" int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launches) {
+    if (!ctx || !ms_total || !launches) DSD_FAIL(DSD_EINVAL, "dsd_profile_read: NULL argument");
+    DSD_HIP(hipStreamSynchronize(ctx->stream));
+    for (int i = 0; i < DSD_KC_COUNT; ++i) {
+        ms_total[i] = 0.0;
+        launches[i] = 0;
+    }
+    for (auto& r : ctx->prof) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess && r.cls >= 0 && r.cls < DSD_KC_COUNT) {
+            ms_total[r.cls] += ms;
+            launches[r.cls] += 1;
+        }
+    }
+    prof_drop(ctx);
     return DSD_OK;
 }
 

@@ -76,12 +76,37 @@ __host__ __device__ inline size_t kv_v_off(const KvGeom& g, int b, int h, int sl
 }
 
 // ----------------------------------------------------------------------------- handles
+struct ProfRec {
+    int cls;
+    hipEvent_t e0, e1;
+};
+
 struct dsd_ctx {
     int device;
     hipStream_t stream;
     char* ws;
     size_t ws_bytes;
     bool force_simple;  // DSD_PATH=simple: run the generic kernels also for bf16 models
+    bool prof_on;
+    std::vector<ProfRec> prof;
+};
+
+// Brackets the launches of one scope with a pair of events when profiling is on.
+struct ProfScope {
+    dsd_ctx* c;
+    ProfRec r;
+    ProfScope(dsd_ctx* ctx, int cls) : c(ctx) {
+        r.cls = cls;
+        r.e0 = r.e1 = nullptr;
+        if (c->prof_on && hipEventCreate(&r.e0) == hipSuccess && hipEventCreate(&r.e1) == hipSuccess)
+            (void)hipEventRecord(r.e0, c->stream);
+    }
+    ~ProfScope() {
+        if (c->prof_on && r.e0 && r.e1) {
+            (void)hipEventRecord(r.e1, c->stream);
+            c->prof.push_back(r);
+        }
+    }
 };
 
 struct LayerW {

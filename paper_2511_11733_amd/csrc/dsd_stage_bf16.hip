@@ -539,7 +539,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     hipStream_t s = ctx->stream;
 
     const size_t nx = (size_t)M * d;
-    rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
+    {
+        ProfScope ps(ctx, DSD_KC_OTHER);
+        rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
+    }
 
     for (int l = 0; l < D.n_layers; ++l) {
         const LayerW& W = w->layers[l];
@@ -552,13 +555,18 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.Wt = (const uint4*)W.qkv_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)W.g1;
         a.q = q; a.kc = kc; a.vc = vc; a.g = g; a.len = kv->len_dev; a.depth = depth; a.k = k; a.Hq = Hq;
         a.theta = D.rope_theta;
-        DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
+        {
+            ProfScope ps(ctx, DSD_KC_QKV);
+            DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
+        }
         // attention
         AttnArgs t;
         t.q = q; t.kc = kc; t.vc = vc; t.g = g; t.len = kv->len_dev; t.mask = tree_mask; t.k = k; t.Hq = Hq; t.G = G;
         t.keys_per_wave = keys_per_wave; t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
         t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
         dim3 ag((n_runs + 3) / 4, Hkv, B);
+        {
+        ProfScope ps(ctx, DSD_KC_ATTN);
         switch (RT) {
             case 1: attn_partial_kernel<1><<<ag, 256, 0, s>>>(t); break;
             case 2: attn_partial_kernel<2><<<ag, 256, 0, s>>>(t); break;
@@ -567,26 +575,43 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
             case 6: attn_partial_kernel<6><<<ag, 256, 0, s>>>(t); break;
             default: attn_partial_kernel<8><<<ag, 256, 0, s>>>(t); break;
         }
+        }
+        {
+        ProfScope ps(ctx, DSD_KC_ATTN_COMBINE);
         attn_combine_kernel<<<dim3(rows, Hkv, B), 128, 0, s>>>(att, part_o, part_ml, n_runs, t.rows_pad, k, G, Hq, Hkv);
+        }
         // x += attn Wo^T
         a = GemmArgs();
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
-        DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+        {
+            ProfScope ps(ctx, DSD_KC_OPROJ);
+            DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+        }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
         a = GemmArgs();
         a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)W.gu_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)W.g2;
         a.hout = h; a.N = F; a.up_tile_off = F / 16;
-        DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
+        {
+            ProfScope ps(ctx, DSD_KC_GATEUP);
+            DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
+        }
         // x += h Wd^T
         a = GemmArgs();
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
-        DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+        {
+            ProfScope ps(ctx, DSD_KC_DOWN);
+            DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+        }
     }
-    if (hidden_out) rows_out_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>((bf16_t*)hidden_out, x, nx);
+    if (hidden_out) {
+        ProfScope ps(ctx, DSD_KC_OTHER);
+        rows_out_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>((bf16_t*)hidden_out, x, nx);
+    }
     if (logits) {
         GemmArgs a = GemmArgs();
         a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)w->lm_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)w->gf;
         a.logits = logits; a.N = D.vocab; a.rows_per_seq = k; a.seq_stride = logits_seq_stride;
+        ProfScope ps(ctx, DSD_KC_HEAD);
         DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
     }
     DSD_HIP(hipGetLastError());

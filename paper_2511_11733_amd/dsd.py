@@ -23,8 +23,9 @@ DSD_MAX_K, DSD_MAX_TOP_M = 64, 16
 EXPORTS = [
     "dsd_last_error", "dsd_create", "dsd_destroy", "dsd_set_stream", "dsd_weights_create", "dsd_weights_destroy",
     "dsd_kv_create", "dsd_kv_destroy", "dsd_kv_import", "dsd_kv_export", "dsd_kv_set_len", "dsd_kv_get_len",
-    "dsd_stage_verify", "dsd_accept", "dsd_kv_commit",
+    "dsd_stage_verify", "dsd_accept", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read",
 ]
+KERNEL_CLASSES = ["qkv", "attn", "attn_combine", "oproj", "gateup", "down", "head", "accept", "other"]
 
 
 class DsdError(RuntimeError):
@@ -79,6 +80,8 @@ def load() -> C.CDLL:
         "dsd_accept": [vp, vp, vp, vp, vp, vp, C.POINTER(AcceptParams), i32, i32, i32, vp, vp, vp,
                        C.POINTER(AcceptStats)],
         "dsd_kv_commit": [vp, vp, vp, vp, i32, i32],
+        "dsd_profile_enable": [vp, i32],
+        "dsd_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -128,6 +131,17 @@ class Context:
 
     def set_stream(self, stream: Optional[torch.cuda.Stream]) -> None:
         _check(self.lib.dsd_set_stream(self.h, None if stream is None else stream.cuda_stream), "dsd_set_stream")
+
+    def profile_enable(self, on: bool) -> None:
+        _check(self.lib.dsd_profile_enable(self.h, int(on)), "dsd_profile_enable")
+
+    def profile_read(self) -> dict:
+        """{kernel class: (total ms, launches)} since the last read."""
+        n = len(KERNEL_CLASSES)
+        ms = (C.c_double * n)()
+        cnt = (C.c_int64 * n)()
+        _check(self.lib.dsd_profile_read(self.h, ms, cnt), "dsd_profile_read")
+        return {KERNEL_CLASSES[i]: (ms[i], cnt[i]) for i in range(n)}
 
     def close(self) -> None:
         if self.h:

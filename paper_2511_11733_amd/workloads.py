@@ -123,7 +123,7 @@ CONFIGS = {
 def scaled(cfg: WorkCfg, **kw) -> WorkCfg:
     """A reduced copy of a workload (fewer layers, narrower, shorter context) for
     parity cases a CPU finishes in seconds.  Keys of ModelCfg go to the model."""
-    mkeys = {k: kw.pop(k) for k in list(kw) if k in ModelCfg.__dataclass_fields__}
+    mkeys = {k: kw.pop(k) for k in list(kw) if k in ModelCfg.__dataclass_fields__ and k != "name"}
     model = replace(cfg.model, **mkeys) if mkeys else cfg.model
     return replace(cfg, model=model, **kw)
 

@@ -60,8 +60,9 @@ class GpuStage:
 
     def import_kv(self, K: np.ndarray, V: np.ndarray, lens):
         """K, V: [L, B, Hkv, C, hd] (model dtype; float64 oracle output is rounded to it)."""
-        for l in range(self.m.L):
-            self.kv.import_layer(l, self._cast(K[l]), self._cast(V[l]))
+        if K.shape[3] > 0:
+            for l in range(self.m.L):
+                self.kv.import_layer(l, self._cast(K[l]), self._cast(V[l]))
         self.kv.set_len(lens)
 
     def _cast(self, a: np.ndarray) -> torch.Tensor:
