@@ -222,6 +222,7 @@ extern "C" int dsd_kv_create(dsd_ctx* ctx, const dsd_model_desc* desc, int max_b
     kv->k = kv->v = nullptr;
     kv->len_dev = nullptr;
     kv->last_k = 0;
+    kv->cap = max_slots;
     if (hipMalloc(&kv->k, bytes) != hipSuccess || hipMalloc(&kv->v, bytes) != hipSuccess ||
         hipMalloc((void**)&kv->len_dev, sizeof(int32_t) * max_batch) != hipSuccess) {
         if (kv->k) hipFree(kv->k);
@@ -257,8 +258,8 @@ extern "C" int dsd_kv_set_len(dsd_ctx* ctx, dsd_kv* kv, const int32_t* host_len,
     if (!ctx || !kv || !host_len) DSD_FAIL(DSD_EINVAL, "dsd_kv_set_len: NULL argument");
     if (B < 1 || B > kv->geom.Bmax) DSD_FAIL(DSD_ESHAPE, "dsd_kv_set_len: B=%d, cache holds %d", B, kv->geom.Bmax);
     for (int b = 0; b < B; ++b)
-        if (host_len[b] < 0 || host_len[b] > kv->geom.S)
-            DSD_FAIL(DSD_ESHAPE, "dsd_kv_set_len: len[%d]=%d, cache holds %d slots", b, host_len[b], kv->geom.S);
+        if (host_len[b] < 0 || host_len[b] > kv->cap)
+            DSD_FAIL(DSD_ESHAPE, "dsd_kv_set_len: len[%d]=%d, cache holds %d slots", b, host_len[b], kv->cap);
     // the host array may go away after the call: copy synchronously
     DSD_HIP(hipStreamSynchronize(ctx->stream));
     DSD_HIP(hipMemcpy(kv->len_dev, host_len, sizeof(int32_t) * B, hipMemcpyHostToDevice));
@@ -280,8 +281,8 @@ extern "C" int dsd_kv_get_len(dsd_ctx* ctx, const dsd_kv* kv, int32_t* host_len,
 extern "C" int dsd_kv_import(dsd_ctx* ctx, dsd_kv* kv, int layer, const void* k, const void* v, int B, int n_slots) {
     if (!ctx || !kv || !k || !v) DSD_FAIL(DSD_EINVAL, "dsd_kv_import: NULL argument");
     if (layer < 0 || layer >= kv->desc.n_layers) DSD_FAIL(DSD_EINVAL, "dsd_kv_import: layer %d", layer);
-    if (B < 1 || B > kv->geom.Bmax || n_slots < 1 || n_slots > kv->geom.S)
-        DSD_FAIL(DSD_ESHAPE, "dsd_kv_import: B=%d n_slots=%d vs cache %d x %d", B, n_slots, kv->geom.Bmax, kv->geom.S);
+    if (B < 1 || B > kv->geom.Bmax || n_slots < 1 || n_slots > kv->cap)
+        DSD_FAIL(DSD_ESHAPE, "dsd_kv_import: B=%d n_slots=%d vs cache %d x %d", B, n_slots, kv->geom.Bmax, kv->cap);
     DSD_HIP(hipSetDevice(ctx->device));
     return kv_import_launch(ctx, kv, layer, k, v, B, n_slots);
 }
@@ -290,9 +291,9 @@ extern "C" int dsd_kv_export(dsd_ctx* ctx, const dsd_kv* kv, int layer, int firs
                              void* k_out, void* v_out) {
     if (!ctx || !kv || !k_out || !v_out) DSD_FAIL(DSD_EINVAL, "dsd_kv_export: NULL argument");
     if (layer < 0 || layer >= kv->desc.n_layers) DSD_FAIL(DSD_EINVAL, "dsd_kv_export: layer %d", layer);
-    if (B < 1 || B > kv->geom.Bmax || first_slot < 0 || n_slots < 1 || first_slot + n_slots > kv->geom.S)
+    if (B < 1 || B > kv->geom.Bmax || first_slot < 0 || n_slots < 1 || first_slot + n_slots > kv->cap)
         DSD_FAIL(DSD_ESHAPE, "dsd_kv_export: B=%d slots [%d,%d) vs cache %d x %d", B, first_slot,
-                 first_slot + n_slots, kv->geom.Bmax, kv->geom.S);
+                 first_slot + n_slots, kv->geom.Bmax, kv->cap);
     DSD_HIP(hipSetDevice(ctx->device));
     return kv_export_launch(ctx, kv, layer, first_slot, n_slots, B, k_out, v_out);
 }
@@ -304,7 +305,7 @@ extern "C" int dsd_kv_commit(dsd_ctx* ctx, dsd_kv* kv, const int32_t* accepted_l
     if (k != kv->last_k) DSD_FAIL(DSD_ESHAPE, "dsd_kv_commit: k=%d but the last verify wrote %d rows", k, kv->last_k);
     DSD_HIP(hipSetDevice(ctx->device));
     DSD_TRY(kv_commit_launch(ctx, kv, accepted_len, accepted_path, B, k));
-    for (int b = 0; b < B; ++b) kv->len_bound[b] = std::min(kv->len_bound[b] + k, kv->geom.S);
+    for (int b = 0; b < B; ++b) kv->len_bound[b] = std::min(kv->len_bound[b] + k, kv->cap);
     kv->last_k = 0;
     return DSD_OK;
 }
@@ -327,9 +328,9 @@ extern "C" int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, 
     if (logits && logits_seq_stride < (int64_t)k * w->desc.vocab)
         DSD_FAIL(DSD_ESHAPE, "dsd_stage_verify: logits_seq_stride smaller than k*V");
     for (int b = 0; b < B; ++b)
-        if (kv->len_bound[b] + k > kv->geom.S)
+        if (kv->len_bound[b] + k > kv->cap)
             DSD_FAIL(DSD_ESHAPE, "dsd_stage_verify: sequence %d: %d + %d rows exceed %d slots", b, kv->len_bound[b], k,
-                     kv->geom.S);
+                     kv->cap);
     DSD_HIP(hipSetDevice(ctx->device));
     int rc;
     if (w->tiled)

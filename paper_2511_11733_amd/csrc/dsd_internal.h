@@ -135,6 +135,7 @@ struct dsd_kv {
     int32_t* len_dev;  // [Bmax] committed lengths (the truth)
     std::vector<int32_t> len_bound;  // host upper bounds, used to size grids and validate
     int last_k;        // rows written by the last dsd_stage_verify
+    int cap;           // slots per sequence the caller asked for (<= geom.S)
 };
 
 inline size_t dsd_elem_size(int dtype) { return dtype == DSD_BF16 ? 2 : 4; }
