@@ -10,6 +10,9 @@
 //     KV-cache append, SiLU*up, residual add, or fp32 logits;
 //   * RMSNorm never makes a pass of its own: x*g is applied while the A operand is loaded, the
 //     sum of squares is accumulated from those same loads, and 1/rms scales the output rows;
+//   * activations enter the matrix cores as a sum of two bf16 terms (hi + lo, two MFMAs per weight
+//     fragment): the weights stay bit-exact bf16, the activations keep ~16 mantissa bits, and
+//     the extra MFMA work is free while the pass is bandwidth bound;
 //   * attention computes S^T = K Q^T so that the scores a lane holds are exactly the P^T operand
 //     of O^T = V^T P^T; V is cached transposed for that product (see KvGeom).
 #include "dsd_internal.h"
@@ -28,6 +31,19 @@ __device__ inline unsigned pack_bf16(float a, float b) {
 __device__ inline bf16x8 pack8(const float* f) {
     uint4 u = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
     return __builtin_bit_cast(bf16x8, u);
+}
+// v = hi + lo with both halves bf16 (lo carries the rounding remainder of hi)
+__device__ inline void split8(const float* v, bf16x8* hi, bf16x8* lo) {
+    uint4 hu = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+    const unsigned hw[4] = {hu.x, hu.y, hu.z, hu.w};
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        r[2 * i] = v[2 * i] - __uint_as_float(hw[i] << 16);
+        r[2 * i + 1] = v[2 * i + 1] - __uint_as_float(hw[i] & 0xFFFF0000u);
+    }
+    *hi = __builtin_bit_cast(bf16x8, hu);
+    *lo = pack8(r);
 }
 __device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     // D[4*(lane/16)+i][lane%16] += sum_k A[lane%16][8*(lane/16)+k] * B[8*(lane/16)+k][lane%16]
@@ -105,7 +121,7 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors) 
 }
 
 // ============================================================================ skinny GEMM
-enum { A_F32_GAIN = 0, A_BF16 = 1 };
+enum { A_F32_GAIN = 0, A_F32 = 1 };
 enum { EPI_QKV = 0, EPI_SWIGLU = 1, EPI_RESID = 2, EPI_LOGITS = 3 };
 
 struct GemmArgs {
@@ -115,18 +131,18 @@ struct GemmArgs {
     // A operand
     const float* x;       // [M][K] fp32 residual stream          (A_F32_GAIN)
     const bf16_t* gain;   // [K]                                   (A_F32_GAIN)
-    const bf16_t* a;      // [M][K] bf16                           (A_BF16)
+    const float* a;       // [M][K] fp32 activations               (A_F32)
     float eps;
     // epilogues
     float* xout;          // EPI_RESID: [M][N] fp32, updated in place
     int N;
-    bf16_t* hout;         // EPI_SWIGLU: [M][F]
+    float* hout;          // EPI_SWIGLU: [M][F]
     int up_tile_off;      // EPI_SWIGLU: F/16
     float* logits;        // EPI_LOGITS
     int rows_per_seq;
     int64_t seq_stride;
     // EPI_QKV
-    bf16_t* q;            // [M][Hq*hd]
+    float* q;             // [M][Hq*hd] rotated queries, fp32
     bf16_t* kc;           // this layer's K cache
     bf16_t* vc;           // this layer's V cache
     KvGeom g;
@@ -172,46 +188,44 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) bfrag[nt] = __builtin_bit_cast(bf16x8, wt[nt][(size_t)ks * 64]);
         const int kb = ks * 32 + g * 8;
-        bf16x8 afrag[MT];
+        bf16x8 ahi[MT], alo[MT];
+        float gf[8];
         if (AMODE == A_F32_GAIN) {
             const uint4 gu = *(const uint4*)(p.gain + kb);
-            float gf[8];
             const unsigned gw[4] = {gu.x, gu.y, gu.z, gu.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 gf[2 * i] = __uint_as_float(gw[i] << 16);
                 gf[2 * i + 1] = __uint_as_float(gw[i] & 0xFFFF0000u);
             }
+        }
+        const float* asrc = (AMODE == A_F32_GAIN) ? p.x : p.a;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int row = mt * 16 + c;
-                float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                if (row < p.M) {
-                    const float4 v0 = *(const float4*)(p.x + (size_t)row * K + kb);
-                    const float4 v1 = *(const float4*)(p.x + (size_t)row * K + kb + 4);
-                    v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
-                    v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
-                }
+        for (int mt = 0; mt < MT; ++mt) {
+            const int row = mt * 16 + c;
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (row < p.M) {
+                const float4 v0 = *(const float4*)(asrc + (size_t)row * K + kb);
+                const float4 v1 = *(const float4*)(asrc + (size_t)row * K + kb + 4);
+                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+                v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+            }
+            if (AMODE == A_F32_GAIN) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     ssq[mt] += v[i] * v[i];
                     v[i] *= gf[i];
                 }
-                afrag[mt] = pack8(v);
             }
-        } else {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int row = mt * 16 + c;
-                uint4 u = {0u, 0u, 0u, 0u};
-                if (row < p.M) u = *(const uint4*)(p.a + (size_t)row * K + kb);
-                afrag[mt] = __builtin_bit_cast(bf16x8, u);
-            }
+            split8(v, &ahi[mt], &alo[mt]);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16(afrag[mt], bfrag[nt], acc[mt][nt]);
+            for (int nt = 0; nt < NT; ++nt) {
+                acc[mt][nt] = mfma16(ahi[mt], bfrag[nt], acc[mt][nt]);
+                acc[mt][nt] = mfma16(alo[mt], bfrag[nt], acc[mt][nt]);
+            }
     }
 
     // partial tiles (and partial sums of squares) of all waves meet in LDS
@@ -264,7 +278,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
             } else if (EPI == EPI_SWIGLU) {
                 const float gate = o[0][i] * rstd[i], up = o[NT - 1][i] * rstd[i];
                 const float h = gate / (1.0f + __expf(-gate)) * up;
-                p.hout[(size_t)m * p.N + tile[0] * 16 + c] = f32_to_bf16(h);
+                p.hout[(size_t)m * p.N + tile[0] * 16 + c] = h;
             } else {  // EPI_QKV
                 const int hd = 128, half = 64;
                 const int head = tile[0] >> 3;                 // 8 column tiles per head
@@ -281,9 +295,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
                     const float r0 = lo * (float)cs - hi * (float)sn;
                     const float r1 = hi * (float)cs + lo * (float)sn;
                     if (head < p.Hq) {
-                        bf16_t* dst = p.q + ((size_t)m * p.Hq + head) * hd;
-                        dst[e] = f32_to_bf16(r0);
-                        dst[e + half] = f32_to_bf16(r1);
+                        float* dst = p.q + ((size_t)m * p.Hq + head) * hd;
+                        dst[e] = r0;
+                        dst[e + half] = r1;
                     } else if (slot < p.g.S) {
                         const int hk = head - p.Hq;
                         p.kc[kv_k_off(p.g, b, hk, slot, e)] = f32_to_bf16(r0);
@@ -328,7 +342,7 @@ static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
 // (row r = t*G + head-in-group).  Partial (max, sum, O) per run go to scratch; attn_combine
 // merges the runs.
 struct AttnArgs {
-    const bf16_t* q;       // [M][Hq*hd]
+    const float* q;        // [M][Hq*hd] fp32
     const bf16_t* kc;
     const bf16_t* vc;
     KvGeom g;
@@ -356,8 +370,8 @@ __global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
     const int j_end = min(j_begin + p.keys_per_wave, nkeys);
     const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad;
 
-    // Q^T fragments: lane (row c of tile rt, k-group g) holds q[row][32j + 8g .. +8]
-    bf16x8 qf[RT][4];
+    // Q^T fragments: lane (row c of tile rt, k-group g) holds q[row][32j + 8g .. +8], as hi + lo
+    bf16x8 qh[RT][4], ql[RT][4];
     uint64_t vis[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -367,9 +381,14 @@ __global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
         if (r < rows) vis[rt] = p.mask ? p.mask[t] : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1ull));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint4 u = {0u, 0u, 0u, 0u};
-            if (r < rows) u = *(const uint4*)(p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8);
-            qf[rt][j] = __builtin_bit_cast(bf16x8, u);
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (r < rows) {
+                const float* src = p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8;
+                const float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
+                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+                v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+            }
+            split8(v, &qh[rt][j], &ql[rt][j]);
         }
     }
     f32x4 o[8][RT];
@@ -399,7 +418,10 @@ __global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
             for (int rt = 0; rt < RT; ++rt) {
                 f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) a = mfma16(kf[j], qf[rt][j], a);
+                for (int j = 0; j < 4; ++j) {
+                    a = mfma16(kf[j], qh[rt][j], a);
+                    a = mfma16(kf[j], ql[rt][j], a);
+                }
                 s[tl][rt] = a;
             }
         }
@@ -442,11 +464,13 @@ __global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
                     ps += e;
                 }
             lrow[rt] = lrow[rt] * alpha + ps;
-            const bf16x8 pf = pack8(pv);
+            bf16x8 ph, pl;
+            split8(pv, &ph, &pl);
 #pragma unroll
             for (int h = 0; h < 8; ++h) {
                 o[h][rt] *= alpha;
-                o[h][rt] = mfma16(vf[h], pf, o[h][rt]);
+                o[h][rt] = mfma16(vf[h], ph, o[h][rt]);
+                o[h][rt] = mfma16(vf[h], pl, o[h][rt]);
             }
         }
     }
@@ -467,25 +491,47 @@ __global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
 }
 
 // out[m][hq*128 + e] = sum_runs 2^(m_run - M) O_run[e] / sum_runs 2^(m_run - M) l_run
-__global__ void attn_combine_kernel(bf16_t* __restrict__ out, const float* __restrict__ part_o,
-                                    const float* __restrict__ part_ml, int n_runs, int rows_pad, int k, int G, int Hq,
-                                    int Hkv) {
+// One block of 128 threads per query row: the run weights are formed once in LDS (threads over
+// runs), then every thread sums its feature over the runs with independent loads.
+#define MAX_RUNS 512
+__global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ out, const float* __restrict__ part_o,
+                                                          const float* __restrict__ part_ml, int n_runs, int rows_pad,
+                                                          int k, int G, int Hq, int Hkv) {
+    __shared__ float wgt[MAX_RUNS];
+    __shared__ float red[4];
     const int r = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-    const int e = threadIdx.x;   // 128 threads
+    const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
     const size_t u0 = (size_t)(b * Hkv + hk) * n_runs;
-    float M = -INFINITY;
-    for (int s = 0; s < n_runs; ++s) M = fmaxf(M, part_ml[((u0 + s) * rows_pad + r) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < n_runs; ++s) {
-        const size_t idx = (u0 + s) * rows_pad + r;
-        const float m = part_ml[idx * 2];
-        if (m == -INFINITY) continue;
-        const float w = exp2f(m - M);
-        den += w * part_ml[idx * 2 + 1];
-        num += w * part_o[idx * 128 + e];
+    float mx = -INFINITY;
+    for (int s = e; s < n_runs; s += 128) {
+        const float m = part_ml[((u0 + s) * rows_pad + r) * 2];
+        wgt[s] = m;
+        mx = fmaxf(mx, m);
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    const float M = fmaxf(red[0], red[1]);
+    float den = 0.f;
+    for (int s = e; s < n_runs; s += 128) {
+        const float m = wgt[s];
+        const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);
+        wgt[s] = w;
+        den += w * part_ml[((u0 + s) * rows_pad + r) * 2 + 1];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o, WAVE);
+    if (lane == 0) red[2 + wave] = den;
+    __syncthreads();
+    den = red[2] + red[3];
+    float num = 0.f;
+    const float* po = part_o + (u0 * rows_pad + r) * 128 + e;
+    const size_t stride = (size_t)rows_pad * 128;
+#pragma unroll 8
+    for (int s = 0; s < n_runs; ++s) num += wgt[s] * po[s * stride];
     const int t = r / G, hq = hk * G + r % G;
-    out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = f32_to_bf16(num / den);
+    out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = num / den;
 }
 
 // ============================================================================ small kernels
@@ -523,17 +569,18 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     long kpw = ((long)max_keys * units + 2047) / 2048;
     kpw = std::max(64L, (kpw + 31) / 32 * 32);
     const int keys_per_wave = (int)kpw;
-    const int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
+    int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
+    if (n_runs > MAX_RUNS) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: %d key runs", n_runs);
     const int rows_pad = RT * 16;
 
-    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 2 * 2 + (size_t)M * F * 2 +
+    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 +
                   (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
     WsBump ws{ctx->ws, 0};
     float* x = ws.take<float>((size_t)M * d);
-    bf16_t* q = ws.take<bf16_t>((size_t)M * qd);
-    bf16_t* att = ws.take<bf16_t>((size_t)M * qd);
-    bf16_t* h = ws.take<bf16_t>((size_t)M * F);
+    float* q = ws.take<float>((size_t)M * qd);
+    float* att = ws.take<float>((size_t)M * qd);
+    float* h = ws.take<float>((size_t)M * F);
     float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
     float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
     hipStream_t s = ctx->stream;
@@ -585,7 +632,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
-            DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+            DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
         a = GemmArgs();
@@ -600,7 +647,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
-            DSD_TRY((gemm_dispatch<1, A_BF16, EPI_RESID>(s, a, d / 16)));
+            DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
     }
     if (hidden_out) {

