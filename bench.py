@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2", help="workload: c2 (default), c3, c4, c5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (a known-size reference for HBM byte counters)")
     ap.add_argument("--cpu-sample-layers", type=int, default=0, help="0 = all layers of the block")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -180,15 +182,35 @@ def main():
         prof = ctx.profile_read()
         ctx.profile_enable(False)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     total_bytes, per_layer, head_bytes, accept_bytes = algorithmic_bytes(cfg)
     kern = {kc: (t / n if n else 0.0) for kc, (t, n) in prof.items()}
     dominant = "gateup"
     dom_bytes = per_layer["gateup"]
     dom_ms = kern[dominant]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+    traffic = None
+    prof_txt = os.path.join(ROOT, "profiles", f"verify_step_{cfg.name}.txt")
+    if os.path.exists(prof_txt):
+        # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+        # (FETCH_SIZE, WRITE_SIZE scaled by the copy-kernel calibration stated in that file)
+        for line in open(prof_txt):
+            if "gemm_skinny_kernel<1, 2, 0, 1" in line or "DOMINANT" in line:
+                parts = line.split()
+                try:
+                    traffic = (float(parts[-2]) + float(parts[-1])) * 1e6
+                except ValueError:
+                    pass
     roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel<.., A_F32_GAIN, EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                "traffic": None, "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+                "traffic": traffic, "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
                 "measured": "hip events on the library stream, second pass of the same steps"}
     out = {
         "metric": "verified_tokens_per_s", "value": B * k / (ms * 1e-3), "unit": "tok/s", "n_gpus": 1,
