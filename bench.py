@@ -192,8 +192,15 @@ def main():
 
     total_bytes, per_layer, head_bytes, accept_bytes = algorithmic_bytes(cfg)
     kern = {kc: (t / n if n else 0.0) for kc, (t, n) in prof.items()}
-    dominant = "gateup"
-    dom_bytes = per_layer["gateup"]
+    if kern.get("stage", 0.0) > 0.0:
+        # at most 16 rows: the whole block of layers is one persistent kernel
+        dominant, dom_bytes = "stage", total_bytes
+        dom_name = "stage_persist_kernel (all layers of the block: QKV, attention, O-proj, gate/up, down)"
+        dom_match = "stage_persist_kernel"
+    else:
+        dominant, dom_bytes = "gateup", per_layer["gateup"]
+        dom_name = "gemm_skinny_kernel<.., A_F32_GAIN, EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)"
+        dom_match = "gemm_skinny_kernel<" + str((B * k + 15) // 16) + ", 2, 0, 1"
     dom_ms = kern[dominant]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
     traffic = None
@@ -202,13 +209,13 @@ def main():
         # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
         # (FETCH_SIZE, WRITE_SIZE scaled by the copy-kernel calibration stated in that file)
         for line in open(prof_txt):
-            if "gemm_skinny_kernel<1, 2, 0, 1" in line or "DOMINANT" in line:
+            if dom_match in line:
                 parts = line.split()
                 try:
                     traffic = (float(parts[-2]) + float(parts[-1])) * 1e6
                 except ValueError:
                     pass
-    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel<.., A_F32_GAIN, EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)",
+    roofline = {"bound": "hbm", "kernel": dom_name,
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": traffic, "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
                 "measured": "hip events on the library stream, second pass of the same steps"}

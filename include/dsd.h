@@ -198,6 +198,7 @@ enum dsd_kernel_class {
     DSD_KC_HEAD,         /* final RMSNorm + LM head                          */
     DSD_KC_ACCEPT,       /* all kernels of dsd_accept                        */
     DSD_KC_OTHER,        /* row load / store                                 */
+    DSD_KC_STAGE,        /* the whole block of layers as one persistent kernel (<= 16 rows) */
     DSD_KC_COUNT
 };
 int dsd_profile_enable(dsd_ctx* ctx, int on);

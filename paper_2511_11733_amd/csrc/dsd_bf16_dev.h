@@ -1,0 +1,345 @@
+// Device-side building blocks of the bf16 verification pass, shared by the per-step kernels
+// (dsd_stage_bf16.hip) and the persistent stage kernel (dsd_stage_persist.hip).
+#pragma once
+
+#include "dsd_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+#define WAVE 64
+#define MAX_RUNS 512
+
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ bf16x8 pack8(const float* f) {
+    uint4 u = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
+    return __builtin_bit_cast(bf16x8, u);
+}
+// v = hi + lo with both halves bf16 (lo carries the rounding remainder of hi)
+__device__ __forceinline__ void split8(const float* v, bf16x8* hi, bf16x8* lo) {
+    uint4 hu = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+    const unsigned hw[4] = {hu.x, hu.y, hu.z, hu.w};
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        r[2 * i] = v[2 * i] - __uint_as_float(hw[i] << 16);
+        r[2 * i + 1] = v[2 * i + 1] - __uint_as_float(hw[i] & 0xFFFF0000u);
+    }
+    *hi = __builtin_bit_cast(bf16x8, hu);
+    *lo = pack8(r);
+}
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    // D[4*(lane/16)+i][lane%16] += sum_k A[lane%16][8*(lane/16)+k] * B[8*(lane/16)+k][lane%16]
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// 8 bf16 gains (one 16-byte load) -> floats
+__device__ __forceinline__ void unpack_gain(uint4 gu, float* gf) {
+    const unsigned gw[4] = {gu.x, gu.y, gu.z, gu.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        gf[2 * i] = __uint_as_float(gw[i] << 16);
+        gf[2 * i + 1] = __uint_as_float(gw[i] & 0xFFFF0000u);
+    }
+}
+
+// ============================================================================ GEMM pieces
+enum { A_F32_GAIN = 0, A_F32 = 1 };
+enum { EPI_QKV = 0, EPI_SWIGLU = 1, EPI_RESID = 2, EPI_LOGITS = 3 };
+
+struct GemmArgs {
+    const uint4* Wt;      // tiled weights: fragment (tile nt, k-step ks) at (nt*KS + ks)*64 + lane
+    int KS;               // K / 32
+    int M;                // rows in use
+    // A operand
+    const float* x;       // [M][K] fp32 residual stream          (A_F32_GAIN)
+    const bf16_t* gain;   // [K]                                   (A_F32_GAIN)
+    const float* a;       // [M][K] fp32 activations               (A_F32)
+    float eps;
+    // epilogues
+    float* xout;          // EPI_RESID: [M][N] fp32, updated in place
+    int N;
+    float* hout;          // EPI_SWIGLU: [M][F]
+    int up_tile_off;      // EPI_SWIGLU: F/16
+    float* logits;        // EPI_LOGITS
+    int rows_per_seq;
+    int64_t seq_stride;
+    // EPI_QKV
+    float* q;             // [M][Hq*hd] rotated queries, fp32
+    bf16_t* kc;           // this layer's K cache
+    bf16_t* vc;           // this layer's V cache
+    KvGeom g;
+    const int32_t* len;
+    const int32_t* depth;
+    int k;
+    int Hq;
+    float theta;
+};
+
+// column tiles a workgroup / unit owns
+template <int NT, int EPI>
+__device__ __forceinline__ void unit_tiles(const GemmArgs& p, int unit, int (&tile)[NT]) {
+    if (EPI == EPI_QKV) {               // column tiles (t, t+4) of one head: the rotary pair
+        tile[0] = (unit >> 2) * 8 + (unit & 3);
+        if (NT > 1) tile[NT - 1] = tile[0] + 4;
+    } else if (EPI == EPI_SWIGLU) {     // gate tile and the matching up tile
+        tile[0] = unit;
+        if (NT > 1) tile[NT - 1] = unit + p.up_tile_off;
+    } else {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) tile[i] = unit * NT + i;
+    }
+}
+
+// Fused epilogue for one 16-row tile: lane (c = lane%16, g = lane/16) holds rows mt*16 + 4g + i,
+// column tile*16 + c of every tile in o[]; rstd[i] = 1/rms of those rows (1 when unused).
+template <int NT, int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, const int (&tile)[NT], const f32x4 (&o)[NT],
+                                              const float (&rstd)[4], int mt, int c, int g) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = mt * 16 + g * 4 + i;      // output row of element i
+        if (m >= p.M) continue;
+        if (EPI == EPI_RESID) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float* dst = p.xout + (size_t)m * p.N + tile[nt] * 16 + c;
+                *dst += o[nt][i];
+            }
+        } else if (EPI == EPI_LOGITS) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                p.logits[(size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N +
+                         tile[nt] * 16 + c] = o[nt][i] * rstd[i];
+        } else if (EPI == EPI_SWIGLU) {
+            const float gate = o[0][i] * rstd[i], up = o[NT - 1][i] * rstd[i];
+            const float h = gate / (1.0f + __expf(-gate)) * up;
+            p.hout[(size_t)m * p.N + tile[0] * 16 + c] = h;
+        } else {  // EPI_QKV
+            const int hd = 128, half = 64;
+            const int head = tile[0] >> 3;                 // 8 column tiles per head
+            const int e = (tile[0] & 7) * 16 + c;          // < 64: first element of the rotary pair
+            const float lo = o[0][i] * rstd[i], hi = o[NT - 1][i] * rstd[i];
+            const int b = m / p.k, t = m % p.k;
+            const int L = p.len[b];
+            const int slot = L + t;
+            if (head < p.Hq + p.g.Hkv) {
+                const double pos = (double)(L + (p.depth ? p.depth[t] : t));
+                const double inv = pow((double)p.theta, -2.0 * (double)e / (double)hd);
+                double sn, cs;
+                sincos(pos * inv, &sn, &cs);
+                const float r0 = lo * (float)cs - hi * (float)sn;
+                const float r1 = hi * (float)cs + lo * (float)sn;
+                if (head < p.Hq) {
+                    float* dst = p.q + ((size_t)m * p.Hq + head) * hd;
+                    dst[e] = r0;
+                    dst[e + half] = r1;
+                } else if (slot < p.g.S) {
+                    const int hk = head - p.Hq;
+                    p.kc[kv_k_off(p.g, b, hk, slot, e)] = f32_to_bf16(r0);
+                    p.kc[kv_k_off(p.g, b, hk, slot, e + half)] = f32_to_bf16(r1);
+                }
+            } else if (slot < p.g.S) {
+                const int hk = head - p.Hq - p.g.Hkv;
+                p.vc[kv_v_off(p.g, b, hk, slot, e)] = f32_to_bf16(lo);
+                p.vc[kv_v_off(p.g, b, hk, slot, e + half)] = f32_to_bf16(hi);
+            }
+        }
+    }
+}
+
+// ============================================================================ attention pieces
+struct AttnArgs {
+    const float* q;        // [M][Hq*hd] fp32
+    const bf16_t* kc;
+    const bf16_t* vc;
+    KvGeom g;
+    const int32_t* len;
+    const uint64_t* mask;
+    int k, Hq, G;
+    int keys_per_wave;     // multiple of 32
+    int n_runs;            // runs per (sequence, kv head)
+    float* part_o;         // [B][Hkv][n_runs][rows_pad][128]
+    float* part_ml;        // [B][Hkv][n_runs][rows_pad][2]
+    int rows_pad;          // multiple of 16, >= k*G
+    float scale_log2e;
+};
+
+// One wavefront: keys [run*keys_per_wave, +keys_per_wave) of (sequence b, kv head hk) against the
+// query rows [row0, row0 + 16*RT) of that kv head (row r = t*G + head-in-group).  S^T = K Q^T puts
+// keys on the M side, so the 8 scores a lane holds (tile 0 keys 4g..4g+3, tile 1 keys 4g..4g+3 of
+// row c) are exactly its share of the P^T operand of O^T = V^T P^T.
+template <int RT>
+__device__ __forceinline__ void attn_run(const AttnArgs& p, int b, int hk, int run, int row0, int lane) {
+    const int c = lane & 15, g = lane >> 4;
+    const int L = p.len[b];
+    const int nkeys = min(L + p.k, p.g.S);
+    const int rows = p.k * p.G;
+    const int j_begin = run * p.keys_per_wave;
+    const int j_end = min(j_begin + p.keys_per_wave, nkeys);
+    const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad + row0;
+
+    bf16x8 qh[RT][4], ql[RT][4];
+    uint64_t vis[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int r = row0 + rt * 16 + c;
+        const int t = r / p.G, hq = hk * p.G + r % p.G;
+        vis[rt] = 0;
+        if (r < rows) vis[rt] = p.mask ? p.mask[t] : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1ull));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (r < rows) {
+                const float* src = p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8;
+                const float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
+                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+                v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+            }
+            split8(v, &qh[rt][j], &ql[rt][j]);
+        }
+    }
+    f32x4 o[8][RT];
+#pragma unroll
+    for (int h = 0; h < 8; ++h)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) o[h][rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float mrow[RT], lrow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        mrow[rt] = -INFINITY;
+        lrow[rt] = 0.f;
+    }
+    const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
+    const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
+
+    for (int j0 = j_begin; j0 < j_end; j0 += 32) {
+        f32x4 s[2][RT];
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl) {
+            bf16x8 kf[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                kf[j] = __builtin_bit_cast(bf16x8, *(const uint4*)(kbase + (size_t)(j0 + tl * 16 + c) * 128 + j * 32 + g * 8));
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    a = mfma16(kf[j], qh[rt][j], a);
+                    a = mfma16(kf[j], ql[rt][j], a);
+                }
+                s[tl][rt] = a;
+            }
+        }
+        bf16x8 vf[8];
+        const bf16_t* vblk = vbase + (size_t)(j0 >> 6) * (128 * 64) + (j0 & 32) + g * 8;
+#pragma unroll
+        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, *(const uint4*)(vblk + (size_t)(h * 16 + c) * 64));
+
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int key = j0 + tl * 16 + g * 4 + i;
+                    bool ok = key < L;
+                    if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
+                    const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
+                    s[tl][rt][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+            const float mnew = fmaxf(mrow[rt], mx);
+            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            const float alpha = exp2f(mrow[rt] - muse);      // 0 when mrow was -inf
+            mrow[rt] = mnew;
+            float pv[8];
+            float ps = 0.f;
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float e = exp2f(s[tl][rt][i] - muse);
+                    pv[tl * 4 + i] = e;
+                    ps += e;
+                }
+            lrow[rt] = lrow[rt] * alpha + ps;
+            bf16x8 ph, pl;
+            split8(pv, &ph, &pl);
+#pragma unroll
+            for (int h = 0; h < 8; ++h) {
+                o[h][rt] *= alpha;
+                o[h][rt] = mfma16(vf[h], ph, o[h][rt]);
+                o[h][rt] = mfma16(vf[h], pl, o[h][rt]);
+            }
+        }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float l = lrow[rt];
+        l += __shfl_xor(l, 16, WAVE);
+        l += __shfl_xor(l, 32, WAVE);
+        const int r = rt * 16 + c;
+        if (g == 0) {
+            p.part_ml[(unit + r) * 2] = mrow[rt];
+            p.part_ml[(unit + r) * 2 + 1] = l;
+        }
+#pragma unroll
+        for (int h = 0; h < 8; ++h) *(f32x4*)(p.part_o + (unit + r) * 128 + h * 16 + g * 4) = o[h][rt];
+    }
+}
+
+// Merge of the key runs of one query row r of (sequence b, kv head hk):
+//   out[m][hq*128 + e] = sum_runs 2^(m_run - M) O_run[e] / sum_runs 2^(m_run - M) l_run
+// Called by a whole workgroup of at least 128 threads (all of them reach the barriers); threads
+// 0..127 each own one feature.  wgt: MAX_RUNS floats of LDS, red: 4 floats of LDS.
+__device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const float* __restrict__ part_o,
+                                                 const float* __restrict__ part_ml, int n_runs, int rows_pad, int k,
+                                                 int G, int Hq, int Hkv, int r, int hk, int b, float* wgt, float* red) {
+    const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
+    const bool on = e < 128;
+    const size_t u0 = (size_t)(b * Hkv + hk) * n_runs;
+    float mx = -INFINITY;
+    if (on)
+        for (int s = e; s < n_runs; s += 128) {
+            const float m = part_ml[((u0 + s) * rows_pad + r) * 2];
+            wgt[s] = m;
+            mx = fmaxf(mx, m);
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+    if (on && lane == 0) red[wave] = mx;
+    __syncthreads();
+    const float M = fmaxf(red[0], red[1]);
+    float den = 0.f;
+    if (on)
+        for (int s = e; s < n_runs; s += 128) {
+            const float m = wgt[s];
+            const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);
+            wgt[s] = w;
+            den += w * part_ml[((u0 + s) * rows_pad + r) * 2 + 1];
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o, WAVE);
+    if (on && lane == 0) red[2 + wave] = den;
+    __syncthreads();
+    if (on) {
+        den = red[2] + red[3];
+        float num = 0.f;
+        const float* po = part_o + (u0 * rows_pad + r) * 128 + e;
+        const size_t stride = (size_t)rows_pad * 128;
+#pragma unroll 8
+        for (int s = 0; s < n_runs; ++s) num += wgt[s] * po[s * stride];
+        const int t = r / G, hq = hk * G + r % G;
+        out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = num / den;
+    }
+    __syncthreads();   // wgt / red may be reused by the caller's next row
+}

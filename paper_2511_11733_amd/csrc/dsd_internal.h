@@ -89,6 +89,12 @@ struct dsd_ctx {
     bool force_simple;  // DSD_PATH=simple: run the generic kernels also for bf16 models
     bool prof_on;
     std::vector<ProfRec> prof;
+    // persistent stage kernel: grid-barrier words and their bookkeeping
+    bool no_persist;               // true unless DSD_PERSIST=1: run one kernel per step
+    int n_cu;
+    unsigned* bar_dev;             // [256] per-workgroup barrier flags, [256] abort word
+    unsigned bar_base;             // barriers passed so far
+    int* abort_host;               // pinned
 };
 
 // Brackets the launches of one scope with a pair of events when profiling is on.
@@ -123,6 +129,7 @@ struct dsd_weights {
     void* gf;
     void* lm;
     void* lm_t;
+    void* layer_table;  // device array of per-layer pointers for the persistent kernel
     std::vector<LayerW> layers;
     std::vector<void*> allocs;
 };
@@ -163,6 +170,22 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors);
 int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
                       const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B,
                       int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
+// persistent form for up to 16 rows (dsd_stage_persist.hip)
+int persist_supported(const dsd_model_desc* d);
+int persist_build_layer_table(dsd_weights* w);
+int persist_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
+                         const uint64_t* tree_mask, const int32_t* depth, int B, int k, void* hidden_out,
+                         float* logits, int64_t logits_seq_stride);
+// weight-streaming GEMMs for 17..128 rows (dsd_gemm_tiled.hip)
+int tiled_supported(const dsd_model_desc* d);
+int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, const float* a, float* x, int M, int N, int K);
+int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* acc, int M, int N, int K,
+                   float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len, const int32_t* depth, int k,
+                   int Hq, float eps, float theta);
+int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* h, int M, int F, int K,
+                      float eps);
+int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* logits, int M, int V,
+                      int K, float eps, int rows_per_seq, int64_t seq_stride);
 // KV utilities (dsd_kv.hip)
 int kv_import_launch(dsd_ctx* ctx, dsd_kv* kv, int layer, const void* k, const void* v, int B, int n_slots);
 int kv_export_launch(dsd_ctx* ctx, const dsd_kv* kv, int layer, int first, int n, int B, void* k, void* v);

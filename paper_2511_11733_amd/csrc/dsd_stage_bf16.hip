@@ -15,40 +15,9 @@
 //     the extra MFMA work is free while the pass is bandwidth bound;
 //   * attention computes S^T = K Q^T so that the scores a lane holds are exactly the P^T operand
 //     of O^T = V^T P^T; V is cached transposed for that product (see KvGeom).
-#include "dsd_internal.h"
+#include <stdlib.h>
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-
-#define WAVE 64
-
-__device__ inline unsigned pack_bf16(float a, float b) {
-    f32x2 v = {a, b};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
-}
-__device__ inline bf16x8 pack8(const float* f) {
-    uint4 u = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
-    return __builtin_bit_cast(bf16x8, u);
-}
-// v = hi + lo with both halves bf16 (lo carries the rounding remainder of hi)
-__device__ inline void split8(const float* v, bf16x8* hi, bf16x8* lo) {
-    uint4 hu = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
-    const unsigned hw[4] = {hu.x, hu.y, hu.z, hu.w};
-    float r[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        r[2 * i] = v[2 * i] - __uint_as_float(hw[i] << 16);
-        r[2 * i + 1] = v[2 * i + 1] - __uint_as_float(hw[i] & 0xFFFF0000u);
-    }
-    *hi = __builtin_bit_cast(bf16x8, hu);
-    *lo = pack8(r);
-}
-__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
-    // D[4*(lane/16)+i][lane%16] += sum_k A[lane%16][8*(lane/16)+k] * B[8*(lane/16)+k][lane%16]
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
+#include "dsd_bf16_dev.h"
 
 // ============================================================================ weight tiling
 // dst fragment (nt, ks): lane l holds W[nt*16 + l%16][ks*32 + (l/16)*8 .. +8]
@@ -117,57 +86,18 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors) 
         DSD_TRY(dev_alloc(w, (size_t)D.vocab * d * 2, &w->lm_t));
         DSD_TRY(tile_into(ctx, w->lm_t, 0, tensors[t + 1], D.vocab, d));
     }
+    if (persist_supported(&D)) DSD_TRY(persist_build_layer_table(w));
     return DSD_OK;
 }
 
 // ============================================================================ skinny GEMM
-enum { A_F32_GAIN = 0, A_F32 = 1 };
-enum { EPI_QKV = 0, EPI_SWIGLU = 1, EPI_RESID = 2, EPI_LOGITS = 3 };
-
-struct GemmArgs {
-    const uint4* Wt;      // tiled weights
-    int KS;               // K / 32
-    int M;                // rows in use
-    // A operand
-    const float* x;       // [M][K] fp32 residual stream          (A_F32_GAIN)
-    const bf16_t* gain;   // [K]                                   (A_F32_GAIN)
-    const float* a;       // [M][K] fp32 activations               (A_F32)
-    float eps;
-    // epilogues
-    float* xout;          // EPI_RESID: [M][N] fp32, updated in place
-    int N;
-    float* hout;          // EPI_SWIGLU: [M][F]
-    int up_tile_off;      // EPI_SWIGLU: F/16
-    float* logits;        // EPI_LOGITS
-    int rows_per_seq;
-    int64_t seq_stride;
-    // EPI_QKV
-    float* q;             // [M][Hq*hd] rotated queries, fp32
-    bf16_t* kc;           // this layer's K cache
-    bf16_t* vc;           // this layer's V cache
-    KvGeom g;
-    const int32_t* len;
-    const int32_t* depth;
-    int k;
-    int Hq;
-    float theta;
-};
-
 template <int MT, int NT, int AMODE, int EPI, int NW>
 __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = NW;
     const int c = lane & 15, g = lane >> 4;
     int tile[NT];
-    if (EPI == EPI_QKV) {               // column tiles (t, t+4) of one head: the rotary pair
-        tile[0] = (blockIdx.x >> 2) * 8 + (blockIdx.x & 3);
-        if (NT > 1) tile[NT - 1] = tile[0] + 4;
-    } else if (EPI == EPI_SWIGLU) {     // gate tile and the matching up tile
-        tile[0] = blockIdx.x;
-        if (NT > 1) tile[NT - 1] = blockIdx.x + p.up_tile_off;
-    } else {
-        for (int i = 0; i < NT; ++i) tile[i] = blockIdx.x * NT + i;
-    }
+    unit_tiles<NT, EPI>(p, blockIdx.x, tile);
     const int K = p.KS * 32;
     f32x4 acc[MT][NT];
 #pragma unroll
@@ -260,56 +190,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
                 rstd[i] = 1.0f / sqrtf(s / (float)K + p.eps);
             }
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = mt * 16 + g * 4 + i;      // output row of element i
-            if (m >= p.M) continue;
-            if (EPI == EPI_RESID) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    float* dst = p.xout + (size_t)m * p.N + tile[nt] * 16 + c;
-                    *dst += o[nt][i];
-                }
-            } else if (EPI == EPI_LOGITS) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    p.logits[(size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N +
-                             tile[nt] * 16 + c] = o[nt][i] * rstd[i];
-            } else if (EPI == EPI_SWIGLU) {
-                const float gate = o[0][i] * rstd[i], up = o[NT - 1][i] * rstd[i];
-                const float h = gate / (1.0f + __expf(-gate)) * up;
-                p.hout[(size_t)m * p.N + tile[0] * 16 + c] = h;
-            } else {  // EPI_QKV
-                const int hd = 128, half = 64;
-                const int head = tile[0] >> 3;                 // 8 column tiles per head
-                const int e = (tile[0] & 7) * 16 + c;          // < 64: first element of the rotary pair
-                const float lo = o[0][i] * rstd[i], hi = o[NT - 1][i] * rstd[i];
-                const int b = m / p.k, t = m % p.k;
-                const int L = p.len[b];
-                const int slot = L + t;
-                if (head < p.Hq + p.g.Hkv) {
-                    const double pos = (double)(L + (p.depth ? p.depth[t] : t));
-                    const double inv = pow((double)p.theta, -2.0 * (double)e / (double)hd);
-                    double sn, cs;
-                    sincos(pos * inv, &sn, &cs);
-                    const float r0 = lo * (float)cs - hi * (float)sn;
-                    const float r1 = hi * (float)cs + lo * (float)sn;
-                    if (head < p.Hq) {
-                        float* dst = p.q + ((size_t)m * p.Hq + head) * hd;
-                        dst[e] = r0;
-                        dst[e + half] = r1;
-                    } else if (slot < p.g.S) {
-                        const int hk = head - p.Hq;
-                        p.kc[kv_k_off(p.g, b, hk, slot, e)] = f32_to_bf16(r0);
-                        p.kc[kv_k_off(p.g, b, hk, slot, e + half)] = f32_to_bf16(r1);
-                    }
-                } else if (slot < p.g.S) {
-                    const int hk = head - p.Hq - p.g.Hkv;
-                    p.vc[kv_v_off(p.g, b, hk, slot, e)] = f32_to_bf16(lo);
-                    p.vc[kv_v_off(p.g, b, hk, slot, e + half)] = f32_to_bf16(hi);
-                }
-            }
-        }
+        gemm_epilogue<NT, EPI>(p, tile, o, rstd, mt, c, g);
     }
 }
 
@@ -327,7 +208,12 @@ template <int NT, int AMODE, int EPI>
 static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
     const int mt = (p.M + 15) / 16;
     switch (mt) {
-        case 1: return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
+        case 1: {
+            static const int nw_env = getenv("DSD_NW") ? atoi(getenv("DSD_NW")) : 16;
+            if (nw_env == 8) return launch_gemm<1, NT, AMODE, EPI, 8>(s, p, n_blocks);
+            if (nw_env == 4) return launch_gemm<1, NT, AMODE, EPI, 4>(s, p, n_blocks);
+            return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
+        }
         case 2: return launch_gemm<2, NT, AMODE, EPI, 16>(s, p, n_blocks);
         case 3: return launch_gemm<3, NT, AMODE, EPI, 8>(s, p, n_blocks);
         case 4: return launch_gemm<4, NT, AMODE, EPI, 8>(s, p, n_blocks);
@@ -338,200 +224,24 @@ static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
 }
 
 // ============================================================================ attention
-// One wavefront owns a run of keys of one (sequence, kv head) and all its k*G query rows
-// (row r = t*G + head-in-group).  Partial (max, sum, O) per run go to scratch; attn_combine
-// merges the runs.
-struct AttnArgs {
-    const float* q;        // [M][Hq*hd] fp32
-    const bf16_t* kc;
-    const bf16_t* vc;
-    KvGeom g;
-    const int32_t* len;
-    const uint64_t* mask;
-    int k, Hq, G;
-    int keys_per_wave;     // multiple of 32
-    int n_runs;            // runs per (sequence, kv head)
-    float* part_o;         // [B][Hkv][n_runs][rows_pad][128]
-    float* part_ml;        // [B][Hkv][n_runs][rows_pad][2]
-    int rows_pad;          // RT*16
-    float scale_log2e;
-};
-
+// One wavefront owns a run of keys of one (sequence, kv head) and all its k*G query rows; the
+// partial (max, sum, O) of every run goes to scratch and attn_combine_kernel merges the runs.
+// blockIdx.x = (group of 4 runs) * n_rowgroups + rowgroup; a row group is RT tiles of 16 query rows.
 template <int RT>
-__global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p) {
+__global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p, int n_rowgroups) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    const int run = blockIdx.x * 4 + wave, hk = blockIdx.y, b = blockIdx.z;
+    const int rg = blockIdx.x % n_rowgroups;
+    const int run = (blockIdx.x / n_rowgroups) * 4 + wave, hk = blockIdx.y, b = blockIdx.z;
     if (run >= p.n_runs) return;
-    const int L = p.len[b];
-    const int nkeys = min(L + p.k, p.g.S);
-    const int rows = p.k * p.G;
-    const int j_begin = run * p.keys_per_wave;
-    const int j_end = min(j_begin + p.keys_per_wave, nkeys);
-    const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad;
-
-    // Q^T fragments: lane (row c of tile rt, k-group g) holds q[row][32j + 8g .. +8], as hi + lo
-    bf16x8 qh[RT][4], ql[RT][4];
-    uint64_t vis[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        const int r = rt * 16 + c;
-        const int t = r / p.G, hq = hk * p.G + r % p.G;
-        vis[rt] = 0;
-        if (r < rows) vis[rt] = p.mask ? p.mask[t] : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1ull));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if (r < rows) {
-                const float* src = p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8;
-                const float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
-                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
-                v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
-            }
-            split8(v, &qh[rt][j], &ql[rt][j]);
-        }
-    }
-    f32x4 o[8][RT];
-#pragma unroll
-    for (int h = 0; h < 8; ++h)
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) o[h][rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float mrow[RT], lrow[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        mrow[rt] = -INFINITY;
-        lrow[rt] = 0.f;
-    }
-    const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
-    const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
-
-    for (int j0 = j_begin; j0 < j_end; j0 += 32) {
-        // S^T tiles: keys on the M side.  Lane (key c, group g) of tile tl holds K[j0+16*tl+c][32j+8g..]
-        f32x4 s[2][RT];
-#pragma unroll
-        for (int tl = 0; tl < 2; ++tl) {
-            bf16x8 kf[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                kf[j] = __builtin_bit_cast(bf16x8, *(const uint4*)(kbase + (size_t)(j0 + tl * 16 + c) * 128 + j * 32 + g * 8));
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    a = mfma16(kf[j], qh[rt][j], a);
-                    a = mfma16(kf[j], ql[rt][j], a);
-                }
-                s[tl][rt] = a;
-            }
-        }
-        // V^T fragments: lane (feature 16*h + c, group g) holds 8 slots in the order the scores
-        // above are held: tile 0 keys 4g..4g+3, tile 1 keys 4g..4g+3
-        bf16x8 vf[8];
-        const bf16_t* vblk = vbase + (size_t)(j0 >> 6) * (128 * 64) + (j0 & 32) + g * 8;
-#pragma unroll
-        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, *(const uint4*)(vblk + (size_t)(h * 16 + c) * 64));
-
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            // mask + running maximum (lane c = query row; its 8 scores are keys 16*tl + 4g + i)
-            float mx = -INFINITY;
-#pragma unroll
-            for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = j0 + tl * 16 + g * 4 + i;
-                    bool ok = key < L;
-                    if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
-                    const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
-                    s[tl][rt][i] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-            const float mnew = fmaxf(mrow[rt], mx);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = exp2f(mrow[rt] - muse);      // 0 when mrow was -inf
-            mrow[rt] = mnew;
-            float pv[8];
-            float ps = 0.f;
-#pragma unroll
-            for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float e = exp2f(s[tl][rt][i] - muse);
-                    pv[tl * 4 + i] = e;
-                    ps += e;
-                }
-            lrow[rt] = lrow[rt] * alpha + ps;
-            bf16x8 ph, pl;
-            split8(pv, &ph, &pl);
-#pragma unroll
-            for (int h = 0; h < 8; ++h) {
-                o[h][rt] *= alpha;
-                o[h][rt] = mfma16(vf[h], ph, o[h][rt]);
-                o[h][rt] = mfma16(vf[h], pl, o[h][rt]);
-            }
-        }
-    }
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        float l = lrow[rt];
-        l += __shfl_xor(l, 16, WAVE);
-        l += __shfl_xor(l, 32, WAVE);
-        const int r = rt * 16 + c;
-        if (g == 0) {
-            p.part_ml[(unit + r) * 2] = mrow[rt];
-            p.part_ml[(unit + r) * 2 + 1] = l;
-        }
-        // O^T tile h: lane holds features 16h + 4g + i of row c
-#pragma unroll
-        for (int h = 0; h < 8; ++h) *(f32x4*)(p.part_o + (unit + r) * 128 + h * 16 + g * 4) = o[h][rt];
-    }
+    attn_run<RT>(p, b, hk, run, rg * RT * 16, lane);
 }
 
-// out[m][hq*128 + e] = sum_runs 2^(m_run - M) O_run[e] / sum_runs 2^(m_run - M) l_run
-// One block of 128 threads per query row: the run weights are formed once in LDS (threads over
-// runs), then every thread sums its feature over the runs with independent loads.
-#define MAX_RUNS 512
 __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ out, const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml, int n_runs, int rows_pad,
                                                           int k, int G, int Hq, int Hkv) {
     __shared__ float wgt[MAX_RUNS];
     __shared__ float red[4];
-    const int r = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-    const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
-    const size_t u0 = (size_t)(b * Hkv + hk) * n_runs;
-    float mx = -INFINITY;
-    for (int s = e; s < n_runs; s += 128) {
-        const float m = part_ml[((u0 + s) * rows_pad + r) * 2];
-        wgt[s] = m;
-        mx = fmaxf(mx, m);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
-    if (lane == 0) red[wave] = mx;
-    __syncthreads();
-    const float M = fmaxf(red[0], red[1]);
-    float den = 0.f;
-    for (int s = e; s < n_runs; s += 128) {
-        const float m = wgt[s];
-        const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);
-        wgt[s] = w;
-        den += w * part_ml[((u0 + s) * rows_pad + r) * 2 + 1];
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o, WAVE);
-    if (lane == 0) red[2 + wave] = den;
-    __syncthreads();
-    den = red[2] + red[3];
-    float num = 0.f;
-    const float* po = part_o + (u0 * rows_pad + r) * 128 + e;
-    const size_t stride = (size_t)rows_pad * 128;
-#pragma unroll 8
-    for (int s = 0; s < n_runs; ++s) num += wgt[s] * po[s * stride];
-    const int t = r / G, hq = hk * G + r % G;
-    out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = num / den;
+    attn_combine_row(out, part_o, part_ml, n_runs, rows_pad, k, G, Hq, Hkv, blockIdx.x, blockIdx.y, blockIdx.z, wgt, red);
 }
 
 // ============================================================================ small kernels
@@ -554,12 +264,18 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const int M = B * k, d = D.d_model, Hq = D.n_q_heads, Hkv = D.n_kv_heads, hd = D.head_dim, F = D.d_ffn;
     const int G = Hq / Hkv, qd = Hq * hd;
     if (M > 128) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: B*k = %d rows exceed 128", M);
+    if (hidden_in && M <= 8 && w->layer_table && !ctx->no_persist) {
+        const int rc = persist_stage_verify(ctx, w, kv, hidden_in, tree_mask, depth, B, k, hidden_out, logits, logits_seq_stride);
+        if (rc != DSD_EUNSUPPORTED) return rc;      // else: one kernel per step
+    }
     if (!hidden_in) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: first-node (embedding) blocks run on the generic path");
     const int rows = k * G;
-    int RT = (rows + 15) / 16;      // row tiles, rounded up to a size the kernel is built for
-    if (RT == 5) RT = 6;
-    if (RT == 7) RT = 8;
-    if (RT > 8) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 128", rows);
+    const int n_rt = (rows + 15) / 16;       // 16-row tiles of query rows per kv head
+    if (n_rt > 8) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 128", rows);
+    // a wave takes at most 4 row tiles (registers); more rows are split into row groups
+    const int n_rg = (n_rt + 3) / 4;
+    const int RT = (n_rt + n_rg - 1) / n_rg;
+    const bool tiled = M > 16 && tiled_supported(&D) && !getenv("DSD_NO_TILED");
 
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
@@ -571,9 +287,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const int keys_per_wave = (int)kpw;
     int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
     if (n_runs > MAX_RUNS) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: %d key runs", n_runs);
-    const int rows_pad = RT * 16;
+    const int rows_pad = RT * n_rg * 16;
 
-    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 +
+    const int n_qkv = (Hq + 2 * Hkv) * hd;
+    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + (size_t)M * n_qkv * 4 +
                   (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
     WsBump ws{ctx->ws, 0};
@@ -583,7 +300,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     float* h = ws.take<float>((size_t)M * F);
     float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
     float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
+    float* qkv_acc = ws.take<float>((size_t)M * n_qkv);
     hipStream_t s = ctx->stream;
+    // split-K partial sums of the QKV projection meet here; every layer leaves it cleared again
+    if (tiled) DSD_HIP(hipMemsetAsync(qkv_acc, 0, (size_t)M * n_qkv * 4, s));
 
     const size_t nx = (size_t)M * d;
     {
@@ -604,24 +324,26 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.theta = D.rope_theta;
         {
             ProfScope ps(ctx, DSD_KC_QKV);
-            DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
+            if (tiled)
+                DSD_TRY(tiled_gemm_qkv(ctx, W.qkv_t, x, (const bf16_t*)W.g1, qkv_acc, M, n_qkv, d, q, kc, vc, g,
+                                       kv->len_dev, depth, k, Hq, D.rms_eps, D.rope_theta));
+            else
+                DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
         }
         // attention
         AttnArgs t;
         t.q = q; t.kc = kc; t.vc = vc; t.g = g; t.len = kv->len_dev; t.mask = tree_mask; t.k = k; t.Hq = Hq; t.G = G;
         t.keys_per_wave = keys_per_wave; t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
         t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
-        dim3 ag((n_runs + 3) / 4, Hkv, B);
+        dim3 ag(((n_runs + 3) / 4) * n_rg, Hkv, B);
         {
-        ProfScope ps(ctx, DSD_KC_ATTN);
-        switch (RT) {
-            case 1: attn_partial_kernel<1><<<ag, 256, 0, s>>>(t); break;
-            case 2: attn_partial_kernel<2><<<ag, 256, 0, s>>>(t); break;
-            case 3: attn_partial_kernel<3><<<ag, 256, 0, s>>>(t); break;
-            case 4: attn_partial_kernel<4><<<ag, 256, 0, s>>>(t); break;
-            case 6: attn_partial_kernel<6><<<ag, 256, 0, s>>>(t); break;
-            default: attn_partial_kernel<8><<<ag, 256, 0, s>>>(t); break;
-        }
+            ProfScope ps(ctx, DSD_KC_ATTN);
+            switch (RT) {
+                case 1: attn_partial_kernel<1><<<ag, 256, 0, s>>>(t, n_rg); break;
+                case 2: attn_partial_kernel<2><<<ag, 256, 0, s>>>(t, n_rg); break;
+                case 3: attn_partial_kernel<3><<<ag, 256, 0, s>>>(t, n_rg); break;
+                default: attn_partial_kernel<4><<<ag, 256, 0, s>>>(t, n_rg); break;
+            }
         }
         {
         ProfScope ps(ctx, DSD_KC_ATTN_COMBINE);
@@ -632,7 +354,8 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
-            DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, att, x, M, d, qd));
+            else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
         a = GemmArgs();
@@ -640,14 +363,16 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.hout = h; a.N = F; a.up_tile_off = F / 16;
         {
             ProfScope ps(ctx, DSD_KC_GATEUP);
-            DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
+            if (tiled) DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, h, M, F, d, D.rms_eps));
+            else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
         }
         // x += h Wd^T
         a = GemmArgs();
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
-            DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, h, x, M, d, F));
+            else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
     }
     if (hidden_out) {
@@ -659,7 +384,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)w->lm_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)w->gf;
         a.logits = logits; a.N = D.vocab; a.rows_per_seq = k; a.seq_stride = logits_seq_stride;
         ProfScope ps(ctx, DSD_KC_HEAD);
-        DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
+        if (tiled)
+            DSD_TRY(tiled_gemm_logits(ctx, w->lm_t, x, (const bf16_t*)w->gf, logits, M, D.vocab, d, D.rms_eps, k,
+                                      logits_seq_stride));
+        else
+            DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
     }
     DSD_HIP(hipGetLastError());
     return DSD_OK;
