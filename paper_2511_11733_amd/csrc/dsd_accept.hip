@@ -4,8 +4,12 @@
 // The vocabulary is cut into slices of SLICE ids; every vocabulary-wide quantity is reduced per
 // slice by one workgroup (wavefront shuffles + one LDS hop), the few per-slice partials are
 // merged by a small second kernel, and only those partials ever reach memory: no probability
-// row is materialised.  All arithmetic is fp64 (MI355X runs fp64 vector math at full rate), so
-// the integer outputs follow an fp64 reference except at exact ties.
+// row is materialised.  Every quantity that decides something by itself (a drafted token's own
+// probabilities, the accept test, all sums and cumulative sums) is fp64; the per-id terms of the
+// vocabulary-wide sums are evaluated in fp32 (relative error below 1e-6, independent between ids,
+// so that a sum over thousands of ids is good to about 1e-9) and accumulated in fp64.  The
+// integer outputs therefore follow an fp64 reference except within the near-tie bands the tests
+// state.
 //
 //   row_stats   per (sequence, row, slice): max and sum-exp of logits/T, top-M candidates of the
 //               logits row and of the draft row
@@ -94,6 +98,17 @@ __device__ inline double soft_weight(double ln_pt, double q, double tau) {
     return exp(e);
 }
 
+// the same weight for one id of a vocabulary-wide sum: fp32 terms (see the header)
+__device__ inline float soft_weight_f(float ln_pt, float q, float tau) {
+    const float a = 1.0f - tau;
+    float e = (a == 0.0f) ? 0.0f : a * ln_pt;
+    if (tau != 0.0f) {
+        if (q <= 0.0f) return 0.0f;
+        e += tau * logf(q);
+    }
+    return expf(e);
+}
+
 struct AcceptWs {
     double* part_m;     // [B][R][S]
     double* part_s;     // [B][R][S]
@@ -133,13 +148,13 @@ row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
         if (in) mx = fmax(mx, (double)lv[j] * inv_temp);
     }
     mx = block_max_d(mx, shd);
-    double sum = 0.0;
+    float fsum = 0.f;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = base + threadIdx.x + j * TPB;
-        if (i < V) sum += exp((double)lv[j] * inv_temp - mx);
+        if (i < V) fsum += expf((float)((double)lv[j] * inv_temp - mx));
     }
-    sum = block_sum_d(sum, shd);
+    double sum = block_sum_d((double)fsum, shd);
     const size_t pidx = ((size_t)b * R + r) * S + s;
     if (threadIdx.x == 0) {
         ws.part_m[pidx] = mx;
@@ -239,22 +254,27 @@ node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
         ws.node_key[nidx] = key ? 1 : 0;
     }
     if (tau == 0.0) return;     // P~ = P_t, Z~ = 1
-    double z = 0.0;
+    float fz = 0.f;
     const int base = s * SLICE;
+    const float ftau = (float)tau;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = base + threadIdx.x + j * TPB;
-        if (i < V) z += soft_weight((double)logits[row + i] * inv_temp - lse, (double)qp[row + i], tau);
+        if (i < V) fz += soft_weight_f((float)((double)logits[row + i] * inv_temp - lse), qp[row + i], ftau);
     }
-    z = block_sum_d(z, shd);
+    const double z = block_sum_d((double)fz, shd);
     if (threadIdx.x == 0) ws.part_z[nidx * S + s] = z;
 }
 
-__global__ void decide_kernel(const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws,
-                              dsd_accept_params prm, int B, int k, int S, int32_t* __restrict__ accepted_len,
-                              int32_t* __restrict__ accepted_path, dsd_accept_stats st) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;   // one thread per sequence
-    if (b >= B) return;
+// One wavefront per sequence: the lanes share the sums over the slices, every lane then takes the
+// same (few, sequential) decisions and lane 0 writes them.
+__global__ void __launch_bounds__(WAVE)
+decide_kernel(const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws,
+              dsd_accept_params prm, int B, int k, int S, int32_t* __restrict__ accepted_len,
+              int32_t* __restrict__ accepted_path, dsd_accept_stats st) {
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const bool writer = lane == 0;
     const int R = k + 1;
     int par[DSD_MAX_K + 1], dep[DSD_MAX_K + 1];
     bool ok[DSD_MAX_K + 1], acc[DSD_MAX_K + 1];
@@ -270,7 +290,8 @@ __global__ void decide_kernel(const int32_t* __restrict__ parent, const float* _
         double z = 1.0;
         if (tau != 0.0) {
             z = 0.0;
-            for (int s = 0; s < S; ++s) z += ws.part_z[nidx * S + s];
+            for (int s = lane; s < S; s += WAVE) z += ws.part_z[nidx * S + s];
+            z = wave_sum_d(z);
         }
         zt[i] = z;
         const double q_y = ws.node_q[nidx];
@@ -278,10 +299,12 @@ __global__ void decide_kernel(const int32_t* __restrict__ parent, const float* _
         const double u = (double)uniforms[(size_t)b * R + i];
         acc[i] = u * q_y < p_y;
         ok[i] = acc[i] && ok[p];
-        if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
-        if (st.node_accept) st.node_accept[nidx] = acc[i] ? 1 : 0;
-        if (st.ratio) st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
-        if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
+        if (writer) {
+            if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
+            if (st.node_accept) st.node_accept[nidx] = acc[i] ? 1 : 0;
+            if (st.ratio) st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
+            if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
+        }
     }
     int vstar = 0;
     if (prm.tree_mode == DSD_TREE_FIRST_ACCEPTED) {
@@ -297,6 +320,7 @@ __global__ void decide_kernel(const int32_t* __restrict__ parent, const float* _
             if (ok[i] && dep[i] > dep[vstar]) vstar = i;
     }
     const int a = dep[vstar];
+    if (!writer) return;
     accepted_len[b] = a;
     if (accepted_path) {
         for (int j = 0; j < k; ++j) accepted_path[(size_t)b * k + j] = -1;
@@ -321,14 +345,14 @@ __global__ void decide_kernel(const int32_t* __restrict__ parent, const float* _
 __device__ inline void draw_weight(const float* __restrict__ logits, const float* __restrict__ qp, size_t row, int i,
                                    double inv_temp, double lse, int mode, double tau, double z, double* w,
                                    double* p) {
-    const double ln_pt = (double)logits[row + i] * inv_temp - lse;
+    const float ln_pt = (float)((double)logits[row + i] * inv_temp - lse);
     if (mode == 0) {
-        *p = exp(ln_pt);
+        *p = (double)expf(ln_pt);
         *w = *p;
     } else {
-        const double q = (double)qp[row + i];
-        *p = soft_weight(ln_pt, q, tau) / z;
-        *w = fmax(*p - q, 0.0);
+        const float q = qp[row + i];
+        *p = (double)soft_weight_f(ln_pt, q, (float)tau) / z;
+        *w = fmax(*p - (double)q, 0.0);
     }
 }
 
@@ -372,35 +396,55 @@ draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     const double tau = ws.draw_tau[b], z = ws.draw_z[b];
     const size_t row = ((size_t)b * R + r) * V;
     const double lse = ws.row_lse[(size_t)b * R + r];
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < WAVE) {
+        // wave 0: total mass, then the first slice whose inclusive cumulative mass exceeds u0 * total
+        const int lane = threadIdx.x;
         const double* part = ws.part_res + (size_t)b * S;
         double total = 0.0;
-        for (int s = 0; s < S; ++s) total += part[s];
+        for (int s = lane; s < S; s += WAVE) total += part[s];
+        total = wave_sum_d(total);
         int fb = 0;
         if (!(total > 0.0)) {      // positive part empty: draw from P itself
             fb = 1;
             part = ws.part_fb + (size_t)b * S;
             total = 0.0;
-            for (int s = 0; s < S; ++s) total += part[s];
+            for (int s = lane; s < S; s += WAVE) total += part[s];
+            total = wave_sum_d(total);
         }
         const double target = (double)uniforms[(size_t)b * R] * total;
-        double cum = 0.0;
+        double carry = 0.0;
         int pick = -1, last_pos = 0;
-        for (int s = 0; s < S; ++s) {
-            if (part[s] > 0.0) last_pos = s;
-            if (pick < 0 && cum + part[s] > target) {
-                pick = s;
-                sh_before = cum;
+        double before = 0.0;
+        for (int s0 = 0; s0 < S; s0 += WAVE) {
+            const int s = s0 + lane;
+            const double v = s < S ? part[s] : 0.0;
+            double inc = v;                                   // inclusive scan over the 64 lanes
+#pragma unroll
+            for (int o = 1; o < WAVE; o <<= 1) {
+                const double t = __shfl_up(inc, o, WAVE);
+                if (lane >= o) inc += t;
             }
-            cum += part[s];
+            inc += carry;
+            const unsigned long long pos = __ballot(v > 0.0);
+            if (pos) last_pos = s0 + 63 - __clzll(pos);
+            const unsigned long long hit = __ballot(s < S && inc > target);
+            if (pick < 0 && hit) {
+                const int l = __ffsll((long long)hit) - 1;
+                pick = s0 + l;
+                before = __shfl(inc - v, l, WAVE);
+            }
+            carry = __shfl(inc, WAVE - 1, WAVE);
         }
-        if (pick < 0) {            // rounding left no crossing: last id with positive weight
-            pick = last_pos;
-            sh_before = -1.0;      // marks "take the last positive id of the slice"
+        if (lane == 0) {
+            if (pick < 0) {        // rounding left no crossing: last id with positive weight
+                pick = last_pos;
+                before = -1.0;     // marks "take the last positive id of the slice"
+            }
+            sh_slice = pick;
+            sh_before = before;
+            sh_fallback = fb;
+            sh_target = target;
         }
-        sh_slice = pick;
-        sh_fallback = fb;
-        sh_target = target;
     }
     __syncthreads();
     const int s = sh_slice, fb = sh_fallback;
@@ -498,7 +542,7 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     row_stats_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp, prm->top_m);
     row_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->top_m);
     node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, *prm, k, V, S, inv_temp);
-    decide_kernel<<<(B + 63) / 64, 64, 0, s>>>(parent, uniforms, ws, *prm, B, k, S, accepted_len, accepted_path, st);
+    decide_kernel<<<B, WAVE, 0, s>>>(parent, uniforms, ws, *prm, B, k, S, accepted_len, accepted_path, st);
     draw_parts_kernel<<<dim3(S, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
     draw_pick_kernel<<<B, TPB, 0, s>>>(logits, draft_probs, uniforms, ws, R, V, S, inv_temp, next_token);
     DSD_HIP(hipGetLastError());

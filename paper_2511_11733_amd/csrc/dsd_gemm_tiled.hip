@@ -7,9 +7,11 @@
 //   * a workgroup of 4 waves owns 128 output columns (each wave two 16-column tiles) over one
 //     contiguous slice of K (grid.y splits K when a matrix has too few column blocks to fill the
 //     chip; partial results are then added atomically into an fp32 buffer);
-//   * the slice is walked in chunks of 128 columns of K: the 256 threads convert the chunk of the
-//     activation rows (gain, hi/lo split) into an LDS panel laid out in A-operand order, double
-//     buffered, one chunk ahead;
+//   * the activations are converted ONCE per GEMM by a small kernel of their own (gain, hi/lo
+//     split, A-operand order, sum of squares for the RMSNorm scale) into a panel in global memory;
+//     doing that inside every workgroup cost more vector ALU time than the matrix cores had work;
+//   * the slice is walked in chunks of 128 columns of K: the 256 threads copy the chunk of the
+//     panel into LDS, double buffered, one chunk ahead;
 //   * every wave keeps its next 32 weight fragments in flight in a register FIFO, issued by hand
 //     (inline asm + explicit s_waitcnt counts, see gload16 / vm_wait) so that neither the panel
 //     prefetch nor the workgroup barriers ever drain the weight stream.
@@ -29,16 +31,16 @@ template <int N>
 __device__ __forceinline__ void vm_wait(u32x4& r) {
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(N));
 }
-// The same pair for values parked in accumulation registers (the panel prefetch: it is only
-// looked at after its wait, and the arch VGPRs are needed for the weight FIFO).  The compiler must
-// never have a reason to copy a register whose load is still in flight, so register pressure is
-// kept away from these values rather than left to the allocator.
-__device__ __forceinline__ void gload16_acc(u32x4& dst, const void* ptr) {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(dst) : "v"(ptr));
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr
+// is wave-uniform and goes through M0).  No register ever holds the data, so nothing the register
+// allocator does can touch a value whose load is still in flight; completion is counted by vmcnt
+// like any other load.
+__device__ __forceinline__ void gload16_lds(unsigned lds_addr, const void* ptr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(ptr) : "memory");
 }
 template <int N>
-__device__ __forceinline__ void vm_wait_acc(u32x4& r) {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+a"(r) : "n"(N));
+__device__ __forceinline__ void vm_wait_all() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
 enum { TE_ATOMIC = 0, TE_SWIGLU = 1, TE_LOGITS = 2 };
@@ -48,8 +50,8 @@ struct TArgs {
     int KS;              // K / 32
     int ks_per_split;    // k-steps per workgroup, multiple of 16
     int M;
-    const float* a;      // [M][K] fp32 activations
-    const bf16_t* gain;  // [K] RMSNorm gain applied to the activations, or NULL
+    const uint4* panel;  // activations as hi/lo bf16 in A-operand order: [2][KS][MT][64] (act_panel_kernel)
+    const float* ssq;    // [16*MT] sum of squares of every activation row, or NULL (no RMSNorm scale)
     float eps;
     float* out;          // TE_ATOMIC: [M][N] fp32, += ;  TE_SWIGLU: h [M][N];  TE_LOGITS: logits
     int N;
@@ -58,62 +60,24 @@ struct TArgs {
     int64_t seq_stride;
 };
 
+// wave w fetches k-step w of a chunk into the panel buffer at LDS byte address buf: entry
+// (ks*MT + mt)*64 + lane of both planes (hi at entry 0, lo at entry 4*MT*64)
 template <int MT>
-__device__ __forceinline__ void tpanel_load(u32x4 (&P)[2 * MT], u32x4& G, const TArgs& p, int K, int k0) {
-    // thread t: k-group q8 = t%16 (8 values) of rows t/16 + 16*i
-    const int q8 = threadIdx.x & 15, r0 = threadIdx.x >> 4;
+__device__ __forceinline__ void tpanel_fetch(const TArgs& p, int ks_abs, unsigned buf) {
+    const int lane = threadIdx.x & 63, ks = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint4* hi = p.panel + ((size_t)(ks_abs + ks) * MT) * 64 + lane;
+    const uint4* lo = hi + (size_t)p.KS * MT * 64;
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-        int r = r0 + 16 * i;
-        r = r < p.M ? r : p.M - 1;                 // a fixed number of loads; rows >= M are never stored
-        const float* src = p.a + (size_t)r * K + k0 + q8 * 8;
-        gload16_acc(P[2 * i], src);
-        gload16_acc(P[2 * i + 1], src + 4);
-    }
-    gload16_acc(G, p.gain ? (const void*)(p.gain + k0 + q8 * 8) : (const void*)(p.a + k0 + q8 * 8));
-}
-
-// YOUNGER: loads of ours issued after the panel loads
-template <int MT, int YOUNGER>
-__device__ __forceinline__ void tpanel_store(u32x4 (&P)[2 * MT], u32x4& G, const TArgs& p, uint4* __restrict__ buf,
-                                             float (&ssq)[MT]) {
-    vm_wait_acc<YOUNGER>(G);
-#pragma unroll
-    for (int r = 0; r < 2 * MT; ++r) asm volatile("" : "+a"(P[r]));
-    float gf[8];
-    if (p.gain) unpack_gain(make_uint4(G.x, G.y, G.z, G.w), gf);
-    const int q8 = threadIdx.x & 15, c = threadIdx.x >> 4;      // row r0 + 16 i = tile i, row-in-tile c
-    const int ks = q8 >> 2, g = q8 & 3;
-    // planes: hi at [0], lo at [4*MT*64]; entry (ks*MT + mt)*64 + g*16 + c
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        float v[8];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            v[j] = __uint_as_float(P[2 * i][j]);
-            v[4 + j] = __uint_as_float(P[2 * i + 1][j]);
-        }
-        if (p.gain) {
-            float q = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                q += v[j] * v[j];
-                v[j] *= gf[j];
-            }
-            ssq[i] += q;
-        }
-        bf16x8 hi, lo;
-        split8(v, &hi, &lo);
-        const int e = (ks * MT + i) * 64 + g * 16 + c;
-        buf[e] = __builtin_bit_cast(uint4, hi);
-        buf[4 * MT * 64 + e] = __builtin_bit_cast(uint4, lo);
+        gload16_lds(buf + ((ks * MT + i) * 64) * 16, hi + i * 64);
+        gload16_lds(buf + ((4 * MT + ks * MT + i) * 64) * 16, lo + i * 64);
     }
 }
 
-// one chunk (4 k-steps) against FIFO slots S0 .. S0+7
-template <int MT, int S0>
-__device__ __forceinline__ void tconsume(u32x4 (&fifo)[TFIFO], const uint4* __restrict__ panel, f32x4 (&acc)[MT][2],
-                                         const uint4*& w0, const uint4*& w1, int& left, int lane) {
+// one chunk (4 k-steps) against FIFO slots S0 .. S0 + 4*NTW - 1
+template <int MT, int NTW, int S0>
+__device__ __forceinline__ void tconsume(u32x4 (&fifo)[TFIFO], const uint4* __restrict__ panel, f32x4 (&acc)[MT][NTW],
+                                         const uint4* (&w)[NTW], int& left, int lane) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         bf16x8 ahi[MT], alo[MT];
@@ -123,118 +87,108 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[TFIFO], const uint4* __re
             alo[mt] = __builtin_bit_cast(bf16x8, panel[4 * MT * 64 + (ks * MT + mt) * 64 + lane]);
         }
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int slot = S0 + ks * 2 + nt;
+        for (int nt = 0; nt < NTW; ++nt) {
+            const int slot = S0 + ks * NTW + nt;
             vm_wait<TFIFO - 1>(fifo[slot]);
             const bf16x8 b = __builtin_bit_cast(bf16x8, fifo[slot]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                acc[mt][nt] = mfma16(ahi[mt], b, acc[mt][nt]);
-                acc[mt][nt] = mfma16(alo[mt], b, acc[mt][nt]);
-            }
-            // refill 16 k-steps ahead; past the end of the slice keep re-reading the last fragment
-            const uint4* src = nt ? w1 : w0;
-            gload16(fifo[slot], src);
-            if (nt) {
-                if (left > 0) {
-                    w0 += 64;
-                    w1 += 64;
-                }
-                --left;
-            }
-        }
-    }
-}
-
-template <int MT, int EPI>
-__global__ void __launch_bounds__(TW * 64) gemm_tiled_kernel(TArgs p) {
-    extern __shared__ uint4 lds[];                    // 2 panel buffers of 2 * 4*MT*64 uint4
-    __shared__ float lds_ssq[MT * 16];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    const int K = p.KS * 32;
-    const int ks0 = blockIdx.y * p.ks_per_split;
-    const int nchunk = p.ks_per_split / 4;
-    int tile0, tile1;
-    if (EPI == TE_SWIGLU) {                           // gate tile and its up tile
-        tile0 = blockIdx.x * TW + wave;
-        tile1 = tile0 + p.up_tile_off;
-    } else {
-        tile0 = blockIdx.x * (2 * TW) + wave * 2;
-        tile1 = tile0 + 1;
-    }
-    const int n_tiles = (EPI == TE_SWIGLU) ? p.up_tile_off : p.N / 16;
-    const bool live0 = tile0 < n_tiles, live1 = (EPI == TE_SWIGLU) ? live0 : tile1 < n_tiles;
-    // dead tiles (ragged last column block) stream a valid tile and are not stored
-    const uint4* w0 = p.Wt + ((size_t)(live0 ? tile0 : 0) * p.KS + ks0) * 64 + lane;
-    const uint4* w1 = p.Wt + ((size_t)(live1 ? tile1 : 0) * p.KS + ks0) * 64 + lane;
-
-    u32x4 fifo[TFIFO];
-    int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
+            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(ahi[mt], b, acc[mt][nt]);
 #pragma unroll
-    for (int i = 0; i < TFIFO / 2; ++i) {
-        gload16(fifo[2 * i], w0);
-        gload16(fifo[2 * i + 1], w1);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(alo[mt], b, acc[mt][nt]);
+            // refill one FIFO turn ahead; past the end of the slice keep re-reading the last fragment
+            gload16(fifo[slot], w[nt]);
+        }
         if (left > 0) {
-            w0 += 64;
-            w1 += 64;
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) w[nt] += 64;
         }
         --left;
     }
-    f32x4 acc[MT][2];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float ssq[MT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) ssq[i] = 0.f;
+}
 
-    const size_t pbuf = (size_t)2 * 4 * MT * 64;
-    u32x4 P[2 * MT], G;
-    tpanel_load<MT>(P, G, p, K, ks0 * 32);
-    tpanel_store<MT, 0>(P, G, p, lds, ssq);
-    __syncthreads();
-    for (int ch = 0; ch < nchunk; ch += 4) {          // 4 chunks = 16 k-steps = one turn of the FIFO
+// MT 16-row tiles x NTW 16-column tiles per wave.  NTW = 4 halves the LDS traffic per MFMA (an
+// activation fragment read from LDS meets four weight fragments), which is what bounds the kernel
+// at 128 rows; NTW = 2 gives twice as many workgroups for matrices with few columns.
+template <int MT, int NTW, int EPI>
+__global__ void __launch_bounds__(TW * 64) gemm_tiled_kernel(TArgs p) {
+    extern __shared__ uint4 lds[];                    // 2 panel buffers of 2 * 4*MT*64 uint4
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int ks0 = blockIdx.y * p.ks_per_split;
+    const int nchunk = p.ks_per_split / 4;
+    int tile[NTW];
+    bool live[NTW];
+    const uint4* w[NTW];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const bool more = ch + q + 1 < nchunk;
-            if (more) tpanel_load<MT>(P, G, p, K, (ks0 + (ch + q + 1) * 4) * 32);
-            const uint4* panel = lds + ((ch + q) & 1) * pbuf;
-            switch (q) {
-                case 0: tconsume<MT, 0>(fifo, panel, acc, w0, w1, left, lane); break;
-                case 1: tconsume<MT, 8>(fifo, panel, acc, w0, w1, left, lane); break;
-                case 2: tconsume<MT, 16>(fifo, panel, acc, w0, w1, left, lane); break;
-                default: tconsume<MT, 24>(fifo, panel, acc, w0, w1, left, lane); break;
-            }
-            if (more) tpanel_store<MT, 8>(P, G, p, lds + (((ch + q) & 1) ^ 1) * pbuf, ssq);
-            __syncthreads();
+    for (int i = 0; i < NTW; ++i) {
+        if (EPI == TE_SWIGLU) {                       // (gate, up) pairs of the same columns
+            const int j = blockIdx.x * (TW * NTW / 2) + wave * (NTW / 2) + i / 2;
+            live[i] = j < p.up_tile_off;
+            tile[i] = j + (i & 1) * p.up_tile_off;
+        } else {
+            tile[i] = blockIdx.x * (TW * NTW) + wave * NTW + i;
+            live[i] = tile[i] < p.N / 16;
         }
+        // dead tiles (ragged last column block) stream a valid tile and are not stored
+        w[i] = p.Wt + ((size_t)(live[i] ? tile[i] : 0) * p.KS + ks0) * 64 + lane;
     }
-    // drain what is still in flight before the registers die
-    vm_wait<0>(fifo[0]);
+
+    // low half of a flat pointer into LDS = its LDS byte address
+    const unsigned lds_addr = (unsigned)(size_t)lds;
+    const unsigned pbuf_bytes = 2 * 4 * MT * 64 * 16;
+    const size_t pbuf = (size_t)2 * 4 * MT * 64;
+    tpanel_fetch<MT>(p, ks0, lds_addr);
+    u32x4 fifo[TFIFO];
+    int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
+#pragma unroll
+    for (int i = 0; i < TFIFO / NTW; ++i) {
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) gload16(fifo[i * NTW + nt], w[nt]);
+        if (left > 0) {
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) w[nt] += 64;
+        }
+        --left;
+    }
+    f32x4 acc[MT][NTW];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    vm_wait_all<TFIFO>();                             // the first panel chunk is older than the FIFO loads
+    __syncthreads();
+    // a chunk consumes 4*NTW slots, so the FIFO turns every 32 / (4*NTW) chunks; ks_per_split is a
+    // multiple of 16 k-steps = 4 chunks.  The fetch of the next chunk is older than this chunk's
+    // 4*NTW refills, which is the count its wait allows to stay in flight.
+#define TILED_CHUNK(Q)                                                                          \
+    {                                                                                           \
+        if (ch + (Q) + 1 < nchunk)                                                              \
+            tpanel_fetch<MT>(p, ks0 + (ch + (Q) + 1) * 4, lds_addr + ((((Q) & 1) ^ 1) * pbuf_bytes)); \
+        tconsume<MT, NTW, ((Q) * 4 * NTW) % TFIFO>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
+        vm_wait_all<4 * NTW>();                                                                 \
+        __syncthreads();                                                                        \
+    }
+    for (int ch = 0; ch < nchunk; ch += 4) {
+        TILED_CHUNK(0)
+        TILED_CHUNK(1)
+        TILED_CHUNK(2)
+        TILED_CHUNK(3)
+    }
+#undef TILED_CHUNK
+    // Drain what is still in flight (the last turn's refills are never consumed).  Every FIFO
+    // register stays live across the wait, so none can be handed to the epilogue while a load may
+    // still land in it.
+    vm_wait_all<0>();
+#pragma unroll
+    for (int i = 0; i < TFIFO; ++i) asm volatile("" : "+v"(fifo[i]));
 
     float rstd[MT][4];
-    if (EPI != TE_ATOMIC && p.gain) {
-        // thread t summed k-groups t%16 of rows t/16 + 16*i: reduce over the 16 threads of a row
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            float q = ssq[i];
-            q += __shfl_xor(q, 1, WAVE);
-            q += __shfl_xor(q, 2, WAVE);
-            q += __shfl_xor(q, 4, WAVE);
-            q += __shfl_xor(q, 8, WAVE);
-            if ((threadIdx.x & 15) == 0) lds_ssq[i * 16 + (threadIdx.x >> 4)] = q;
-        }
-        __syncthreads();
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) rstd[mt][i] = 1.0f / sqrtf(lds_ssq[mt * 16 + g * 4 + i] / (float)K + p.eps);
-    } else {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) rstd[mt][i] = 1.f;
-    }
+        for (int i = 0; i < 4; ++i)
+            rstd[mt][i] = (EPI != TE_ATOMIC && p.ssq)
+                              ? 1.0f / sqrtf(p.ssq[mt * 16 + g * 4 + i] / (float)(p.KS * 32) + p.eps) : 1.f;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -242,41 +196,72 @@ __global__ void __launch_bounds__(TW * 64) gemm_tiled_kernel(TArgs p) {
             const int m = mt * 16 + g * 4 + i;
             if (m >= p.M) continue;
             if (EPI == TE_ATOMIC) {
-                if (live0) unsafeAtomicAdd(p.out + (size_t)m * p.N + tile0 * 16 + c, acc[mt][0][i]);
-                if (live1) unsafeAtomicAdd(p.out + (size_t)m * p.N + tile1 * 16 + c, acc[mt][1][i]);
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt)
+                    if (live[nt]) unsafeAtomicAdd(p.out + (size_t)m * p.N + tile[nt] * 16 + c, acc[mt][nt][i]);
             } else if (EPI == TE_SWIGLU) {
-                if (live0) {
-                    const float gate = acc[mt][0][i] * rstd[mt][i], up = acc[mt][1][i] * rstd[mt][i];
-                    p.out[(size_t)m * p.N + tile0 * 16 + c] = gate / (1.0f + __expf(-gate)) * up;
-                }
+#pragma unroll
+                for (int nt = 0; nt < NTW; nt += 2)
+                    if (live[nt]) {
+                        const float gate = acc[mt][nt][i] * rstd[mt][i], up = acc[mt][nt + 1][i] * rstd[mt][i];
+                        p.out[(size_t)m * p.N + tile[nt] * 16 + c] = gate / (1.0f + __expf(-gate)) * up;
+                    }
             } else {
                 float* row = p.out + (size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N;
-                if (live0) row[tile0 * 16 + c] = acc[mt][0][i] * rstd[mt][i];
-                if (live1) row[tile1 * 16 + c] = acc[mt][1][i] * rstd[mt][i];
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt)
+                    if (live[nt]) row[tile[nt] * 16 + c] = acc[mt][nt][i] * rstd[mt][i];
             }
         }
 }
 
+// Activations -> panel.  Block (chunk, mt) of 4 waves: wave w handles k-step 4*chunk + w, lane
+// (c = lane%16, g = lane/16) the 8 values k = 32ks + 8g .. +8 of row 16mt + c: multiplied by the gain
+// (if any), split into hi + lo bf16, stored at entry (ks*MT + mt)*64 + lane of the two planes.  With
+// a gain the sum of squares of every row is accumulated (atomically) for the RMSNorm scale.
+__global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ panel, float* __restrict__ ssq,
+                                                        const float* __restrict__ a,
+                                                        const bf16_t* __restrict__ gain, int M, int K, int MT) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4, mt = blockIdx.y;
+    const int ks = blockIdx.x * 4 + wave, KS = K / 32;
+    const int row = mt * 16 + c, kb = ks * 32 + g * 8;
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (row < M) {
+        const float4 v0 = *(const float4*)(a + (size_t)row * K + kb), v1 = *(const float4*)(a + (size_t)row * K + kb + 4);
+        v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+        v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+    }
+    if (gain) {
+        float gf[8];
+        unpack_gain(*(const uint4*)(gain + kb), gf);
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            q += v[i] * v[i];
+            v[i] *= gf[i];
+        }
+        q += __shfl_xor(q, 16, WAVE);
+        q += __shfl_xor(q, 32, WAVE);
+        if (lane < 16) unsafeAtomicAdd(ssq + row, q);
+    }
+    bf16x8 hi, lo;
+    split8(v, &hi, &lo);
+    const size_t e = ((size_t)ks * MT + mt) * 64 + lane;
+    panel[e] = __builtin_bit_cast(uint4, hi);
+    panel[(size_t)KS * MT * 64 + e] = __builtin_bit_cast(uint4, lo);
+}
+
 // q, k, v rows accumulated by the split-K QKV GEMM -> RMSNorm scale, rotary embedding, cache append.
 // One block per row; the accumulator row is cleared for the next layer.
-__global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc, const float* __restrict__ x,
+__global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc, const float* __restrict__ ssq,
                                                          float* __restrict__ q, bf16_t* __restrict__ kc,
                                                          bf16_t* __restrict__ vc, KvGeom g,
                                                          const int32_t* __restrict__ len,
                                                          const int32_t* __restrict__ depth, int k, int Hq, int d,
                                                          float eps, float theta) {
-    __shared__ float red[4];
     const int m = blockIdx.x, b = m / k, t = m % k;
-    float s = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        const float v = x[(size_t)m * d + i];
-        s += v * v;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-    __syncthreads();
-    const float rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+    const float rstd = 1.0f / sqrtf(ssq[m] / (float)d + eps);
     const int L = len[b];
     const int slot = L + t;
     const double pos = (double)(L + (depth ? depth[t] : t));
@@ -307,25 +292,31 @@ __global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc
 }
 
 // ---------------------------------------------------------------------------- host side
-template <int MT, int EPI>
+template <int MT, int NTW, int EPI>
 static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
     const size_t lds = (size_t)2 * 2 * 4 * MT * 64 * 16;
-    auto kern = gemm_tiled_kernel<MT, EPI>;
+    auto kern = gemm_tiled_kernel<MT, NTW, EPI>;
     if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     kern<<<dim3(n_blocks, ksplit), TW * 64, lds, s>>>(p);
     return DSD_OK;
 }
 
-template <int EPI>
+template <int NTW, int EPI>
 static int tiled_dispatch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
     switch ((p.M + 15) / 16) {
-        case 2: return tiled_launch<2, EPI>(s, p, n_blocks, ksplit);
-        case 3: return tiled_launch<3, EPI>(s, p, n_blocks, ksplit);
-        case 4: return tiled_launch<4, EPI>(s, p, n_blocks, ksplit);
-        case 5: case 6: return tiled_launch<6, EPI>(s, p, n_blocks, ksplit);
-        case 7: case 8: return tiled_launch<8, EPI>(s, p, n_blocks, ksplit);
+        case 2: return tiled_launch<2, NTW, EPI>(s, p, n_blocks, ksplit);
+        case 3: return tiled_launch<3, NTW, EPI>(s, p, n_blocks, ksplit);
+        case 4: return tiled_launch<4, NTW, EPI>(s, p, n_blocks, ksplit);
+        case 5: case 6: return tiled_launch<6, NTW, EPI>(s, p, n_blocks, ksplit);
+        case 7: case 8: return tiled_launch<8, NTW, EPI>(s, p, n_blocks, ksplit);
         default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: %d rows", p.M);
     }
+}
+
+// column tiles per wave: 4 when that still gives (with the K split) a workgroup per compute unit
+static int choose_ntw(int n_tiles16, int KS, int n_cu) {
+    const long wgs4 = (long)((n_tiles16 + 4 * TW - 1) / (4 * TW)) * (KS / 16);
+    return wgs4 >= n_cu ? 4 : 2;
 }
 
 // K split so that a matrix with few column blocks still fills the chip; every slice a multiple of
@@ -346,48 +337,71 @@ int tiled_supported(const dsd_model_desc* d) {
     return mfma_supported(d) && d->d_model % 512 == 0 && (d->n_q_heads * d->head_dim) % 512 == 0 && d->d_ffn % 512 == 0;
 }
 
+static int mt_of(int M) {
+    const int mt = (M + 15) / 16;
+    return mt == 5 ? 6 : (mt == 7 ? 8 : mt);      // tile counts the kernel is built for
+}
+
+static void make_panel(dsd_ctx* ctx, uint4* panel, float* ssq, const float* a, const bf16_t* gain, int M, int K) {
+    const int MT = mt_of(M);
+    act_panel_kernel<<<dim3(K / 128, MT), 256, 0, ctx->stream>>>(panel, ssq, a, gain, M, K, MT);
+}
+
 // x[M][N] += a[M][K] W^T   (atomic accumulation over the K slices)
-int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, const float* a, float* x, int M, int N, int K) {
+int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, const float* a, float* x, int M, int N, int K, void* panel) {
+    make_panel(ctx, (uint4*)panel, nullptr, a, nullptr, M, K);
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.a = a; p.out = x; p.N = N;
-    const int nb = (N / 16 + 2 * TW - 1) / (2 * TW);
+    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = x; p.N = N;
+    if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
+    const int ntw = choose_ntw(N / 16, p.KS, ctx->n_cu);
+    const int nb = (N / 16 + ntw * TW - 1) / (ntw * TW);
     const int sp = choose_ksplit(p.KS, nb, ctx->n_cu);
-    if (!sp) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     p.ks_per_split = p.KS / sp;
-    return tiled_dispatch<TE_ATOMIC>(ctx->stream, p, nb, sp);
+    return ntw == 4 ? tiled_dispatch<4, TE_ATOMIC>(ctx->stream, p, nb, sp)
+                    : tiled_dispatch<2, TE_ATOMIC>(ctx->stream, p, nb, sp);
 }
 
 // acc[M][N] += (x*gain)[M][K] Wqkv^T, then finish (norm scale, rotary, append)
 int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* acc, int M, int N, int K,
                    float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len, const int32_t* depth, int k,
-                   int Hq, float eps, float theta) {
+                   int Hq, float eps, float theta, void* panel, float* ssq) {
+    make_panel(ctx, (uint4*)panel, ssq, x, gain, M, K);
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.a = x; p.gain = gain; p.out = acc; p.N = N;
-    const int nb = (N / 16 + 2 * TW - 1) / (2 * TW);
+    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = acc; p.N = N;
+    if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
+    const int ntw = choose_ntw(N / 16, p.KS, ctx->n_cu);
+    const int nb = (N / 16 + ntw * TW - 1) / (ntw * TW);
     const int sp = choose_ksplit(p.KS, nb, ctx->n_cu);
-    if (!sp) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     p.ks_per_split = p.KS / sp;
-    DSD_TRY(tiled_dispatch<TE_ATOMIC>(ctx->stream, p, nb, sp));
-    qkv_finish_kernel<<<M, 256, 0, ctx->stream>>>(acc, x, q, kc, vc, g, len, depth, k, Hq, K, eps, theta);
+    if (ntw == 4) DSD_TRY((tiled_dispatch<4, TE_ATOMIC>(ctx->stream, p, nb, sp)));
+    else DSD_TRY((tiled_dispatch<2, TE_ATOMIC>(ctx->stream, p, nb, sp)));
+    qkv_finish_kernel<<<M, 256, 0, ctx->stream>>>(acc, ssq, q, kc, vc, g, len, depth, k, Hq, K, eps, theta);
     return DSD_OK;
 }
 
 // h[M][F] = silu(rms(x) Wg^T) * (rms(x) Wu^T)
 int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* h, int M, int F, int K,
-                      float eps) {
+                      float eps, void* panel, float* ssq) {
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
+    make_panel(ctx, (uint4*)panel, ssq, x, gain, M, K);
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.a = x; p.gain = gain; p.eps = eps;
-    p.out = h; p.N = F; p.up_tile_off = F / 16;
-    return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, (F / 16 + TW - 1) / TW, 1);
+    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
+    p.eps = eps; p.out = h; p.N = F; p.up_tile_off = F / 16;
+    // fused SiLU*up needs the whole K in one workgroup: no K split, so 4 tiles per wave only if F is large
+    if ((F / 16 + 2 * TW - 1) / (2 * TW) >= ctx->n_cu)
+        return tiled_dispatch<4, TE_SWIGLU>(ctx->stream, p, (F / 16 + 2 * TW - 1) / (2 * TW), 1);
+    return tiled_dispatch<2, TE_SWIGLU>(ctx->stream, p, (F / 16 + TW - 1) / TW, 1);
 }
 
 // logits = rms(x; gf) Wlm^T
 int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* logits, int M, int V,
-                      int K, float eps, int rows_per_seq, int64_t seq_stride) {
+                      int K, float eps, int rows_per_seq, int64_t seq_stride, void* panel, float* ssq) {
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
+    make_panel(ctx, (uint4*)panel, ssq, x, gain, M, K);
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.a = x; p.gain = gain; p.eps = eps;
-    p.out = logits; p.N = V; p.rows_per_seq = rows_per_seq; p.seq_stride = seq_stride;
-    return tiled_dispatch<TE_LOGITS>(ctx->stream, p, (V / 16 + 2 * TW - 1) / (2 * TW), 1);
+    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
+    p.eps = eps; p.out = logits; p.N = V; p.rows_per_seq = rows_per_seq; p.seq_stride = seq_stride;
+    if ((V / 16 + 4 * TW - 1) / (4 * TW) >= ctx->n_cu)
+        return tiled_dispatch<4, TE_LOGITS>(ctx->stream, p, (V / 16 + 4 * TW - 1) / (4 * TW), 1);
+    return tiled_dispatch<2, TE_LOGITS>(ctx->stream, p, (V / 16 + 2 * TW - 1) / (2 * TW), 1);
 }

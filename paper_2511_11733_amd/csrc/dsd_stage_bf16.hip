@@ -208,12 +208,7 @@ template <int NT, int AMODE, int EPI>
 static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
     const int mt = (p.M + 15) / 16;
     switch (mt) {
-        case 1: {
-            static const int nw_env = getenv("DSD_NW") ? atoi(getenv("DSD_NW")) : 16;
-            if (nw_env == 8) return launch_gemm<1, NT, AMODE, EPI, 8>(s, p, n_blocks);
-            if (nw_env == 4) return launch_gemm<1, NT, AMODE, EPI, 4>(s, p, n_blocks);
-            return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
-        }
+        case 1: return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
         case 2: return launch_gemm<2, NT, AMODE, EPI, 16>(s, p, n_blocks);
         case 3: return launch_gemm<3, NT, AMODE, EPI, 8>(s, p, n_blocks);
         case 4: return launch_gemm<4, NT, AMODE, EPI, 8>(s, p, n_blocks);
@@ -290,7 +285,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const int rows_pad = RT * n_rg * 16;
 
     const int n_qkv = (Hq + 2 * Hkv) * hd;
+    const size_t kmax = (size_t)std::max(std::max(d, qd), F);
+    const size_t n_ssq = (size_t)128 * (2 * D.n_layers + 1);
     size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + (size_t)M * n_qkv * 4 +
+                  128 * kmax * 4 + n_ssq * 4 +
                   (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
     WsBump ws{ctx->ws, 0};
@@ -301,9 +299,12 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
     float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
     float* qkv_acc = ws.take<float>((size_t)M * n_qkv);
+    float* ssq_all = ws.take<float>(n_ssq);          // one row-sum-of-squares array per normalised GEMM input
+    void* panel = ws.take<float>(128 * kmax);         // activations as hi/lo bf16 in A-operand order
     hipStream_t s = ctx->stream;
-    // split-K partial sums of the QKV projection meet here; every layer leaves it cleared again
-    if (tiled) DSD_HIP(hipMemsetAsync(qkv_acc, 0, (size_t)M * n_qkv * 4, s));
+    // split-K partial sums of the QKV projection meet in qkv_acc (every layer leaves it cleared again);
+    // qkv_acc and ssq_all are adjacent: one fill
+    if (tiled) DSD_HIP(hipMemsetAsync(qkv_acc, 0, (size_t)((char*)(ssq_all + n_ssq) - (char*)qkv_acc), s));
 
     const size_t nx = (size_t)M * d;
     {
@@ -326,7 +327,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
             ProfScope ps(ctx, DSD_KC_QKV);
             if (tiled)
                 DSD_TRY(tiled_gemm_qkv(ctx, W.qkv_t, x, (const bf16_t*)W.g1, qkv_acc, M, n_qkv, d, q, kc, vc, g,
-                                       kv->len_dev, depth, k, Hq, D.rms_eps, D.rope_theta));
+                                       kv->len_dev, depth, k, Hq, D.rms_eps, D.rope_theta, panel, ssq_all + (size_t)128 * (2 * l)));
             else
                 DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
         }
@@ -354,7 +355,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
-            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, att, x, M, d, qd));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, att, x, M, d, qd, panel));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
@@ -363,7 +364,9 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.hout = h; a.N = F; a.up_tile_off = F / 16;
         {
             ProfScope ps(ctx, DSD_KC_GATEUP);
-            if (tiled) DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, h, M, F, d, D.rms_eps));
+            if (tiled)
+                DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, h, M, F, d, D.rms_eps, panel,
+                                          ssq_all + (size_t)128 * (2 * l + 1)));
             else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
         }
         // x += h Wd^T
@@ -371,7 +374,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
-            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, h, x, M, d, F));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, h, x, M, d, F, panel));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
     }
@@ -386,7 +389,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         ProfScope ps(ctx, DSD_KC_HEAD);
         if (tiled)
             DSD_TRY(tiled_gemm_logits(ctx, w->lm_t, x, (const bf16_t*)w->gf, logits, M, D.vocab, d, D.rms_eps, k,
-                                      logits_seq_stride));
+                                      logits_seq_stride, panel, ssq_all + (size_t)128 * (2 * D.n_layers)));
         else
             DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
     }
