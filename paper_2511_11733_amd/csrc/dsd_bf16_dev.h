@@ -153,6 +153,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, const int (&til
 }
 
 // ============================================================================ attention pieces
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr
+// is wave-uniform and goes through M0).  No register ever holds the data, so nothing the register
+// allocator does can touch a value whose load is still in flight; completion is counted by vmcnt
+// like any other load.
+__device__ __forceinline__ void gload16_lds(unsigned lds_addr, const void* ptr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(ptr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void vm_wait_all() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 struct AttnArgs {
     const float* q;        // [M][Hq*hd] fp32
     const bf16_t* kc;
@@ -224,7 +236,7 @@ __device__ __forceinline__ void attn_run(const AttnArgs& p, int b, int hk, int r
             bf16x8 kf[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                kf[j] = __builtin_bit_cast(bf16x8, *(const uint4*)(kbase + (size_t)(j0 + tl * 16 + c) * 128 + j * 32 + g * 8));
+                kf[j] = __builtin_bit_cast(bf16x8, *(const uint4*)(kbase + (size_t)(j0 + tl * 16) * 128 + j * 512 + lane * 8));
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 f32x4 a = {0.f, 0.f, 0.f, 0.f};
@@ -237,9 +249,9 @@ __device__ __forceinline__ void attn_run(const AttnArgs& p, int b, int hk, int r
             }
         }
         bf16x8 vf[8];
-        const bf16_t* vblk = vbase + (size_t)(j0 >> 6) * (128 * 64) + (j0 & 32) + g * 8;
+        const bf16_t* vblk = vbase + (size_t)(j0 >> 5) * (32 * 128) + lane * 8;
 #pragma unroll
-        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, *(const uint4*)(vblk + (size_t)(h * 16 + c) * 64));
+        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, *(const uint4*)(vblk + h * 512));
 
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {

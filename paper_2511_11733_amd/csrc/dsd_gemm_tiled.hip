@@ -10,16 +10,18 @@
 //   * the activations are converted ONCE per GEMM by a small kernel of their own (gain, hi/lo
 //     split, A-operand order, sum of squares for the RMSNorm scale) into a panel in global memory;
 //     doing that inside every workgroup cost more vector ALU time than the matrix cores had work;
-//   * the slice is walked in chunks of 128 columns of K: the 256 threads copy the chunk of the
-//     panel into LDS, double buffered, one chunk ahead;
-//   * every wave keeps its next 32 weight fragments in flight in a register FIFO, issued by hand
-//     (inline asm + explicit s_waitcnt counts, see gload16 / vm_wait) so that neither the panel
-//     prefetch nor the workgroup barriers ever drain the weight stream.
+//   * the slice is walked in chunks of 128 columns of K; the workgroup has 4 more waves that do
+//     nothing but fetch the next chunk of the panel from global memory straight into LDS (double
+//     buffered).  Vector memory loads of one wave complete in order, so a wave that fetched the
+//     panel itself would have to drain its older weight loads at every chunk; as it is, the only
+//     things a computing wave ever waits for are its own weight stream and the workgroup barrier;
+//   * every computing wave keeps its next 32 weight fragments in flight in a register FIFO, issued
+//     by hand (inline asm + explicit s_waitcnt counts, see gload16 / vm_wait).
 #include "dsd_bf16_dev.h"
 
-#define TW 4
+#define TP 4             // panel-fetching waves per workgroup
+#define NTW 2            // 16-column tiles per computing wave
 #define TCH 128          // K per panel chunk: 4 k-steps
-#define TFIFO 32         // fragments in flight per wave: 16 k-steps x 2 tiles
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void gload16(u32x4& dst, const void* ptr) {
@@ -31,18 +33,6 @@ template <int N>
 __device__ __forceinline__ void vm_wait(u32x4& r) {
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(N));
 }
-// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr
-// is wave-uniform and goes through M0).  No register ever holds the data, so nothing the register
-// allocator does can touch a value whose load is still in flight; completion is counted by vmcnt
-// like any other load.
-__device__ __forceinline__ void gload16_lds(unsigned lds_addr, const void* ptr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(ptr) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void vm_wait_all() {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 enum { TE_ATOMIC = 0, TE_SWIGLU = 1, TE_LOGITS = 2 };
 
 struct TArgs {
@@ -60,11 +50,11 @@ struct TArgs {
     int64_t seq_stride;
 };
 
-// wave w fetches k-step w of a chunk into the panel buffer at LDS byte address buf: entry
-// (ks*MT + mt)*64 + lane of both planes (hi at entry 0, lo at entry 4*MT*64)
+// fetching wave ks (0..3) brings k-step ks of a chunk into the panel buffer at LDS byte address buf:
+// entry (ks*MT + mt)*64 + lane of both planes (hi at entry 0, lo at entry 4*MT*64)
 template <int MT>
-__device__ __forceinline__ void tpanel_fetch(const TArgs& p, int ks_abs, unsigned buf) {
-    const int lane = threadIdx.x & 63, ks = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+__device__ __forceinline__ void tpanel_fetch(const TArgs& p, int ks_abs, unsigned buf, int ks) {
+    const int lane = threadIdx.x & 63;
     const uint4* hi = p.panel + ((size_t)(ks_abs + ks) * MT) * 64 + lane;
     const uint4* lo = hi + (size_t)p.KS * MT * 64;
 #pragma unroll
@@ -74,9 +64,19 @@ __device__ __forceinline__ void tpanel_fetch(const TArgs& p, int ks_abs, unsigne
     }
 }
 
+// Next k-step of the weight stream; past the end of the slice (the last turn of refills, never
+// consumed) it stays on the last fragment.
+__device__ __forceinline__ void tadvance(const uint4* (&w)[NTW], int& left) {
+    if (left > 0) {
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) w[nt] += 64;
+    }
+    --left;
+}
+
 // one chunk (4 k-steps) against FIFO slots S0 .. S0 + 4*NTW - 1
-template <int MT, int NTW, int S0>
-__device__ __forceinline__ void tconsume(u32x4 (&fifo)[TFIFO], const uint4* __restrict__ panel, f32x4 (&acc)[MT][NTW],
+template <int MT, int NF, int S0>
+__device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restrict__ panel, f32x4 (&acc)[MT][NTW],
                                          const uint4* (&w)[NTW], int& left, int lane) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -89,7 +89,7 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[TFIFO], const uint4* __re
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
             const int slot = S0 + ks * NTW + nt;
-            vm_wait<TFIFO - 1>(fifo[slot]);
+            vm_wait<NF - 1>(fifo[slot]);
             const bf16x8 b = __builtin_bit_cast(bf16x8, fifo[slot]);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(ahi[mt], b, acc[mt][nt]);
@@ -98,74 +98,76 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[TFIFO], const uint4* __re
             // refill one FIFO turn ahead; past the end of the slice keep re-reading the last fragment
             gload16(fifo[slot], w[nt]);
         }
-        if (left > 0) {
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) w[nt] += 64;
-        }
-        --left;
+        tadvance(w, left);
     }
 }
 
-// MT 16-row tiles x NTW 16-column tiles per wave.  NTW = 4 halves the LDS traffic per MFMA (an
-// activation fragment read from LDS meets four weight fragments), which is what bounds the kernel
-// at 128 rows; NTW = 2 gives twice as many workgroups for matrices with few columns.
-template <int MT, int NTW, int EPI>
-__global__ void __launch_bounds__(TW * 64) gemm_tiled_kernel(TArgs p) {
+// TWC computing waves (4 or 8), each MT 16-row tiles x NTW 16-column tiles; waves TWC .. TWC+3 fetch
+// the panel.  More computing waves per workgroup mean fewer workgroups fetching the same panel.  The
+// second launch bound is waves per SIMD: two resident workgroups for the smallest tiles.
+template <int MT, int TWC, int EPI>
+__global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 : 2)) gemm_tiled_kernel(TArgs p) {
     extern __shared__ uint4 lds[];                    // 2 panel buffers of 2 * 4*MT*64 uint4
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int ks0 = blockIdx.y * p.ks_per_split;
     const int nchunk = p.ks_per_split / 4;
+    const size_t pbuf = (size_t)2 * 4 * MT * 64;
+    if (wave >= TWC) {
+        // low half of a flat pointer into LDS = its LDS byte address
+        const unsigned lds_addr = (unsigned)(size_t)lds;
+        const unsigned pbuf_bytes = 2 * 4 * MT * 64 * 16;
+        // one barrier per chunk, matched by the computing waves below
+        tpanel_fetch<MT>(p, ks0, lds_addr, wave - TWC);
+        vm_wait_all<0>();
+        __syncthreads();
+        for (int ch = 0; ch < nchunk; ++ch) {
+            if (ch + 1 < nchunk)
+                tpanel_fetch<MT>(p, ks0 + (ch + 1) * 4, lds_addr + ((ch & 1) ^ 1) * pbuf_bytes, wave - TWC);
+            vm_wait_all<0>();
+            __syncthreads();
+        }
+        return;
+    }
     int tile[NTW];
     bool live[NTW];
     const uint4* w[NTW];
 #pragma unroll
     for (int i = 0; i < NTW; ++i) {
         if (EPI == TE_SWIGLU) {                       // (gate, up) pairs of the same columns
-            const int j = blockIdx.x * (TW * NTW / 2) + wave * (NTW / 2) + i / 2;
+            const int j = blockIdx.x * (TWC * NTW / 2) + wave * (NTW / 2) + i / 2;
             live[i] = j < p.up_tile_off;
             tile[i] = j + (i & 1) * p.up_tile_off;
         } else {
-            tile[i] = blockIdx.x * (TW * NTW) + wave * NTW + i;
+            tile[i] = blockIdx.x * (TWC * NTW) + wave * NTW + i;
             live[i] = tile[i] < p.N / 16;
         }
         // dead tiles (ragged last column block) stream a valid tile and are not stored
         w[i] = p.Wt + ((size_t)(live[i] ? tile[i] : 0) * p.KS + ks0) * 64 + lane;
     }
 
-    // low half of a flat pointer into LDS = its LDS byte address
-    const unsigned lds_addr = (unsigned)(size_t)lds;
-    const unsigned pbuf_bytes = 2 * 4 * MT * 64 * 16;
-    const size_t pbuf = (size_t)2 * 4 * MT * 64;
-    tpanel_fetch<MT>(p, ks0, lds_addr);
-    u32x4 fifo[TFIFO];
+    // fragments in flight per wave: 32 (16 k-steps), or 16 where 128 rows of accumulators and
+    // activation fragments leave no more registers at two waves per SIMD
+    constexpr int NF = MT <= 3 ? 8 : 16;
+    u32x4 fifo[NF];
     int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
 #pragma unroll
-    for (int i = 0; i < TFIFO / NTW; ++i) {
+    for (int i = 0; i < NF / NTW; ++i) {
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) gload16(fifo[i * NTW + nt], w[nt]);
-        if (left > 0) {
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) w[nt] += 64;
-        }
-        --left;
+        tadvance(w, left);
     }
     f32x4 acc[MT][NTW];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    vm_wait_all<TFIFO>();                             // the first panel chunk is older than the FIFO loads
     __syncthreads();
-    // a chunk consumes 4*NTW slots, so the FIFO turns every 32 / (4*NTW) chunks; ks_per_split is a
-    // multiple of 16 k-steps = 4 chunks.  The fetch of the next chunk is older than this chunk's
-    // 4*NTW refills, which is the count its wait allows to stay in flight.
+    // a chunk consumes 4*NTW slots, so the FIFO turns every NF / (4*NTW) chunks (1, 2 or 4);
+    // ks_per_split is a multiple of 16 k-steps = 4 chunks
 #define TILED_CHUNK(Q)                                                                          \
     {                                                                                           \
-        if (ch + (Q) + 1 < nchunk)                                                              \
-            tpanel_fetch<MT>(p, ks0 + (ch + (Q) + 1) * 4, lds_addr + ((((Q) & 1) ^ 1) * pbuf_bytes)); \
-        tconsume<MT, NTW, ((Q) * 4 * NTW) % TFIFO>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
-        vm_wait_all<4 * NTW>();                                                                 \
+        tconsume<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
         __syncthreads();                                                                        \
     }
     for (int ch = 0; ch < nchunk; ch += 4) {
@@ -180,7 +182,7 @@ __global__ void __launch_bounds__(TW * 64) gemm_tiled_kernel(TArgs p) {
     // still land in it.
     vm_wait_all<0>();
 #pragma unroll
-    for (int i = 0; i < TFIFO; ++i) asm volatile("" : "+v"(fifo[i]));
+    for (int i = 0; i < NF; ++i) asm volatile("" : "+v"(fifo[i]));
 
     float rstd[MT][4];
 #pragma unroll
@@ -292,31 +294,44 @@ __global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc
 }
 
 // ---------------------------------------------------------------------------- host side
-template <int MT, int NTW, int EPI>
+template <int MT, int TWC, int EPI>
 static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
     const size_t lds = (size_t)2 * 2 * 4 * MT * 64 * 16;
-    auto kern = gemm_tiled_kernel<MT, NTW, EPI>;
+    auto kern = gemm_tiled_kernel<MT, TWC, EPI>;
     if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<dim3(n_blocks, ksplit), TW * 64, lds, s>>>(p);
+    kern<<<dim3(n_blocks, ksplit), (TWC + TP) * 64, lds, s>>>(p);
     return DSD_OK;
 }
 
-template <int NTW, int EPI>
-static int tiled_dispatch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
-    switch ((p.M + 15) / 16) {
-        case 2: return tiled_launch<2, NTW, EPI>(s, p, n_blocks, ksplit);
-        case 3: return tiled_launch<3, NTW, EPI>(s, p, n_blocks, ksplit);
-        case 4: return tiled_launch<4, NTW, EPI>(s, p, n_blocks, ksplit);
-        case 5: case 6: return tiled_launch<6, NTW, EPI>(s, p, n_blocks, ksplit);
-        case 7: case 8: return tiled_launch<8, NTW, EPI>(s, p, n_blocks, ksplit);
+// twc = computing waves per workgroup: 8 only for up to 64 rows (registers)
+template <int EPI>
+static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, int ksplit) {
+    const int mt = (p.M + 15) / 16;
+    if (twc == 8) {
+        switch (mt) {
+            case 2: return tiled_launch<2, 8, EPI>(s, p, n_blocks, ksplit);
+            case 3: return tiled_launch<3, 8, EPI>(s, p, n_blocks, ksplit);
+            case 4: return tiled_launch<4, 8, EPI>(s, p, n_blocks, ksplit);
+            default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: 8 computing waves with %d rows", p.M);
+        }
+    }
+    switch (mt) {
+        case 2: return tiled_launch<2, 4, EPI>(s, p, n_blocks, ksplit);
+        case 3: return tiled_launch<3, 4, EPI>(s, p, n_blocks, ksplit);
+        case 4: return tiled_launch<4, 4, EPI>(s, p, n_blocks, ksplit);
+        case 5: case 6: return tiled_launch<6, 4, EPI>(s, p, n_blocks, ksplit);
+        case 7: case 8: return tiled_launch<8, 4, EPI>(s, p, n_blocks, ksplit);
         default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: %d rows", p.M);
     }
 }
 
-// column tiles per wave: 4 when that still gives (with the K split) a workgroup per compute unit
-static int choose_ntw(int n_tiles16, int KS, int n_cu) {
-    const long wgs4 = (long)((n_tiles16 + 4 * TW - 1) / (4 * TW)) * (KS / 16);
-    return wgs4 >= n_cu ? 4 : 2;
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Column tiles (16 wide) per workgroup: 16 (8 computing waves) when the rows allow it and the matrix
+// is wide enough to give about a workgroup per compute unit without cutting K, else 8.
+static int choose_twc(int M, int n_tiles16, int n_cu) {
+    if ((M + 15) / 16 > 4) return 4;
+    return (long)ceil_div(n_tiles16, 8 * NTW) * 5 >= (long)n_cu * 4 ? 8 : 4;
 }
 
 // K split so that a matrix with few column blocks still fills the chip; every slice a multiple of
@@ -353,12 +368,11 @@ int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, const float* a, float* x, int
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = x; p.N = N;
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    const int ntw = choose_ntw(N / 16, p.KS, ctx->n_cu);
-    const int nb = (N / 16 + ntw * TW - 1) / (ntw * TW);
+    const int twc = choose_twc(M, N / 16, ctx->n_cu);
+    const int nb = ceil_div(N / 16, twc * NTW);
     const int sp = choose_ksplit(p.KS, nb, ctx->n_cu);
     p.ks_per_split = p.KS / sp;
-    return ntw == 4 ? tiled_dispatch<4, TE_ATOMIC>(ctx->stream, p, nb, sp)
-                    : tiled_dispatch<2, TE_ATOMIC>(ctx->stream, p, nb, sp);
+    return tiled_dispatch<TE_ATOMIC>(ctx->stream, p, twc, nb, sp);
 }
 
 // acc[M][N] += (x*gain)[M][K] Wqkv^T, then finish (norm scale, rotary, append)
@@ -369,12 +383,11 @@ int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* g
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = acc; p.N = N;
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    const int ntw = choose_ntw(N / 16, p.KS, ctx->n_cu);
-    const int nb = (N / 16 + ntw * TW - 1) / (ntw * TW);
+    const int twc = choose_twc(M, N / 16, ctx->n_cu);
+    const int nb = ceil_div(N / 16, twc * NTW);
     const int sp = choose_ksplit(p.KS, nb, ctx->n_cu);
     p.ks_per_split = p.KS / sp;
-    if (ntw == 4) DSD_TRY((tiled_dispatch<4, TE_ATOMIC>(ctx->stream, p, nb, sp)));
-    else DSD_TRY((tiled_dispatch<2, TE_ATOMIC>(ctx->stream, p, nb, sp)));
+    DSD_TRY((tiled_dispatch<TE_ATOMIC>(ctx->stream, p, twc, nb, sp)));
     qkv_finish_kernel<<<M, 256, 0, ctx->stream>>>(acc, ssq, q, kc, vc, g, len, depth, k, Hq, K, eps, theta);
     return DSD_OK;
 }
@@ -387,10 +400,9 @@ int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.eps = eps; p.out = h; p.N = F; p.up_tile_off = F / 16;
-    // fused SiLU*up needs the whole K in one workgroup: no K split, so 4 tiles per wave only if F is large
-    if ((F / 16 + 2 * TW - 1) / (2 * TW) >= ctx->n_cu)
-        return tiled_dispatch<4, TE_SWIGLU>(ctx->stream, p, (F / 16 + 2 * TW - 1) / (2 * TW), 1);
-    return tiled_dispatch<2, TE_SWIGLU>(ctx->stream, p, (F / 16 + TW - 1) / TW, 1);
+    // fused SiLU*up needs the whole K in one workgroup: no K split
+    const int twc = choose_twc(M, 2 * (F / 16), ctx->n_cu);
+    return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, twc, ceil_div(F / 16, twc * NTW / 2), 1);
 }
 
 // logits = rms(x; gf) Wlm^T
@@ -401,7 +413,6 @@ int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.eps = eps; p.out = logits; p.N = V; p.rows_per_seq = rows_per_seq; p.seq_stride = seq_stride;
-    if ((V / 16 + 4 * TW - 1) / (4 * TW) >= ctx->n_cu)
-        return tiled_dispatch<4, TE_LOGITS>(ctx->stream, p, (V / 16 + 4 * TW - 1) / (4 * TW), 1);
-    return tiled_dispatch<2, TE_LOGITS>(ctx->stream, p, (V / 16 + 2 * TW - 1) / (2 * TW), 1);
+    const int twc = choose_twc(M, V / 16, ctx->n_cu);
+    return tiled_dispatch<TE_LOGITS>(ctx->stream, p, twc, ceil_div(V / 16, twc * NTW), 1);
 }

@@ -50,29 +50,32 @@ template <> __device__ inline void st_f32<float>(float* p, float v) { *p = v; }
 template <> __device__ inline void st_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
 // ----------------------------------------------------------------------------- KV cache layout
-// Per layer, sequence and kv head:
-//   K : [S][hd]                      slot-major, a row is one rotated key
-//   V : [S/64][hd][64]               transposed in blocks of 64 slots, and inside every group of
-//                                    32 slots the slots are stored in the order in which the
-//                                    attention kernel's score tiles hand them to the P*V product
-//                                    (see v_slot_perm), so that a lane's 8 values are contiguous.
+// Per layer, sequence and kv head, both caches are kept in the order in which the attention kernel's
+// matrix instructions take their operands, so that a wavefront fetches every operand fragment as
+// one contiguous 1 KiB (hd = 128) piece, lane l taking bytes 16l .. 16l+15:
+//   K : [S/16][hd/8][16][8]          tile of 16 slots; inside it feature group e/8, slot, feature e%8
+//   V : [S/32][hd/16][4][16][8]      block of 32 slots; inside it feature tile e/16, then the slot's
+//                                    place p = v_slot_perm(slot % 32) in the P*V product as p/8,
+//                                    feature e%16, p%8
+// v_slot_perm is the order in which the score tiles of S^T = K Q^T hand their keys to the P*V
+// product: key 16*tile + 4g + i sits at reduction index 8g + 4*tile + i.
 // S (slots per sequence) is a multiple of 64.
 struct KvGeom {
     int Hkv, hd, S, Bmax;
     size_t head_elems;   // S * hd
     size_t layer_elems;  // Bmax * Hkv * S * hd
 };
-__host__ __device__ inline int v_slot_perm(int s64) {
-    int grp = s64 >> 5, kk = s64 & 31;
-    int tile = kk >> 4, r = kk & 15;
-    return (grp << 5) + ((r >> 2) << 3) + (r & 3) + (tile << 2);
+__host__ __device__ inline int v_slot_perm(int s32) {
+    const int tile = s32 >> 4, r = s32 & 15;
+    return ((r >> 2) << 3) + (r & 3) + (tile << 2);
 }
 __host__ __device__ inline size_t kv_k_off(const KvGeom& g, int b, int h, int slot, int e) {
-    return ((size_t)(b * g.Hkv + h) * g.S + slot) * g.hd + e;
+    return ((size_t)(b * g.Hkv + h) * g.S + (slot & ~15)) * g.hd + (size_t)(e >> 3) * 128 + (slot & 15) * 8 + (e & 7);
 }
 __host__ __device__ inline size_t kv_v_off(const KvGeom& g, int b, int h, int slot, int e) {
-    return (size_t)(b * g.Hkv + h) * g.head_elems + (size_t)(slot >> 6) * (g.hd * 64) + (size_t)e * 64 +
-           v_slot_perm(slot & 63);
+    const int p = v_slot_perm(slot & 31);
+    return (size_t)(b * g.Hkv + h) * g.head_elems + (size_t)(slot >> 5) * (g.hd * 32) + (size_t)(e >> 4) * 512 +
+           (p >> 3) * 128 + (e & 15) * 8 + (p & 7);
 }
 
 // ----------------------------------------------------------------------------- handles

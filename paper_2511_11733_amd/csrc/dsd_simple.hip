@@ -169,8 +169,7 @@ __global__ void attn_rowhead_kernel(float* __restrict__ out, const float* __rest
         float s = -INFINITY;
         if (j < L || ((vis >> (j - L)) & 1ull)) {
             s = 0.f;
-            const T* kr = kc + kv_k_off(g, b, hk, j, 0);
-            for (int e = 0; e < hd; ++e) s += qr[e] * ld_f32(kr + e);
+            for (int e = 0; e < hd; ++e) s += qr[e] * ld_f32(kc + kv_k_off(g, b, hk, j, e));
             s *= scale;
         }
         sc[j] = s;

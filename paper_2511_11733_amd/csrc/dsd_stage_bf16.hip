@@ -219,16 +219,173 @@ static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
 }
 
 // ============================================================================ attention
-// One wavefront owns a run of keys of one (sequence, kv head) and all its k*G query rows; the
-// partial (max, sum, O) of every run goes to scratch and attn_combine_kernel merges the runs.
-// blockIdx.x = (group of 4 runs) * n_rowgroups + rowgroup; a row group is RT tiles of 16 query rows.
+// One wavefront owns a run of keys of one (sequence, kv head) and RT tiles of 16 of its k*G query
+// rows; the partial (max, sum, O) of every run goes to scratch and attn_combine_kernel merges the
+// runs.  K and V never pass through registers on their way in: each step of 32 keys (8 KiB of K,
+// 8 KiB of V, already in MFMA operand order per lane) is fetched global -> LDS directly into one of
+// two stages private to the wave, one step ahead of the arithmetic, so that a wave needs no partner
+// to hide memory latency and no barrier.  The caches are stored in that operand order, so a step is
+// two contiguous 8 KiB pieces.  Stage layout: 16 fragments of 1 KiB (lane l at 16*l): K tile 0
+// features 0..31, 32..63, 64..95, 96..127, K tile 1 likewise, then V features 16h..16h+15.
+// blockIdx.x = (group of blockDim.x/64 runs) * n_rowgroups + rowgroup.
+#define ATT_STAGE_BYTES 16384
+
+__device__ __forceinline__ void attn_fetch(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int j0,
+                                           unsigned stage, int lane) {
+    const bf16_t* kt = kbase + (size_t)j0 * 128 + lane * 8;           // two tiles of 16 keys, 4 fragments each
+#pragma unroll
+    for (int f = 0; f < 8; ++f) gload16_lds(stage + f * 1024, kt + f * 512);
+    const bf16_t* vb = vbase + (size_t)(j0 >> 5) * (32 * 128) + lane * 8;
+#pragma unroll
+    for (int h = 0; h < 8; ++h) gload16_lds(stage + 8192 + h * 1024, vb + h * 512);
+}
+
 template <int RT>
-__global__ void __launch_bounds__(256) attn_partial_kernel(AttnArgs p, int n_rowgroups) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowgroups) {
+    extern __shared__ uint4 att_lds[];                // per wave: 2 stages of ATT_STAGE_BYTES
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c = lane & 15, g = lane >> 4;
     const int rg = blockIdx.x % n_rowgroups;
-    const int run = (blockIdx.x / n_rowgroups) * 4 + wave, hk = blockIdx.y, b = blockIdx.z;
+    const int run = (blockIdx.x / n_rowgroups) * (blockDim.x >> 6) + wave, hk = blockIdx.y, b = blockIdx.z;
     if (run >= p.n_runs) return;
-    attn_run<RT>(p, b, hk, run, rg * RT * 16, lane);
+    const int row0 = rg * RT * 16;
+    const int L = p.len[b];
+    const int nkeys = min(L + p.k, p.g.S);
+    const int rows = p.k * p.G;
+    const int j_begin = run * p.keys_per_wave;
+    const int j_end = min(j_begin + p.keys_per_wave, nkeys);
+    const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad + row0;
+    const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
+    const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
+    const uint4* stage_ptr = att_lds + (size_t)wave * (2 * ATT_STAGE_BYTES / 16);
+    const unsigned stage_addr = (unsigned)(size_t)stage_ptr;      // low half of a flat LDS pointer = LDS address
+    if (j_begin < j_end) attn_fetch(kbase, vbase, j_begin, stage_addr, lane);
+
+    bf16x8 qh[RT][4], ql[RT][4];
+    uint64_t vis[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int r = row0 + rt * 16 + c;
+        const int t = r / p.G, hq = hk * p.G + r % p.G;
+        vis[rt] = 0;
+        if (r < rows) vis[rt] = p.mask ? p.mask[t] : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1ull));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (r < rows) {
+                const float* src = p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8;
+                const float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
+                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+                v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+            }
+            split8(v, &qh[rt][j], &ql[rt][j]);
+        }
+    }
+    f32x4 o[8][RT];
+#pragma unroll
+    for (int h = 0; h < 8; ++h)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) o[h][rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float mrow[RT], lrow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        mrow[rt] = -INFINITY;
+        lrow[rt] = 0.f;
+    }
+    // the loads of the queries above are the compiler's and complete by its own waits; from here on
+    // the only vector memory operations in flight are the stage fetches
+    int st = 0;
+    for (int j0 = j_begin; j0 < j_end; j0 += 32, st ^= 1) {
+        if (j0 + 32 < j_end) {
+            attn_fetch(kbase, vbase, j0 + 32, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane);
+            vm_wait_all<16>();                        // this step's 16 fetches are older than those
+        } else {
+            vm_wait_all<0>();
+        }
+        const uint4* sp = stage_ptr + st * (ATT_STAGE_BYTES / 16) + lane;
+        f32x4 s[2][RT];
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl) {
+            bf16x8 kf[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kf[j] = __builtin_bit_cast(bf16x8, sp[(tl * 4 + j) * 64]);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    a = mfma16(kf[j], qh[rt][j], a);
+                    a = mfma16(kf[j], ql[rt][j], a);
+                }
+                s[tl][rt] = a;
+            }
+        }
+        bf16x8 vf[8];
+#pragma unroll
+        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, sp[(8 + h) * 64]);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int key = j0 + tl * 16 + g * 4 + i;
+                    bool ok = key < L;
+                    if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
+                    const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
+                    s[tl][rt][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+            const float mnew = fmaxf(mrow[rt], mx);
+            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            const float alpha = exp2f(mrow[rt] - muse);      // 0 when mrow was -inf
+            mrow[rt] = mnew;
+            float pv[8];
+            float ps = 0.f;
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float e = exp2f(s[tl][rt][i] - muse);
+                    pv[tl * 4 + i] = e;
+                    ps += e;
+                }
+            lrow[rt] = lrow[rt] * alpha + ps;
+            bf16x8 ph, pl;
+            split8(pv, &ph, &pl);
+#pragma unroll
+            for (int h = 0; h < 8; ++h) {
+                o[h][rt] *= alpha;
+                o[h][rt] = mfma16(vf[h], ph, o[h][rt]);
+                o[h][rt] = mfma16(vf[h], pl, o[h][rt]);
+            }
+        }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float l = lrow[rt];
+        l += __shfl_xor(l, 16, WAVE);
+        l += __shfl_xor(l, 32, WAVE);
+        const int r = rt * 16 + c;
+        if (g == 0) {
+            p.part_ml[(unit + r) * 2] = mrow[rt];
+            p.part_ml[(unit + r) * 2 + 1] = l;
+        }
+#pragma unroll
+        for (int h = 0; h < 8; ++h) *(f32x4*)(p.part_o + (unit + r) * 128 + h * 16 + g * 4) = o[h][rt];
+    }
+}
+
+template <int RT>
+static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int waves_per_wg, int Hkv, int B) {
+    const size_t lds = (size_t)waves_per_wg * 2 * ATT_STAGE_BYTES;
+    auto kern = attn_stream_kernel<RT>;
+    if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    kern<<<dim3(((t.n_runs + waves_per_wg - 1) / waves_per_wg) * n_rg, Hkv, B), waves_per_wg * 64, lds, s>>>(t, n_rg);
+    return DSD_OK;
 }
 
 __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ out, const float* __restrict__ part_o,
@@ -275,12 +432,17 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
     const int max_keys = std::min(max_len + k, g.S);
-    // runs of keys per wave: aim at about 8 waves per CU over the whole grid
+    // Runs of keys per wave: LDS holds the stages of 4 waves per compute unit, so aim at that many
+    // waves over the whole grid (one round), in workgroups of 4 waves; small problems take shorter
+    // runs (at least 64 keys) in smaller workgroups so that more compute units take part.
     const long units = (long)B * Hkv;
-    long kpw = ((long)max_keys * units + 2047) / 2048;
+    const long wave_slots = (long)ctx->n_cu * 4;
+    long kpw = ((long)max_keys * units * n_rg + wave_slots - 1) / wave_slots;
     kpw = std::max(64L, (kpw + 31) / 32 * 32);
     const int keys_per_wave = (int)kpw;
     int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
+    const long n_waves = units * n_rg * n_runs;
+    const int att_waves_per_wg = n_waves >= wave_slots ? 4 : (n_waves * 2 >= wave_slots ? 2 : 1);
     if (n_runs > MAX_RUNS) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: %d key runs", n_runs);
     const int rows_pad = RT * n_rg * 16;
 
@@ -336,14 +498,13 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         t.q = q; t.kc = kc; t.vc = vc; t.g = g; t.len = kv->len_dev; t.mask = tree_mask; t.k = k; t.Hq = Hq; t.G = G;
         t.keys_per_wave = keys_per_wave; t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
         t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
-        dim3 ag(((n_runs + 3) / 4) * n_rg, Hkv, B);
         {
             ProfScope ps(ctx, DSD_KC_ATTN);
             switch (RT) {
-                case 1: attn_partial_kernel<1><<<ag, 256, 0, s>>>(t, n_rg); break;
-                case 2: attn_partial_kernel<2><<<ag, 256, 0, s>>>(t, n_rg); break;
-                case 3: attn_partial_kernel<3><<<ag, 256, 0, s>>>(t, n_rg); break;
-                default: attn_partial_kernel<4><<<ag, 256, 0, s>>>(t, n_rg); break;
+                case 1: DSD_TRY(attn_launch<1>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
+                case 2: DSD_TRY(attn_launch<2>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
+                case 3: DSD_TRY(attn_launch<3>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
+                default: DSD_TRY(attn_launch<4>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
             }
         }
         {
