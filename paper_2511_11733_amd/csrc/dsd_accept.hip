@@ -109,6 +109,42 @@ __device__ inline float soft_weight_f(float ln_pt, float q, float tau) {
     return expf(e);
 }
 
+__device__ inline unsigned order_u32(float v) {
+    const unsigned u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+// One selection round of a wave over o[j] = order_u32 of id base + threadIdx.x + j*TPB (0 = not a
+// candidate): finds the largest value, the lowest id among its holders, clears it there and returns
+// its rank_key to every lane (0 when nothing is left).
+__device__ inline u64 select_round(unsigned (&o)[EPT], int base, int lane) {
+    unsigned best = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) best = o[j] > best ? o[j] : best;
+    unsigned top = best;
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) {
+        const unsigned t = __shfl_xor(top, s, WAVE);
+        top = t > top ? t : top;
+    }
+    if (top == 0) return 0ull;                        // wave-uniform
+    int my_j = EPT;
+#pragma unroll
+    for (int j = EPT - 1; j >= 0; --j) my_j = o[j] == top ? j : my_j;
+    const unsigned long long holders = __ballot(my_j < EPT);
+    int win = __ffsll((long long)holders) - 1;
+    if (__popcll(holders) > 1) {                      // rare: equal values in several lanes
+        int key = my_j < EPT ? (my_j << 6) | lane : 0x7FFFFFFF;
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) key = min(key, __shfl_xor(key, s, WAVE));
+        win = key & 63;
+    }
+    const int win_j = __shfl(my_j, win, WAVE);
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) o[j] = (lane == win && j == win_j) ? 0u : o[j];
+    const int id = base + (int)(threadIdx.x - lane) + win + win_j * TPB;
+    return ((u64)top << 32) | (u64)(0xFFFFFFFFu - (unsigned)id);
+}
+
 struct AcceptWs {
     double* part_m;     // [B][R][S]
     double* part_s;     // [B][R][S]
@@ -120,6 +156,8 @@ struct AcceptWs {
     double* node_lnpt;  // [B][k]  ln P_t(y)
     double* node_q;     // [B][k]  q(y)
     int32_t* node_key;  // [B][k]
+    int32_t* node_acc;  // [B][k]  the node's own test
+    double* node_z;     // [B][k]  Z~ of the node's softened target
     double* part_z;     // [B][k][S]
     int32_t* draw_row;  // [B]
     int32_t* draw_mode; // [B] 0 = target row (bonus), 1 = positive part of P - q
@@ -133,7 +171,7 @@ __global__ void __launch_bounds__(TPB)
 row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp, AcceptWs ws, int R, int V, int S,
                  double inv_temp, int top_m) {
     __shared__ double shd[TPB / WAVE];
-    __shared__ u64 shu[TPB / WAVE];
+    __shared__ u64 sh_top[2][TPB / WAVE][MAXM];
     const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
     const size_t row = ((size_t)b * R + r) * V;
     const int base = s * SLICE;
@@ -160,33 +198,48 @@ row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
         ws.part_m[pidx] = mx;
         ws.part_s[pidx] = sum;
     }
-    // top_m candidates of this slice, for the logits row and for the draft row
-    for (int which = 0; which < 2; ++which) {
-        unsigned taken = 0;
-        u64* out = (which == 0 ? ws.part_top_t : ws.part_top_q) + pidx * MAXM;
-        for (int round = 0; round < top_m; ++round) {
-            u64 best = 0;
-            int bj = -1;
+    // top_m candidates of this slice, for the logits row and for the draft row.  Every wave first
+    // selects among its own 512 ids, without barriers, on the 32-bit order-preserving image of the
+    // values (0 = taken or out of range): top_m rounds of a wave-wide maximum; among equal values the
+    // lowest id wins, which inside a wave is the lowest j, then the lowest lane.  Wave 0 then merges
+    // the 4 lists (at most 64 candidates: one per lane) on the full (value, id) keys.
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    unsigned ot[EPT], oq[EPT];
 #pragma unroll
-            for (int j = 0; j < EPT; ++j) {
-                const int i = base + threadIdx.x + j * TPB;
-                if (i < V && !((taken >> j) & 1u)) {
-                    const u64 key = rank_key(which == 0 ? lv[j] : qv[j], i);
-                    if (key > best) {
-                        best = key;
-                        bj = j;
-                    }
-                }
+    for (int j = 0; j < EPT; ++j) {
+        const int i = base + threadIdx.x + j * TPB;
+        ot[j] = i < V ? order_u32(lv[j]) : 0u;
+        oq[j] = i < V ? order_u32(qv[j]) : 0u;
+    }
+    for (int round = 0; round < top_m; ++round) {
+        const u64 wt = select_round(ot, base, lane), wq = select_round(oq, base, lane);
+        if (lane == 0) {
+            sh_top[0][wave][round] = wt;
+            sh_top[1][wave][round] = wq;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int w = lane / MAXM, r = lane % MAXM;          // TPB/WAVE * MAXM = 64 candidates
+        u64 ct = r < top_m ? sh_top[0][w][r] : 0ull, cq = r < top_m ? sh_top[1][w][r] : 0ull;
+        u64* out_t = ws.part_top_t + pidx * MAXM;
+        u64* out_q = ws.part_top_q + pidx * MAXM;
+        for (int round = 0; round < top_m; ++round) {
+            const u64 wt = wave_max_u(ct), wq = wave_max_u(cq);   // 0 when the slice ran out of ids
+            ct = ct == wt ? 0ull : ct;
+            cq = cq == wq ? 0ull : cq;
+            if (lane == 0) {
+                out_t[round] = wt;
+                out_q[round] = wq;
             }
-            const u64 win = block_max_u(best, shu);
-            if (win == best && bj >= 0) taken |= 1u << bj;   // ids are unique, so one owner
-            if (threadIdx.x == 0) out[round] = win;          // 0 when the slice ran out of ids
         }
     }
 }
 
+// cand_lds = 1: the 2 * S * top_m candidates of the row fit the dynamic LDS and are read from memory once
 __global__ void __launch_bounds__(WAVE)
-row_merge_kernel(AcceptWs ws, int R, int S, int top_m) {
+row_merge_kernel(AcceptWs ws, int R, int S, int top_m, int cand_lds) {
+    extern __shared__ u64 sh_cand[];                  // [2][S*top_m] when cand_lds
     const int r = blockIdx.x, b = blockIdx.y;
     const int lane = threadIdx.x;
     const size_t ridx = (size_t)b * R + r;
@@ -196,23 +249,40 @@ row_merge_kernel(AcceptWs ws, int R, int S, int top_m) {
     double sum = 0.0;
     for (int s = lane; s < S; s += WAVE) sum += ws.part_s[ridx * S + s] * exp(ws.part_m[ridx * S + s] - m);
     sum = wave_sum_d(sum);
-    // merge the per-slice candidate lists: top_m rounds of a wave-wide maximum
-    int idt[MAXM], idq[MAXM];
-    for (int which = 0; which < 2; ++which) {
-        const u64* cand = (which == 0 ? ws.part_top_t : ws.part_top_q) + ridx * S * MAXM;
-        const int n = S * MAXM;
-        u64 last = ~0ull;           // keys are distinct: select strictly below the previous winner
-        for (int round = 0; round < top_m; ++round) {
-            u64 best = 0;
-            for (int i = lane; i < n; i += WAVE) {
-                if ((i % MAXM) >= top_m) continue;
-                const u64 key = cand[i];
-                if (key < last && key > best) best = key;
-            }
-            best = wave_max_u(best);
-            last = best;
-            (which == 0 ? idt : idq)[round] = key_id(best);
+    // merge the per-slice candidate lists: top_m rounds of a wave-wide maximum; keys are distinct, so
+    // each round selects strictly below the previous winner
+    const u64* gt = ws.part_top_t + ridx * S * MAXM;
+    const u64* gq = ws.part_top_q + ridx * S * MAXM;
+    const int n = S * top_m;
+    if (cand_lds) {
+        for (int i = lane; i < n; i += WAVE) {
+            const int src = (i / top_m) * MAXM + i % top_m;
+            sh_cand[i] = gt[src];
+            sh_cand[n + i] = gq[src];
         }
+        __syncthreads();
+    }
+    int idt[MAXM], idq[MAXM];
+    u64 last_t = ~0ull, last_q = ~0ull;
+    for (int round = 0; round < top_m; ++round) {
+        u64 bt = 0, bq = 0;
+        for (int i = lane; i < n; i += WAVE) {
+            u64 a, c;
+            if (cand_lds) {
+                a = sh_cand[i];
+                c = sh_cand[n + i];
+            } else {
+                const int src = (i / top_m) * MAXM + i % top_m;
+                a = gt[src];
+                c = gq[src];
+            }
+            if (a < last_t && a > bt) bt = a;
+            if (c < last_q && c > bq) bq = c;
+        }
+        last_t = wave_max_u(bt);
+        last_q = wave_max_u(bq);
+        idt[round] = key_id(last_t);
+        idq[round] = key_id(last_q);
     }
     if (lane == 0) {
         int common = 0;
@@ -266,46 +336,70 @@ node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     if (threadIdx.x == 0) ws.part_z[nidx * S + s] = z;
 }
 
-// One wavefront per sequence: the lanes share the sums over the slices, every lane then takes the
-// same (few, sequential) decisions and lane 0 writes them.
+// One wavefront per (sequence, node): Z~ of the node's softened target from the slice partials, the
+// node's test u * q(y) < P~(y), and the optional statistics.
 __global__ void __launch_bounds__(WAVE)
-decide_kernel(const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws,
-              dsd_accept_params prm, int B, int k, int S, int32_t* __restrict__ accepted_len,
-              int32_t* __restrict__ accepted_path, dsd_accept_stats st) {
-    const int b = blockIdx.x;
+node_accept_kernel(const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws, int k, int S,
+                   dsd_accept_stats st) {
+    const int i = blockIdx.x + 1, b = blockIdx.y;
     const int lane = threadIdx.x;
-    const bool writer = lane == 0;
     const int R = k + 1;
-    int par[DSD_MAX_K + 1], dep[DSD_MAX_K + 1];
-    bool ok[DSD_MAX_K + 1], acc[DSD_MAX_K + 1];
-    double zt[DSD_MAX_K + 1];
-    par[0] = 0; dep[0] = 0; ok[0] = true; acc[0] = true; zt[0] = 1.0;
-    for (int i = 1; i <= k; ++i) {
-        int p = parent ? parent[i - 1] : i - 1;
-        p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
-        par[i] = p;
-        dep[i] = dep[p] + 1;
-        const size_t nidx = (size_t)b * k + i - 1;
-        const double tau = ws.node_tau[nidx];
-        double z = 1.0;
-        if (tau != 0.0) {
-            z = 0.0;
-            for (int s = lane; s < S; s += WAVE) z += ws.part_z[nidx * S + s];
-            z = wave_sum_d(z);
-        }
-        zt[i] = z;
-        const double q_y = ws.node_q[nidx];
-        const double p_y = soft_weight(ws.node_lnpt[nidx], q_y, tau) / z;
-        const double u = (double)uniforms[(size_t)b * R + i];
-        acc[i] = u * q_y < p_y;
-        ok[i] = acc[i] && ok[p];
-        if (writer) {
-            if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
-            if (st.node_accept) st.node_accept[nidx] = acc[i] ? 1 : 0;
-            if (st.ratio) st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
-            if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
-        }
+    int p = parent ? parent[i - 1] : i - 1;
+    p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
+    const size_t nidx = (size_t)b * k + i - 1;
+    const double tau = ws.node_tau[nidx];
+    double z = 1.0;
+    if (tau != 0.0) {
+        z = 0.0;
+        for (int s = lane; s < S; s += WAVE) z += ws.part_z[nidx * S + s];
+        z = wave_sum_d(z);
     }
+    if (lane != 0) return;
+    const double q_y = ws.node_q[nidx];
+    const double p_y = soft_weight(ws.node_lnpt[nidx], q_y, tau) / z;
+    const double u = (double)uniforms[(size_t)b * R + i];
+    const bool acc = u * q_y < p_y;
+    ws.node_z[nidx] = z;
+    ws.node_acc[nidx] = acc ? 1 : 0;
+    if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
+    if (st.node_accept) st.node_accept[nidx] = acc ? 1 : 0;
+    if (st.ratio) st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
+    if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
+}
+
+// One workgroup per sequence: thread i = node i (0 = the root) walks up to the root for its depth and
+// for whether it and all its ancestors passed their tests; thread 0 then picks the accepted path and
+// what the extra token is drawn from.  The tree lives in LDS.
+#define DECIDE_TPB 128
+__global__ void __launch_bounds__(DECIDE_TPB)
+decide_kernel(const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params prm, int k,
+              int32_t* __restrict__ accepted_len, int32_t* __restrict__ accepted_path) {
+    __shared__ int par[DSD_MAX_K + 1], acc[DSD_MAX_K + 1], dep[DSD_MAX_K + 1], ok[DSD_MAX_K + 1];
+    const int b = blockIdx.x;
+    const int i = threadIdx.x;
+    if (i <= k) {
+        int p = 0, a = 1;
+        if (i > 0) {
+            p = parent ? parent[i - 1] : i - 1;
+            p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
+            a = ws.node_acc[(size_t)b * k + i - 1] != 0;
+        }
+        par[i] = p;
+        acc[i] = a;
+    }
+    if (accepted_path && i < k) accepted_path[(size_t)b * k + i] = -1;
+    __syncthreads();
+    if (i <= k) {
+        int d = 0, good = acc[i];
+        for (int n = i; n != 0; n = par[n]) {        // parents precede children: at most k steps
+            ++d;
+            good &= acc[par[n]];
+        }
+        dep[i] = d;
+        ok[i] = good;
+    }
+    __syncthreads();
+    if (i != 0) return;
     int vstar = 0;
     if (prm.tree_mode == DSD_TREE_FIRST_ACCEPTED) {
         for (;;) {
@@ -316,16 +410,13 @@ decide_kernel(const int32_t* __restrict__ parent, const float* __restrict__ unif
             vstar = nxt;
         }
     } else {
-        for (int i = 1; i <= k; ++i)
-            if (ok[i] && dep[i] > dep[vstar]) vstar = i;
+        for (int c = 1; c <= k; ++c)
+            if (ok[c] && dep[c] > dep[vstar]) vstar = c;
     }
     const int a = dep[vstar];
-    if (!writer) return;
     accepted_len[b] = a;
-    if (accepted_path) {
-        for (int j = 0; j < k; ++j) accepted_path[(size_t)b * k + j] = -1;
+    if (accepted_path)
         for (int n = vstar, j = a - 1; n != 0; n = par[n], --j) accepted_path[(size_t)b * k + j] = n;
-    }
     int child = 0;
     for (int c = vstar + 1; c <= k; ++c)
         if (par[c] == vstar) { child = c; break; }
@@ -337,7 +428,7 @@ decide_kernel(const int32_t* __restrict__ parent, const float* __restrict__ unif
     } else {
         ws.draw_mode[b] = 1;
         ws.draw_tau[b] = ws.node_tau[(size_t)b * k + child - 1];
-        ws.draw_z[b] = zt[child];
+        ws.draw_z[b] = ws.node_z[(size_t)b * k + child - 1];
     }
 }
 
@@ -510,8 +601,8 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     const int R = k + 1;
     const int S = (V + SLICE - 1) / SLICE;
     const size_t BR = (size_t)B * R, BK = (size_t)B * k;
-    size_t need = (BR * S * 2 + BR * 2 + BK * 3 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
-                  BR * S * MAXM * 8 * 2 + (BK + 2 * (size_t)B) * 4 + 32 * 256;
+    size_t need = (BR * S * 2 + BR * 2 + BK * 4 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
+                  BR * S * MAXM * 8 * 2 + (2 * BK + 2 * (size_t)B) * 4 + 32 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
     WsBump bump{ctx->ws, 0};
     AcceptWs ws;
@@ -525,6 +616,8 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     ws.node_lnpt = bump.take<double>(BK);
     ws.node_q = bump.take<double>(BK);
     ws.node_key = bump.take<int32_t>(BK);
+    ws.node_acc = bump.take<int32_t>(BK);
+    ws.node_z = bump.take<double>(BK);
     ws.part_z = bump.take<double>(BK * S);
     ws.draw_row = bump.take<int32_t>(B);
     ws.draw_mode = bump.take<int32_t>(B);
@@ -540,9 +633,12 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     if (B > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
     ProfScope ps(ctx, DSD_KC_ACCEPT);
     row_stats_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp, prm->top_m);
-    row_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->top_m);
+    const size_t cand_bytes = (size_t)2 * S * prm->top_m * sizeof(u64);
+    const int cand_lds = cand_bytes <= 48 * 1024;
+    row_merge_kernel<<<dim3(R, B), WAVE, cand_lds ? cand_bytes : 0, s>>>(ws, R, S, prm->top_m, cand_lds);
     node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, *prm, k, V, S, inv_temp);
-    decide_kernel<<<B, WAVE, 0, s>>>(parent, uniforms, ws, *prm, B, k, S, accepted_len, accepted_path, st);
+    node_accept_kernel<<<dim3(k, B), WAVE, 0, s>>>(parent, uniforms, ws, k, S, st);
+    decide_kernel<<<B, DECIDE_TPB, 0, s>>>(parent, ws, *prm, k, accepted_len, accepted_path);
     draw_parts_kernel<<<dim3(S, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
     draw_pick_kernel<<<B, TPB, 0, s>>>(logits, draft_probs, uniforms, ws, R, V, S, inv_temp, next_token);
     DSD_HIP(hipGetLastError());
