@@ -102,6 +102,47 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restr
     }
 }
 
+// The same for 6 or 8 row tiles, where one k-step is 24..32 matrix instructions behind 12..16 LDS
+// reads: the row tiles are taken in two halves and the activation fragments of the next half are
+// requested before the matrix instructions of the current one, so that LDS latency hides behind
+// them (a computing wave has no partner on its SIMD to do that for it).  A weight fragment is used
+// by both halves and its FIFO slot refilled after the second, so when slot (ks, nt) is waited for,
+// the refills of (ks, 0..nt-1) have not been issued yet: NF - 1 - nt younger loads.
+template <int MT, int NF, int S0>
+__device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* __restrict__ panel,
+                                                f32x4 (&acc)[MT][NTW], const uint4* (&w)[NTW], int& left, int lane) {
+    constexpr int H = MT / 2;
+    bf16x8 a[2][2 * H];                               // [buffer][hi of H tiles, lo of H tiles]
+    auto fetch = [&](int buf, int ks, int half) {
+#pragma unroll
+        for (int m = 0; m < H; ++m) {
+            a[buf][m] = __builtin_bit_cast(bf16x8, panel[(ks * MT + half * H + m) * 64 + lane]);
+            a[buf][H + m] = __builtin_bit_cast(bf16x8, panel[4 * MT * 64 + (ks * MT + half * H + m) * 64 + lane]);
+        }
+    };
+    fetch(0, 0, 0);
+#pragma unroll
+    for (int hs = 0; hs < 8; ++hs) {
+        const int ks = hs >> 1, half = hs & 1;
+        if (hs + 1 < 8) fetch((hs + 1) & 1, (hs + 1) >> 1, (hs + 1) & 1);
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            const int slot = S0 + ks * NTW + nt;
+            if (half == 0) {
+                if (nt == 0) vm_wait<NF - 1>(fifo[slot]);
+                else vm_wait<NF - 2>(fifo[slot]);
+            }
+            const bf16x8 b = __builtin_bit_cast(bf16x8, fifo[slot]);
+#pragma unroll
+            for (int m = 0; m < H; ++m) acc[half * H + m][nt] = mfma16(a[hs & 1][m], b, acc[half * H + m][nt]);
+#pragma unroll
+            for (int m = 0; m < H; ++m) acc[half * H + m][nt] = mfma16(a[hs & 1][H + m], b, acc[half * H + m][nt]);
+            if (half == 1) gload16(fifo[slot], w[nt]);
+        }
+        if (half == 1) tadvance(w, left);
+    }
+}
+
 // TWC computing waves (4 or 8), each MT 16-row tiles x NTW 16-column tiles; waves TWC .. TWC+3 fetch
 // the panel.  More computing waves per workgroup mean fewer workgroups fetching the same panel.  The
 // second launch bound is waves per SIMD: two resident workgroups for the smallest tiles.
@@ -167,7 +208,8 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
     // ks_per_split is a multiple of 16 k-steps = 4 chunks
 #define TILED_CHUNK(Q)                                                                          \
     {                                                                                           \
-        tconsume<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
+        if (MT >= 6) tconsume_halves<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
+        else tconsume<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
         __syncthreads();                                                                        \
     }
     for (int ch = 0; ch < nchunk; ch += 4) {
