@@ -59,7 +59,7 @@ def cpu_baseline(cfg, weights, K, V, hid, parent, sample_layers):
     sample_layers = sample_layers or cfg.model.L
     m = W.scaled(cfg, L=sample_layers, has_head=False, V=0).model
     reps, dt = 0, 0.0
-    while reps < 3 and dt < 10.0:          # about 10-30 s of CPU work
+    while dt < 10.0 and reps < 50:         # about 10-30 s of CPU work
         t0 = time.perf_counter()
         O.stage_forward(m, weights.__getitem__, K[:sample_layers], V[:sample_layers], [cfg.C] * cfg.B, hid, None,
                         parent=parent)
