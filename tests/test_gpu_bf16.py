@@ -83,6 +83,23 @@ def test_max_rows_tree_32_nodes():
     check(mini("mini_m128", B=4, k=32, lens=[150, 90, 33, 64], tree=((4, 3, 2, 2, 1, 1), 32), head=True, L=1))
 
 
+def test_two_and_three_row_tiles():
+    check(mini("mini_m24", B=4, k=6, lens=[100, 5, 64, 33]))
+    check(mini("mini_m40", B=5, k=8, lens=[17, 200, 63, 1, 128], head=True, V=4112, L=1))
+
+
+def test_six_row_tiles():
+    # 80 and 96 rows both run the 6-tile kernels (row tiles taken in two halves of 3)
+    check(mini("mini_m80", B=10, k=8, lens=[30, 200, 64, 65, 1, 100, 7, 150, 90, 129], head=True, V=4112, L=1))
+    check(mini("mini_m96", B=12, k=8, lens=[60] * 12, L=1))
+
+
+def test_wide_ffn_picks_eight_computing_waves():
+    # with this many gate/up columns the 17..64-row GEMM runs 8 computing waves per workgroup
+    check(mini("mini_wide24", B=4, k=6, lens=[50, 20, 64, 9], F=26624, L=1))
+    check(mini("mini_wide64", B=8, k=8, lens=[50, 20, 64, 9, 1, 100, 33, 80], F=26624, L=1))
+
+
 def test_empty_context():
     check(mini("mini_empty", B=2, k=6, lens=[0, 0]))
 
