@@ -340,7 +340,13 @@ template <int MT, int TWC, int EPI>
 static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
     const size_t lds = (size_t)2 * 2 * 4 * MT * 64 * 16;
     auto kern = gemm_tiled_kernel<MT, TWC, EPI>;
-    if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    // once per instantiation and process: the limit is a property of the function, and setting it
+    // again on every call would put a non-stream call into a caller's graph capture
+    static bool raised = false;
+    if (lds > 64 * 1024 && !raised) {
+        DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        raised = true;
+    }
     kern<<<dim3(n_blocks, ksplit), (TWC + TP) * 64, lds, s>>>(p);
     return DSD_OK;
 }

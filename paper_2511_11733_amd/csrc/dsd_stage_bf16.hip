@@ -199,7 +199,13 @@ static int launch_gemm(hipStream_t s, const GemmArgs& p, int n_blocks) {
     const int nw = NW;
     const size_t lds = (size_t)nw * MT * NT * 64 * 16 + (size_t)nw * MT * 16 * 4;
     auto kern = gemm_skinny_kernel<MT, NT, AMODE, EPI, NW>;
-    if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    // once per instantiation and process: the limit is a property of the function, and setting it
+    // again on every call would put a non-stream call into a caller's graph capture
+    static bool raised = false;
+    if (lds > 64 * 1024 && !raised) {
+        DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        raised = true;
+    }
     kern<<<n_blocks, nw * 64, lds, s>>>(p);
     return DSD_OK;
 }
@@ -383,7 +389,13 @@ template <int RT>
 static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int waves_per_wg, int Hkv, int B) {
     const size_t lds = (size_t)waves_per_wg * 2 * ATT_STAGE_BYTES;
     auto kern = attn_stream_kernel<RT>;
-    if (lds > 64 * 1024) DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    // once per instantiation and process: the limit is a property of the function, and setting it
+    // again on every call would put a non-stream call into a caller's graph capture
+    static bool raised = false;
+    if (lds > 64 * 1024 && !raised) {
+        DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        raised = true;
+    }
     kern<<<dim3(((t.n_runs + waves_per_wg - 1) / waves_per_wg) * n_rg, Hkv, B), waves_per_wg * 64, lds, s>>>(t, n_rg);
     return DSD_OK;
 }
@@ -397,6 +409,10 @@ __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ o
 }
 
 // ============================================================================ small kernels
+__global__ void zero16_kernel(uint4* __restrict__ p, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
 __global__ void rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__ h, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) x[i] = bf16_to_f32(h[i]);
@@ -466,7 +482,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     hipStream_t s = ctx->stream;
     // split-K partial sums of the QKV projection meet in qkv_acc (every layer leaves it cleared again);
     // qkv_acc and ssq_all are adjacent: one fill
-    if (tiled) DSD_HIP(hipMemsetAsync(qkv_acc, 0, (size_t)((char*)(ssq_all + n_ssq) - (char*)qkv_acc), s));
+    // (a kernel rather than a memset, so that a caller may capture the call into a HIP graph)
+    if (tiled) {
+        const size_t n16 = (size_t)((char*)(ssq_all + n_ssq) - (char*)qkv_acc) / 16;
+        zero16_kernel<<<(unsigned)((n16 + 255) / 256), 256, 0, s>>>((uint4*)qkv_acc, n16);
+    }
 
     const size_t nx = (size_t)M * d;
     {

@@ -152,3 +152,44 @@ def test_shape_errors():
         H.D.dsd_stage_verify(st.ctx, st.w, st.kv, st._cast(hid), None, None, None, 2, 4, None, lg)
     with pytest.raises(H.D.DsdError):            # batch larger than the cache
         H.D.dsd_stage_verify(st.ctx, st.w, st.kv, st._cast(hid), None, None, None, 3, 4, st._cast(hid), None)
+
+
+def test_stage_replays_from_a_hip_graph():
+    """Once the workspace has its size the call issues only kernels on the context's stream, so a caller
+    may capture it; every replay (with eager work and synchronisations in between) must reproduce the
+    eager result: bit for bit where the arithmetic is ordered (<= 16 rows), to 1e-4 where K-split sums
+    meet by atomics (more rows)."""
+    for name, B, k in (("graph_m5", 1, 5), ("graph_m40", 5, 8)):
+        cfg, m, w, K, V, hid, parent, lens = mini(name, B=B, k=k, lens=[70 + 9 * b for b in range(B)], head=True,
+                                                  V=4112, L=2)
+        stream = torch.cuda.Stream()
+        ctx = H.D.Context(0, stream)
+        st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3, ctx=ctx)
+        with torch.cuda.stream(stream):
+            st.import_kv(K, V, lens)
+            h = st._cast(hid)
+            out = torch.empty((B, k, m.d), dtype=torch.bfloat16, device="cuda:0")
+            lg = torch.empty((B, k, m.V), dtype=torch.float32, device="cuda:0")
+
+            def run():
+                H.D.dsd_stage_verify(ctx, st.w, st.kv, h, None, None, None, B, k, out, lg, 0, 0)
+
+            run()                                             # eager: sizes the workspace
+            stream.synchronize()
+            out_ref, lg_ref = out.clone(), lg.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                run()
+            stream.synchronize()
+            for rep in range(3):
+                out.zero_()
+                lg.zero_()
+                stream.synchronize()
+                g.replay()
+                stream.synchronize()
+                if B * k <= 16:
+                    assert torch.equal(out, out_ref) and torch.equal(lg, lg_ref), f"{name}: replay {rep} differs"
+                else:
+                    H.assert_close(H.to_np64(lg), H.to_np64(lg_ref), H.TOL["f32"], f"{name} logits, replay {rep}")
+                run()                                         # eager work between the replays
+                stream.synchronize()
