@@ -43,7 +43,7 @@ enum dsd_status {
 };
 
 enum dsd_dtype { DSD_F32 = 0, DSD_BF16 = 1 };
-enum dsd_tree_mode { DSD_TREE_LONGEST = 0, DSD_TREE_FIRST_ACCEPTED = 1 };
+enum dsd_tree_mode { DSD_TREE_LONGEST = 0, DSD_TREE_FIRST_ACCEPTED = 1, DSD_TREE_LOSSLESS = 2 };
 
 #define DSD_MAX_K 64      /* drafted rows per sequence (tree masks are 64-bit rows) */
 #define DSD_MAX_TOP_M 16  /* support size of NormMatch                             */
@@ -166,11 +166,22 @@ int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void*
  * drawn from P_t of that node's row; otherwise from the normalised positive part of P - q of
  * that row, P as used for its lowest-id child (if that is all zero, from P); drawn by inverse
  * CDF in token-id order with u_0.
+ * DSD_TREE_LOSSLESS replaces the per-node test by recursive rejection over siblings that were
+ * drawn WITHOUT replacement from their parent's draft row (the token-tree verification of the
+ * SpecInfer line of work cited in section 1), which keeps the target distribution when a node
+ * has several children: at node v, starting from p = P_t(. | v) and q = draft row v, the children
+ * are tried in node order; child c with token y passes when u_c * q(y) < p(y); after a rejection
+ * p becomes the normalised positive part of p - q and q loses y and is renormalised.  The first
+ * passing child becomes v (its own rows are used from there); when no child passes, or v is a
+ * leaf, the additional token is drawn from the p that is left.  The relaxation (tau) is not
+ * applied in this mode; key flags and NormMatch are still reported, node_accept and ratio only
+ * for the nodes the walk tried (0 elsewhere).  A chain gives the same result as the strict rule.
  *   accepted_len  device int32 [B]
  *   next_token    device int32 [B]
  *   accepted_path device int32 [B,k] node ids of the path, -1 padded; may be NULL
  *   stats         optional, may be NULL
- * All vocabulary-wide reductions run in fp64; no probability row is written to memory. */
+ * Sums over the vocabulary are accumulated in fp64 from fp32 per-id terms; every quantity that
+ * decides something by itself is fp64; no probability row is written to memory. */
 int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                const int32_t* parent, const float* uniforms, const dsd_accept_params* params,
                int B, int k, int V, int32_t* accepted_len, int32_t* next_token,

@@ -210,6 +210,7 @@ def kv_commit(kv_k: np.ndarray, kv_v: np.ndarray, ctx_len: np.ndarray, new_k: np
 # =============================================================================== accept
 TREE_LONGEST = 0
 TREE_FIRST_ACCEPTED = 1
+TREE_LOSSLESS = 2      # recursive rejection over siblings drawn without replacement (see accept_lossless)
 
 
 @dataclass
@@ -307,6 +308,8 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
     if parent is None:
         parent = list(range(k))
     parent = [int(p) for p in parent]
+    if prm.tree_mode == TREE_LOSSLESS:
+        return accept_lossless(logits, draft_probs, draft_tokens, parent, uniforms, prm)
     children: Dict[int, List[int]] = {}
     for i in range(1, k + 1):
         children.setdefault(parent[i - 1], []).append(i)
@@ -408,6 +411,98 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
             if w.sum() == 0.0:
                 w = ptil
         tok, gap = inverse_cdf(w, u0)
+        if gap < 1e-6:
+            out.near_tie[b] |= 4
+        out.next_token[b] = tok
+    return out
+
+
+def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray, parent: Sequence[int],
+                    uniforms: np.ndarray, prm: AcceptParams) -> AcceptOut:
+    """Tree verification that keeps the target distribution when a node has several children.
+
+    The paper verifies chains (section 2.1, Algorithm 1); for the token trees of the line of work
+    it builds on (SpecInfer, cited in section 1) the accept test generalises to recursive rejection
+    over the siblings, here for siblings drawn WITHOUT replacement from the parent's draft row:
+    at node v with target row p_1 = P_t(. | v) and draft row q_1 = q_v, for the children c_1, c_2, ...
+    in node order with tokens y_1, y_2, ...
+
+        accept c_i  iff  u_{c_i} * q_i(y_i) < p_i(y_i)                     (probability min(1, p_i/q_i))
+        on rejection    p_{i+1} = norm(max(0, p_i - q_i)),
+                        q_{i+1} = q_i with y_i removed, renormalised        (the law of the next sibling)
+
+    The first accepted child becomes v and the walk goes on with ITS rows; when every child of v is
+    rejected (or v is a leaf) the additional token is drawn from the p that is left (the target row
+    itself at a leaf) by inverse CDF with u_0.  The adaptive relaxation is not applied in this mode
+    (tau_i = 0 for every node: the rule is about keeping P_t exactly); key flags and NormMatch are
+    still reported.  node_accept and ratio are set for the nodes the walk tested, 0 elsewhere.
+    A chain is the special case of one child per node and reproduces the strict chain rule."""
+    B, k1, V = logits.shape
+    k = k1 - 1
+    children: Dict[int, List[int]] = {}
+    for i in range(1, k + 1):
+        children.setdefault(parent[i - 1], []).append(i)
+    out = AcceptOut(
+        accepted_len=np.zeros(B, dtype=np.int32), next_token=np.zeros(B, dtype=np.int32),
+        accepted_path=-np.ones((B, max(k, 1)), dtype=np.int32), key=np.zeros((B, k), dtype=bool),
+        node_accept=np.zeros((B, k), dtype=bool), tau_used=np.zeros((B, k)), ratio=np.zeros((B, k)),
+        norm_match=np.zeros((B, k)), near_tie=np.zeros(B, dtype=np.int32))
+    for b in range(B):
+        # key flags and NormMatch as in the other modes (reported only)
+        for i in range(1, k + 1):
+            p_row = parent[i - 1]
+            y = int(draft_tokens[b, i - 1])
+            pt = softmax_row(logits[b, p_row], prm.temperature)
+            q = draft_probs[b, p_row].astype(F64)
+            nm = norm_match(pt, q, prm.top_m)
+            out.key[b, i - 1] = is_key(pt[y], q[y], nm, prm)
+            out.norm_match[b, i - 1] = nm
+            srt_rows = (np.sort(pt)[::-1], np.sort(q)[::-1])
+            for srt in srt_rows:
+                if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
+                    out.near_tie[b] |= 2
+            with np.errstate(divide="ignore", invalid="ignore"):
+                h_t, h_d = -np.log(pt[y]), -np.log(q[y])
+                if np.isfinite(prm.lambda1) and np.isfinite(h_t) and np.isfinite(h_d) and \
+                        abs(h_d - prm.lambda1 * h_t) < 1e-3 * abs(prm.lambda1 * h_t):
+                    out.near_tie[b] |= 2
+            if np.isfinite(prm.lambda2) and abs(abs(pt[y] - q[y]) - prm.lambda2) < 1e-3 * prm.lambda2:
+                out.near_tie[b] |= 2
+        v = 0
+        path: List[int] = []
+        while True:
+            p = softmax_row(logits[b, v], prm.temperature)
+            q = draft_probs[b, v].astype(F64).copy()
+            taken = None
+            for c in children.get(v, []):
+                y = int(draft_tokens[b, c - 1])
+                u = F64(uniforms[b, c])
+                acc = bool(u * q[y] < p[y])
+                with np.errstate(divide="ignore", invalid="ignore"):
+                    ratio = p[y] / q[y] if q[y] > 0 else (np.inf if p[y] > 0 else 0.0)
+                if abs(ratio - u) < 1e-3:
+                    out.near_tie[b] |= 1
+                out.node_accept[b, c - 1] = acc
+                out.ratio[b, c - 1] = ratio
+                if acc:
+                    taken = c
+                    break
+                r = np.maximum(p - q, 0.0)
+                s = r.sum()
+                if s > 0.0:
+                    p = r / s
+                q[y] = 0.0
+                s = q.sum()
+                if s > 0.0:
+                    q = q / s
+            if taken is None:
+                break
+            path.append(taken)
+            v = taken
+        a = len(path)
+        out.accepted_len[b] = a
+        out.accepted_path[b, :a] = path
+        tok, gap = inverse_cdf(p, F64(uniforms[b, 0]))
         if gap < 1e-6:
             out.near_tie[b] |= 4
         out.next_token[b] = tok

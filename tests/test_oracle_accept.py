@@ -409,3 +409,149 @@ def test_synthetic_draft_acceptance_rate_matches_closed_form():
     q = O.softmax_row(lo + s * rng.standard_normal(V), 1.0)
     alpha = np.minimum(pt, q).sum()
     assert abs(alpha - 2 * stats.norm.cdf(-s / 2)) < 0.01
+
+
+# ------------------------------------------------------------------ lossless multi-sibling tree rule
+def _lossless_first_token(pt, q, m, child_rows=None):
+    """Exact law of the first emitted token at a root with m leaf children drawn without replacement
+    from q, recovered from the oracle's decisions only (bisection on the uniforms)."""
+    import itertools
+    V = len(pt)
+    prm = O.AcceptParams(tree_mode=O.TREE_LOSSLESS)
+    rows = [logits_of(pt)] + [logits_of(rand_dist(np.random.default_rng(90 + i), V)) for i in range(m)]
+    qrows = [q] + [np.full(V, 1.0 / V)] * m
+    parent = [0] * m
+    hi = np.nextafter(1.0, 0)
+    law = np.zeros(V)
+    for ys in itertools.permutations(range(V), m):
+        w, left = 1.0, 1.0
+        for y in ys:                       # probability of drawing this ordered tuple without replacement
+            w *= q[y] / left if left > 0 else 0.0
+            left -= q[y]
+        if w == 0.0:
+            continue
+        reach = 1.0                        # probability that siblings 0..i-1 were all rejected
+        for i in range(m):
+            def accepted(u, i=i):
+                uu = [0.5] + [hi] * i + [u] + [hi] * (m - i - 1)
+                r = run1(rows, qrows, list(ys), uu, prm, parent)
+                return r.accepted_len[0] == 1 and r.accepted_path[0][0] == i + 1
+            A = sup_where(accepted)
+            law[ys[i]] += w * reach * A
+            reach *= 1.0 - A
+            if reach == 0.0:
+                break
+        if reach > 0.0:
+            cdf = np.array([sup_where(lambda u0, v=v: run1(rows, qrows, list(ys), [u0] + [hi] * m, prm,
+                                                              parent).next_token[0] <= v) for v in range(V)])
+            law += w * reach * np.diff(np.concatenate([[0.0], cdf]))
+    return law
+
+
+@pytest.mark.parametrize("V,m,seed", [(4, 2, 0), (5, 2, 1), (5, 3, 2), (6, 4, 3)])
+def test_lossless_tree_rule_emits_the_target_exact(V, m, seed):
+    rng = np.random.default_rng(seed)
+    pt, q = rand_dist(rng, V, 1.5), rand_dist(rng, V, 0.7)
+    law = _lossless_first_token(pt, q, m)
+    np.testing.assert_allclose(law, pt, atol=1e-9)
+
+
+def test_lossless_tree_rule_with_zero_mass_tokens():
+    pt = np.array([0.0, 0.5, 0.3, 0.2, 0.0])
+    q = np.array([0.3, 0.0, 0.3, 0.2, 0.2])
+    law = _lossless_first_token(pt, q, 2)
+    np.testing.assert_allclose(law, pt, atol=1e-9)
+
+
+def test_lossless_chain_is_the_strict_chain_rule():
+    rng = np.random.default_rng(5)
+    B, k, V = 64, 5, 12
+    lo = rng.normal(size=(B, k + 1, V))
+    q = np.stack([[rand_dist(rng, V) for _ in range(k + 1)] for _ in range(B)])
+    toks = rng.integers(0, V, size=(B, k)).astype(np.int32)
+    u = rng.random((B, k + 1))
+    a = O.accept(lo, q, toks, None, u, O.AcceptParams(tree_mode=O.TREE_LONGEST))
+    b = O.accept(lo, q, toks, None, u, O.AcceptParams(tree_mode=O.TREE_LOSSLESS))
+    np.testing.assert_array_equal(a.accepted_len, b.accepted_len)
+    np.testing.assert_array_equal(a.next_token, b.next_token)
+    np.testing.assert_array_equal(a.accepted_path, b.accepted_path)
+    # the nodes the walk reached carry the same tests; the walk stops at the first rejection
+    for s in range(B):
+        n = int(a.accepted_len[s])
+        np.testing.assert_array_equal(a.node_accept[s, :min(n + 1, k)], b.node_accept[s, :min(n + 1, k)])
+        assert not b.node_accept[s, n + 1:].any()
+
+
+def test_lossless_walk_continues_with_the_accepted_childs_rows():
+    """Two levels: whichever child of the root is accepted, the next token follows that child's own
+    target row (its children are held to it, and their siblings' residual starts from it)."""
+    V = 4
+    rng = np.random.default_rng(11)
+    parent = [0, 0, 1, 1, 2, 2]
+    pts = [rand_dist(rng, V, 1.2) for _ in range(7)]
+    qs = [rand_dist(rng, V, 0.8) for _ in range(7)]
+    rows = [logits_of(p) for p in pts]
+    prm = O.AcceptParams(tree_mode=O.TREE_LOSSLESS)
+    hi = np.nextafter(1.0, 0)
+    for first, kids in ((1, (3, 4)), (2, (5, 6))):
+        import itertools
+        law = np.zeros(V)
+        for ys in itertools.permutations(range(V), 2):
+            w = qs[first][ys[0]] * qs[first][ys[1]] / (1.0 - qs[first][ys[0]])
+            # node 1 holds a token the target under-weights (so that it can be rejected), node 2 one
+            # that survives in the residual (so that it can be accepted after that rejection)
+            toks = [int(np.argmin(pts[0] / qs[0])), int(np.argmax(pts[0] - qs[0])), 0, 0, 0, 0]
+            toks[kids[0] - 1], toks[kids[1] - 1] = ys
+            base = [0.5] + [hi] * 6
+            # force the walk into `first`: reject the elder sibling if there is one, accept `first`
+            base[first] = 0.0
+            reach = 1.0
+            for i, c in enumerate(kids):
+                def accepted(u, i=i, c=c):
+                    uu = list(base)
+                    for j in range(i):
+                        uu[kids[j]] = hi
+                    uu[c] = u
+                    r = run1(rows, qs, toks, uu, prm, parent)
+                    return r.accepted_len[0] == 2 and r.accepted_path[0][1] == c
+                A = sup_where(accepted)
+                law[ys[i]] += w * reach * A
+                reach *= 1.0 - A
+            if reach > 0:
+                cdf = np.array([sup_where(lambda u0, v=v: run1(rows, qs, toks, [u0] + base[1:], prm,
+                                                                  parent).next_token[0] <= v) for v in range(V)])
+                law += w * reach * np.diff(np.concatenate([[0.0], cdf]))
+        np.testing.assert_allclose(law, pts[first], atol=1e-9)
+
+
+def test_lossless_monte_carlo_tree():
+    """Chi-square over seeds on a 3-2 tree, vocabulary 8: first emitted token ~ P_t(root)."""
+    rng = np.random.default_rng(21)
+    V, N = 8, 20000
+    parent = [int(x) for x in W.ranked_tree_parents((3, 2), 9)]
+    k = len(parent)
+    pt = [rand_dist(rng, V, 1.3) for _ in range(k + 1)]
+    qd = [rand_dist(rng, V, 0.9) for _ in range(k + 1)]
+    lo = np.tile(np.stack([logits_of(p) for p in pt])[None], (N, 1, 1))
+    q = np.tile(np.stack(qd)[None], (N, 1, 1))
+    toks = np.zeros((N, k), dtype=np.int32)
+    ud = rng.random((N, k))
+    kids = W.children_of(np.asarray(parent))
+    for n in range(N):
+        for p_node, cs in kids.items():
+            qq = qd[p_node].copy()
+            for c in cs:
+                t = W.draw_categorical(qq, float(ud[n, c - 1]))
+                toks[n, c - 1] = t
+                qq[t] = 0.0
+    u = rng.random((N, k + 1))
+    r = O.accept(lo, q, toks, parent, u, O.AcceptParams(tree_mode=O.TREE_LOSSLESS))
+    first = np.where(r.accepted_len > 0, toks[np.arange(N), np.maximum(r.accepted_path[:, 0], 1) - 1], r.next_token)
+    cnt = np.bincount(first, minlength=V)
+    chi2 = float(((cnt - N * pt[0]) ** 2 / (N * pt[0])).sum())
+    assert chi2 < 30.0, chi2            # 7 degrees of freedom: P(chi2 > 30) ~ 1e-4
+    # and the plain per-node rule on the same inputs is visibly NOT the target (what this mode fixes)
+    r0 = O.accept(lo, q, toks, parent, u, O.AcceptParams(tree_mode=O.TREE_FIRST_ACCEPTED))
+    first0 = np.where(r0.accepted_len > 0, toks[np.arange(N), np.maximum(r0.accepted_path[:, 0], 1) - 1], r0.next_token)
+    cnt0 = np.bincount(first0, minlength=V)
+    assert float(((cnt0 - N * pt[0]) ** 2 / (N * pt[0])).sum()) > 60.0
