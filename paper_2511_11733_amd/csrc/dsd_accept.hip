@@ -595,6 +595,220 @@ draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     }
 }
 
+// ---------------------------------------------------------------------------- DSD_TREE_LOSSLESS
+// Recursive rejection over siblings drawn without replacement (see dsd.h).  One workgroup per
+// sequence walks down the tree; what it carries at a node after n rejected children is the chain
+//     p_{j+1}(id) = max(0, p_j(id) - q_j(id)) / Z_j,   q_j(id) = [id not among y_0..y_{j-1}] q(id) / (1 - R_j)
+// with Z_j the sum of the positive parts and R_j the draft mass of the removed tokens, so that any
+// p_n(id) is a few operations on the two rows and 2n stored scalars.  A child's test evaluates the
+// chain for its own token in fp64; a rejection costs one pass of the workgroup over the vocabulary
+// (fp32 terms, fp64 sum) for the next Z; the additional token costs one pass for the per-thread
+// masses of contiguous id ranges, a scan, and a rescan of one range.
+#define WALK_TPB 1024
+struct WalkChain {
+    int n;                            // rejections so far at this node
+    const int* y;                     // [n] removed tokens
+    const float* inv_z;               // [n] 1/Z_j, 0 = "p_j equals q_j: keep p"
+    const float* q_scale;             // [n+1] 1/(1 - R_j), 0 when the draft row is used up
+};
+__device__ inline float walk_p(const WalkChain& c, float p1, float q1, int id, float* q_n) {
+    float p = p1;
+    bool removed = false;
+    for (int j = 0; j < c.n; ++j) {
+        const float qj = removed ? 0.f : q1 * c.q_scale[j];
+        if (c.inv_z[j] > 0.f) p = fmaxf(p - qj, 0.f) * c.inv_z[j];
+        removed = removed || id == c.y[j];
+    }
+    *q_n = removed ? 0.f : q1 * c.q_scale[c.n];
+    return p;
+}
+
+__global__ void __launch_bounds__(WALK_TPB)
+lossless_walk_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const int32_t* __restrict__ tokens,
+                     const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws, int k, int V,
+                     double inv_temp, int32_t* __restrict__ accepted_len, int32_t* __restrict__ next_token,
+                     int32_t* __restrict__ accepted_path, dsd_accept_stats st) {
+    __shared__ int s_par[DSD_MAX_K + 1], s_y[DSD_MAX_K];
+    __shared__ float s_inv_z[DSD_MAX_K], s_q_scale[DSD_MAX_K + 1];
+    __shared__ double s_inv_z_d[DSD_MAX_K], s_q_scale_d[DSD_MAX_K + 1];
+    __shared__ double s_red[WALK_TPB / WAVE];
+    __shared__ double s_wave_tot[WALK_TPB / WAVE];
+    __shared__ int s_pick[2];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int R = k + 1;
+    for (int i = tid; i <= k; i += WALK_TPB) {
+        int p = 0;
+        if (i > 0) {
+            p = parent ? parent[i - 1] : i - 1;
+            p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
+            const size_t nidx = (size_t)b * k + i - 1;
+            if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
+            if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
+            if (st.node_accept) st.node_accept[nidx] = 0;
+            if (st.ratio) st.ratio[nidx] = 0.0;
+            if (accepted_path) accepted_path[nidx] = -1;
+        }
+        s_par[i] = p;
+    }
+    if (tid == 0) {
+        s_q_scale[0] = 1.f;
+        s_q_scale_d[0] = 1.0;
+    }
+    __syncthreads();
+
+    int v = 0, a = 0, n = 0;
+    size_t row = (size_t)b * R * V;
+    double lse = ws.row_lse[(size_t)b * R];
+    for (;;) {                                        // one turn per node on the path; all branches are uniform
+        row = ((size_t)b * R + v) * V;
+        lse = ws.row_lse[(size_t)b * R + v];
+        n = 0;
+        double removed_mass = 0.0;
+        int taken = 0;
+        for (int c = v + 1; c <= k && !taken; ++c) {
+            if (s_par[c] != v) continue;
+            int y = tokens[(size_t)b * k + c - 1];
+            y = y < 0 ? 0 : (y >= V ? V - 1 : y);
+            // the child's own test, fp64, by every thread alike
+            double p = exp((double)logits[row + y] * inv_temp - lse);
+            const double q1 = (double)qp[row + y];
+            bool removed = false;
+            for (int j = 0; j < n; ++j) {
+                const double qj = removed ? 0.0 : q1 * s_q_scale_d[j];
+                if (s_inv_z_d[j] > 0.0) p = fmax(p - qj, 0.0) * s_inv_z_d[j];
+                removed = removed || y == s_y[j];
+            }
+            const double qn = removed ? 0.0 : q1 * s_q_scale_d[n];
+            const double u = (double)uniforms[(size_t)b * R + c];
+            const bool acc = u * qn < p;
+            if (tid == 0) {
+                const size_t nidx = (size_t)b * k + c - 1;
+                if (st.node_accept) st.node_accept[nidx] = acc ? 1 : 0;
+                if (st.ratio) st.ratio[nidx] = qn > 0.0 ? p / qn : (p > 0.0 ? INFINITY : 0.0);
+            }
+            if (acc) {
+                taken = c;
+                break;
+            }
+            // rejected: Z_n = sum of the positive part of p_n - q_n
+            WalkChain ch{n, s_y, s_inv_z, s_q_scale};
+            double z = 0.0;
+            const bool vec = (V & 3) == 0 && (row & 3) == 0;      // rows start 16-byte aligned
+            const int step = vec ? 4 : 1;
+            for (int id = tid * step; id < V; id += WALK_TPB * step) {
+                float lv[4], qv[4];
+                if (vec) {
+                    const float4 l4 = *(const float4*)(logits + row + id), q4 = *(const float4*)(qp + row + id);
+                    lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w;
+                    qv[0] = q4.x; qv[1] = q4.y; qv[2] = q4.z; qv[3] = q4.w;
+                } else {
+                    lv[0] = logits[row + id];
+                    qv[0] = qp[row + id];
+                }
+                float zf = 0.f;                                   // at most 4 terms: exact enough before the fp64 sum
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (e < step) {
+                        const float p1 = expf((float)((double)lv[e] * inv_temp - lse));
+                        float qn_id;
+                        const float pn = walk_p(ch, p1, qv[e], id + e, &qn_id);
+                        zf += fmaxf(pn - qn_id, 0.f);
+                    }
+                }
+                z += (double)zf;
+            }
+            z = wave_sum_d(z);
+            __syncthreads();                          // everyone is done with the chain arrays and s_red
+            if (lane == 0) s_red[wave] = z;
+            __syncthreads();
+            if (tid == 0) {
+                double tot = 0.0;
+                for (int i = 0; i < WALK_TPB / WAVE; ++i) tot += s_red[i];
+                const double iz = tot > 0.0 ? 1.0 / tot : 0.0;
+                if (!removed) removed_mass += q1;
+                const double left = 1.0 - removed_mass;
+                const double qs = left > 0.0 ? 1.0 / left : 0.0;
+                s_y[n] = y;
+                s_inv_z_d[n] = iz;
+                s_inv_z[n] = (float)iz;
+                s_q_scale_d[n + 1] = qs;
+                s_q_scale[n + 1] = (float)qs;
+            }
+            // removed_mass lives in thread 0 only; the others never read it
+            ++n;
+            __syncthreads();
+        }
+        if (!taken) break;
+        if (tid == 0 && accepted_path) accepted_path[(size_t)b * k + a] = taken;
+        ++a;
+        v = taken;
+    }
+
+    // The additional token: inverse CDF over p_n of row v in token-id order with u_0.  Wave w owns
+    // the contiguous ids [w*span, (w+1)*span), read 64 at a time in lane order (coalesced): first the
+    // mass of every wave's range, then the wave holding the crossing walks its range again in groups
+    // of 64 ids, and the crossing group is resolved by a scan over its lanes.
+    WalkChain ch{n, s_y, s_inv_z, s_q_scale};
+    const int span = ((V + WALK_TPB / WAVE - 1) / (WALK_TPB / WAVE) + WAVE - 1) / WAVE * WAVE;
+    const int w0 = wave * span, w1 = min(w0 + span, V);
+    auto weight = [&](int id) -> float {
+        const float p1 = expf((float)((double)logits[row + id] * inv_temp - lse));
+        float qn_id;
+        return walk_p(ch, p1, qp[row + id], id, &qn_id);
+    };
+    double mass = 0.0;
+    int lastpos = -1;
+    for (int id = w0 + lane; id < w1; id += WAVE) {
+        const float pn = weight(id);
+        mass += (double)pn;
+        if (pn > 0.f) lastpos = id;
+    }
+    mass = wave_sum_d(mass);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, o, WAVE));
+    if (lane == 0) s_wave_tot[wave] = mass;
+    if (tid == 0) {
+        s_pick[0] = 0x7FFFFFFF;
+        s_pick[1] = -1;
+    }
+    __syncthreads();
+    double before = 0.0, total = 0.0;
+    for (int i = 0; i < WALK_TPB / WAVE; ++i) {
+        if (i < wave) before += s_wave_tot[i];
+        total += s_wave_tot[i];
+    }
+    const double target = (double)uniforms[(size_t)b * R] * total;
+    if (lane == 0 && lastpos >= 0) atomicMax(&s_pick[1], lastpos);
+    if (before <= target && target < before + mass) {     // the crossing lies in this wave's range (at most one wave)
+        double c = before;
+        int found = -1;
+        for (int g0 = w0; g0 < w1 && found < 0; g0 += WAVE) {
+            const int id = g0 + lane;
+            const double wgt = id < w1 ? (double)weight(id) : 0.0;
+            const double gsum = wave_sum_d(wgt);
+            if (c + gsum > target) {
+                double inc = wgt;                             // inclusive scan over the lanes
+#pragma unroll
+                for (int o = 1; o < WAVE; o <<= 1) {
+                    const double t = __shfl_up(inc, o, WAVE);
+                    if (lane >= o) inc += t;
+                }
+                const unsigned long long hit = __ballot(id < w1 && c + inc > target);
+                if (hit) found = g0 + __ffsll((long long)hit) - 1;
+            }
+            c += gsum;
+        }
+        if (lane == 0 && found >= 0) atomicMin(&s_pick[0], found);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int tok = s_pick[0];
+        if (tok == 0x7FFFFFFF) tok = s_pick[1] >= 0 ? s_pick[1] : 0;   // rounding left no crossing: last id with mass
+        next_token[b] = tok;
+        accepted_len[b] = a;
+    }
+}
+
 int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                   const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k, int V,
                   int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path, const dsd_accept_stats* stats) {
@@ -636,6 +850,17 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     const size_t cand_bytes = (size_t)2 * S * prm->top_m * sizeof(u64);
     const int cand_lds = cand_bytes <= 48 * 1024;
     row_merge_kernel<<<dim3(R, B), WAVE, cand_lds ? cand_bytes : 0, s>>>(ws, R, S, prm->top_m, cand_lds);
+    if (prm->tree_mode == DSD_TREE_LOSSLESS) {
+        // no relaxation in this mode: node_soft only evaluates the key rule (reported), then the walk
+        dsd_accept_params strict = *prm;
+        strict.tau = 0.0;
+        strict.tau_override = nullptr;
+        node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, strict, k, V, S, inv_temp);
+        lossless_walk_kernel<<<B, WALK_TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, uniforms, ws, k, V, inv_temp,
+                                                      accepted_len, next_token, accepted_path, st);
+        DSD_HIP(hipGetLastError());
+        return DSD_OK;
+    }
     node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, *prm, k, V, S, inv_temp);
     node_accept_kernel<<<dim3(k, B), WAVE, 0, s>>>(parent, uniforms, ws, k, S, st);
     decide_kernel<<<B, DECIDE_TPB, 0, s>>>(parent, ws, *prm, k, accepted_len, accepted_path);

@@ -365,7 +365,7 @@ extern "C" int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_
         DSD_FAIL(DSD_ESHAPE, "dsd_accept: top_m=%d (limit %d, V=%d)", p->top_m, DSD_MAX_TOP_M, V);
     if (!(p->tau >= 0.0 && p->tau <= 1.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: tau=%g outside [0,1]", p->tau);
     if (!(p->temperature > 0.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: temperature=%g", p->temperature);
-    if (p->tree_mode != DSD_TREE_LONGEST && p->tree_mode != DSD_TREE_FIRST_ACCEPTED)
+    if (p->tree_mode != DSD_TREE_LONGEST && p->tree_mode != DSD_TREE_FIRST_ACCEPTED && p->tree_mode != DSD_TREE_LOSSLESS)
         DSD_FAIL(DSD_EINVAL, "dsd_accept: tree_mode=%d", p->tree_mode);
     DSD_HIP(hipSetDevice(ctx->device));
     return accept_launch(ctx, logits, draft_probs, draft_tokens, parent, uniforms, p, B, k, V, accepted_len,

@@ -123,6 +123,30 @@ def test_trees(ctx, mode):
     run_case(ctx, lg, q, toks, small, u, dict(tau=0.0, tree_mode=mode), f"small tree mode {mode}")
 
 
+def test_lossless_tree_rule(ctx):
+    """DSD_TREE_LOSSLESS: recursive rejection over siblings drawn without replacement."""
+    parent = W.ranked_tree_parents()
+    k = len(parent)
+    lg, q, toks, u = make_rows(21, 6, k, 6000, parent=parent)
+    ora, g, ex, near = run_case(ctx, lg, q, toks, parent, u, dict(tau=0.2, lambda3=0.3, tree_mode=2), "lossless 32-node tree")
+    assert ora.accepted_len.max() >= 2
+    assert (ora.node_accept.sum(1) >= ora.accepted_len).all()
+    # many rejections per level: a bushy tree under a poor draft
+    bushy = [0] * 6 + [1] * 3 + [2] * 3
+    lg, q, toks, u = make_rows(22, 24, len(bushy), 300, parent=bushy, noise=2.0)
+    ora, *_ = run_case(ctx, lg, q, toks, bushy, u, dict(tree_mode=2), "lossless bushy tree")
+    assert (ora.accepted_len == 0).any() and (ora.accepted_len > 0).any()
+    # a chain gives the strict chain rule
+    lg, q, toks, u = make_rows(23, 10, 7, 2500)
+    ora, g, *_ = run_case(ctx, lg, q, toks, None, u, dict(tree_mode=2), "lossless chain")
+    strict = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, None, u, H.oracle_prm(O, dict(tau=0.0)))
+    np.testing.assert_array_equal(g["accepted_len"], strict.accepted_len)
+    np.testing.assert_array_equal(g["next_token"], strict.next_token)
+    # draft rows with exact zeros, full-size vocabulary
+    lg, q, toks, u = make_rows(24, 2, 10, 128256, parent=W.ranked_tree_parents((3, 2, 2), 10), zero_frac=0.5)
+    run_case(ctx, lg, q, toks, W.ranked_tree_parents((3, 2, 2), 10), u, dict(tree_mode=2), "lossless, vocabulary 128256")
+
+
 def test_k_max_chain(ctx):
     lg, q, toks, u = make_rows(15, 2, 64, 1000, noise=0.1)
     ora, *_ = run_case(ctx, lg, q, toks, None, u, dict(tau=0.3), "k=64")

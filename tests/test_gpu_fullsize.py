@@ -119,9 +119,9 @@ def draft_from(cfg, logits_np, parent, tag):
     return q, toks
 
 
-def accept_both_ways(name, cfg, st, buf, refs, parent):
+def accept_both_ways(name, cfg, st, buf, refs, parent, tree_mode=0):
     l1, l2, l3 = lambdas()
-    prm = dict(tau=cfg.tau, lambda1=l1, lambda2=l2, lambda3=l3, top_m=cfg.top_m)
+    prm = dict(tau=cfg.tau, lambda1=l1, lambda2=l2, lambda3=l3, top_m=cfg.top_m, tree_mode=tree_mode)
     k = cfg.k
     # (i) every sequence, on the logits the GPU produced (fed bit-identically to the oracle)
     lg = buf.cpu().numpy()
@@ -165,3 +165,5 @@ def test_c5_tree_final_stage_full_size_with_adaptive_accept():
     cfg, st, buf, refs, parent = run_config("c5", [2])
     ora = accept_both_ways("c5", cfg, st, buf, refs, parent)
     assert ora.accepted_path.shape[1] == 32
+    # the same logits under the lossless multi-sibling rule
+    accept_both_ways("c5 lossless", cfg, st, buf, refs, parent, tree_mode=2)
