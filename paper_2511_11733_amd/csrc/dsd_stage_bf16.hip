@@ -37,7 +37,7 @@ __global__ void tile_weights_kernel(uint4* __restrict__ dst, const bf16_t* __res
 
 int mfma_supported(const dsd_model_desc* d) {
     return d->dtype == DSD_BF16 && d->head_dim == 128 && d->d_model % 32 == 0 && d->d_ffn % 32 == 0 &&
-           d->d_model % 16 == 0 && d->d_ffn % 16 == 0 && (!d->has_head || d->vocab % 16 == 0) && !d->has_embed;
+           d->d_model % 16 == 0 && d->d_ffn % 16 == 0 && (!d->has_head || d->vocab % 16 == 0);
 }
 
 static int tile_into(dsd_ctx* ctx, void* dst, size_t dst_tile_off, const void* src, int N, int K) {
@@ -417,6 +417,14 @@ __global__ void rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) x[i] = bf16_to_f32(h[i]);
 }
+// first node of the pipeline: x[m,:] = E[token[m],:]  (ids clamped into the table)
+__global__ void embed_rows_kernel(float* __restrict__ x, const bf16_t* __restrict__ embed, const int32_t* __restrict__ tokens,
+                                  int d, int vocab) {
+    const int m = blockIdx.x;
+    int t = tokens[m];
+    t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = bf16_to_f32(embed[(size_t)t * d + i]);
+}
 __global__ void rows_out_kernel(bf16_t* __restrict__ h, const float* __restrict__ x, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) h[i] = f32_to_bf16(x[i]);
@@ -426,7 +434,6 @@ __global__ void rows_out_kernel(bf16_t* __restrict__ h, const float* __restrict_
 int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
                       const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B, int k,
                       void* hidden_out, float* logits, int64_t logits_seq_stride) {
-    (void)draft_tokens;
     const dsd_model_desc& D = w->desc;
     const KvGeom& g = kv->geom;
     const int M = B * k, d = D.d_model, Hq = D.n_q_heads, Hkv = D.n_kv_heads, hd = D.head_dim, F = D.d_ffn;
@@ -436,7 +443,8 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         const int rc = persist_stage_verify(ctx, w, kv, hidden_in, tree_mask, depth, B, k, hidden_out, logits, logits_seq_stride);
         if (rc != DSD_EUNSUPPORTED) return rc;      // else: one kernel per step
     }
-    if (!hidden_in) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: first-node (embedding) blocks run on the generic path");
+    if (!hidden_in && (!D.has_embed || !draft_tokens))
+        DSD_FAIL(DSD_EINVAL, "bf16 path: neither hidden_in nor (embedding table, draft_tokens)");
     const int rows = k * G;
     const int n_rt = (rows + 15) / 16;       // 16-row tiles of query rows per kv head
     if (n_rt > 8) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 128", rows);
@@ -491,7 +499,8 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const size_t nx = (size_t)M * d;
     {
         ProfScope ps(ctx, DSD_KC_OTHER);
-        rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
+        if (hidden_in) rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
+        else embed_rows_kernel<<<M, 256, 0, s>>>(x, (const bf16_t*)w->embed, draft_tokens, d, D.vocab);
     }
 
     for (int l = 0; l < D.n_layers; ++l) {

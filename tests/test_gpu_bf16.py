@@ -15,10 +15,10 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-def mini(name, B, k, lens, tree=None, head=False, L=2, d=512, Hq=8, Hkv=2, F=1536, V=8000, seed=3):
+def mini(name, B, k, lens, tree=None, head=False, L=2, d=512, Hq=8, Hkv=2, F=1536, V=8000, seed=3, embed=False):
     base = W.CONFIGS["c3" if head else "c2"]
     cfg = W.scaled(base, name=name, B=B, k=k, C=max(lens), seed=seed, L=L, d=d, Hq=Hq, Hkv=Hkv, F=F,
-                   V=V if head else 0, has_head=head)
+                   V=V if (head or embed) else 0, has_head=head, has_embed=embed)
     m = cfg.model
     w = W.make_weights(m, cfg.seed)
     K, Vv = W.make_kv(cfg)
@@ -98,6 +98,23 @@ def test_wide_ffn_picks_eight_computing_waves():
     # with this many gate/up columns the 17..64-row GEMM runs 8 computing waves per workgroup
     check(mini("mini_wide24", B=4, k=6, lens=[50, 20, 64, 9], F=26624, L=1))
     check(mini("mini_wide64", B=8, k=8, lens=[50, 20, 64, 9, 1, 100, 33, 80], F=26624, L=1))
+
+
+def test_first_node_block_with_embedding():
+    """A block that starts the pipeline: rows come from the embedding table (ids out of range are
+    clamped), here with the head as well, i.e. a whole small model in one call."""
+    for name, B, k in (("mini_embed5", 1, 5), ("mini_embed40", 5, 8)):
+        cfg, m, w, K, V, hid, parent, lens = mini(name, B=B, k=k, lens=[33 + 20 * b for b in range(B)], head=True,
+                                                  V=4112, embed=True)
+        toks = W.rng_for(cfg.seed, W.STREAM_STATE, "ids").integers(0, m.V, size=(B, k), dtype=np.int32)
+        ref = O.stage_forward(m, w.__getitem__, K, V, lens, None, toks)
+        st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
+        st.import_kv(K, V, lens)
+        out, lg = st.verify(tokens=toks)
+        tol = H.TOL["bf16"]
+        H.assert_close(H.to_np64(out), ref.hidden, tol, f"{name} hidden")
+        nrms, worst = H.assert_close(H.to_np64(lg), ref.logits, tol, f"{name} logits")
+        print(f"{name}: logits normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}")
 
 
 def test_empty_context():
