@@ -308,6 +308,8 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
     if parent is None:
         parent = list(range(k))
     parent = [int(p) for p in parent]
+    if prm.temperature == 0.0:
+        return accept_greedy(logits, draft_tokens, parent, prm)
     if prm.tree_mode == TREE_LOSSLESS:
         return accept_lossless(logits, draft_probs, draft_tokens, parent, uniforms, prm)
     children: Dict[int, List[int]] = {}
@@ -506,4 +508,59 @@ def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: n
         if gap < 1e-6:
             out.near_tie[b] |= 4
         out.next_token[b] = tok
+    return out
+
+
+def accept_greedy(logits: np.ndarray, draft_tokens: np.ndarray, parent: Sequence[int], prm: AcceptParams) -> AcceptOut:
+    """Verification at temperature 0 (the t = 0.0 rows of Table 1): the target is the one-hot
+    distribution on arg max logits (ties to the lower id), so node i passes iff its token is the arg max
+    of its parent's row, whatever the draft probabilities and the uniforms, and the additional token
+    is the arg max of the row of the path's last node (the limit of both the residual and the bonus
+    rule).  The accepted path follows tree_mode as at T > 0 (the lossless rule coincides with the
+    first-accepted descent here: at most one child of a node can hold the arg max).  No relaxation,
+    no key flags; ratio is 1 for a pass and 0 otherwise."""
+    B, k1, V = logits.shape
+    k = k1 - 1
+    children: Dict[int, List[int]] = {}
+    depth = np.zeros(k + 1, dtype=np.int64)
+    for i in range(1, k + 1):
+        children.setdefault(parent[i - 1], []).append(i)
+        depth[i] = depth[parent[i - 1]] + 1
+    out = AcceptOut(
+        accepted_len=np.zeros(B, dtype=np.int32), next_token=np.zeros(B, dtype=np.int32),
+        accepted_path=-np.ones((B, max(k, 1)), dtype=np.int32), key=np.zeros((B, k), dtype=bool),
+        node_accept=np.zeros((B, k), dtype=bool), tau_used=np.zeros((B, k)), ratio=np.zeros((B, k)),
+        norm_match=np.zeros((B, k)), near_tie=np.zeros(B, dtype=np.int32))
+    for b in range(B):
+        best = [int(np.argmax(logits[b, r])) for r in range(k + 1)]      # numpy: first of equal maxima
+        acc = np.zeros(k + 1, dtype=bool)
+        acc[0] = True
+        for i in range(1, k + 1):
+            acc[i] = int(draft_tokens[b, i - 1]) == best[parent[i - 1]]
+            out.node_accept[b, i - 1] = acc[i]
+            out.ratio[b, i - 1] = 1.0 if acc[i] else 0.0
+        if prm.tree_mode == TREE_LONGEST:
+            ok = np.zeros(k + 1, dtype=bool)
+            ok[0] = True
+            vstar = 0
+            for i in range(1, k + 1):
+                ok[i] = acc[i] and ok[parent[i - 1]]
+                if ok[i] and depth[i] > depth[vstar]:
+                    vstar = i
+        else:
+            vstar = 0
+            while True:
+                nxt = [c for c in children.get(vstar, []) if acc[c]]
+                if not nxt:
+                    break
+                vstar = nxt[0]
+        path = []
+        n = vstar
+        while n != 0:
+            path.append(n)
+            n = parent[n - 1]
+        path.reverse()
+        out.accepted_len[b] = len(path)
+        out.accepted_path[b, :len(path)] = path
+        out.next_token[b] = best[vstar]
     return out

@@ -555,3 +555,46 @@ def test_lossless_monte_carlo_tree():
     first0 = np.where(r0.accepted_len > 0, toks[np.arange(N), np.maximum(r0.accepted_path[:, 0], 1) - 1], r0.next_token)
     cnt0 = np.bincount(first0, minlength=V)
     assert float(((cnt0 - N * pt[0]) ** 2 / (N * pt[0])).sum()) > 60.0
+
+
+# ------------------------------------------------------------------ temperature 0 (greedy verification)
+def test_greedy_is_the_zero_temperature_limit():
+    """At T -> 0+ the stochastic rule takes the same decisions as the greedy one for every uniform:
+    the target tends to the one-hot on the arg max, a token the draft could draw has q > 0."""
+    rng = np.random.default_rng(31)
+    B, k, V = 200, 4, 9
+    lo = rng.normal(size=(B, k + 1, V)) * 3.0
+    q = np.stack([[rand_dist(rng, V) for _ in range(k + 1)] for _ in range(B)])
+    toks = np.zeros((B, k), dtype=np.int32)
+    for b in range(B):
+        for i in range(k):                    # half of the drafts hit the arg max, the rest are drawn from q
+            toks[b, i] = int(np.argmax(lo[b, i])) if rng.random() < 0.6 else int(rng.choice(V, p=q[b, i]))
+    u = rng.random((B, k + 1))
+    g = O.accept(lo, q, toks, None, u, O.AcceptParams(temperature=0.0))
+    s = O.accept(lo, q, toks, None, u, O.AcceptParams(temperature=1e-3))
+    np.testing.assert_array_equal(g.accepted_len, s.accepted_len)
+    np.testing.assert_array_equal(g.next_token, s.next_token)
+    assert 0 < g.accepted_len.mean() < k
+
+
+def test_greedy_edge_cases():
+    lo = np.zeros((1, 4, 5))
+    lo[0, 0, [1, 3]] = 2.0                      # a tie: the lower id is the arg max
+    lo[0, 1, 4] = 1.0
+    lo[0, 2, 0] = 1.0
+    lo[0, 3, 2] = 1.0
+    q = np.full((1, 4, 5), 0.2)
+    u = np.zeros((1, 4))
+    r = O.accept(lo, q, np.array([[1, 4, 0]], dtype=np.int32), None, u, O.AcceptParams(temperature=0.0))
+    assert r.accepted_len[0] == 3 and r.next_token[0] == 2          # all pass, bonus = arg max of the last row
+    r = O.accept(lo, q, np.array([[3, 4, 0]], dtype=np.int32), None, u, O.AcceptParams(temperature=0.0))
+    assert r.accepted_len[0] == 0 and r.next_token[0] == 1          # the other maximum of the tie is rejected
+    r = O.accept(lo, q, np.array([[1, 2, 0]], dtype=np.int32), None, u, O.AcceptParams(temperature=0.0))
+    assert r.accepted_len[0] == 1 and r.next_token[0] == 4 and list(r.accepted_path[0]) == [1, -1, -1]
+    # a tree: the arg-max child is found among siblings in either tree mode
+    par = [0, 0, 1, 1, 2]
+    lo = np.zeros((1, 6, 5)); lo[0, 0, 2] = 1; lo[0, 2, 3] = 1; lo[0, 5, 1] = 1
+    toks = np.array([[4, 2, 0, 1, 3]], dtype=np.int32)              # node 2 holds the root's arg max, node 5 node 2's
+    for mode in (O.TREE_LONGEST, O.TREE_FIRST_ACCEPTED, O.TREE_LOSSLESS):
+        r = O.accept(lo, np.full((1, 6, 5), 0.2), toks, par, np.zeros((1, 6)), O.AcceptParams(temperature=0.0, tree_mode=mode))
+        assert list(r.accepted_path[0][:2]) == [2, 5] and r.accepted_len[0] == 2 and r.next_token[0] == 1
