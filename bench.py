@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--config", default="c2", help="workload: c2 (default), c3, c4, c5")
     ap.add_argument("--tree-mode", default="longest", choices=["longest", "first", "lossless"],
                     help="dsd_accept's tree rule (final-stage workloads); lossless = recursive rejection over siblings")
+    ap.add_argument("--temperature", type=float, default=1.0, help="dsd_accept's temperature; 0 = greedy verification")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a known-size reference for HBM byte counters)")
@@ -142,7 +143,7 @@ def main():
         alen = torch.zeros(B, dtype=torch.int32, device=dev)
         nxt = torch.zeros(B, dtype=torch.int32, device=dev)
         path = torch.zeros((B, k), dtype=torch.int32, device=dev)
-        prm = D.accept_params(lambda1=1.05, lambda2=2e-5, lambda3=0.3, tau=cfg.tau, top_m=cfg.top_m,
+        prm = D.accept_params(lambda1=1.05, lambda2=2e-5, lambda3=0.3, tau=cfg.tau, top_m=cfg.top_m, temperature=args.temperature,
                               tree_mode={"longest": 0, "first": 1, "lossless": 2}[args.tree_mode])
 
     def stage():
@@ -239,7 +240,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {m.name} L={m.L} d={m.d} heads={m.Hq}/{m.Hkv} F={m.F} V={m.V} "
                                f"B={B} C={cfg.C} k={k} {'tree' if cfg.tree else 'chain'}"
-                               + (f" accept={args.tree_mode}" if m.has_head and args.tree_mode != "longest" else "")},
+                               + (f" accept={args.tree_mode}" if m.has_head and args.tree_mode != "longest" else "")
+                               + (f" T={args.temperature:g}" if m.has_head and args.temperature != 1.0 else "")},
         "verify_step_latency_ms": ms,
         "stage_algorithmic_GB": total_bytes / 1e9,
         "stage_achieved_GBps": (total_bytes + accept_bytes) / (ms * 1e-3) / 1e9,

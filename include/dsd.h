@@ -78,7 +78,7 @@ typedef struct dsd_model_desc {
 typedef struct dsd_accept_params {
     double lambda1, lambda2, lambda3;
     double tau;          /* in [0,1] */
-    double temperature;  /* > 0; P_t = softmax(logits / temperature) */
+    double temperature;  /* > 0: P_t = softmax(logits / temperature); 0: greedy verification (see dsd_accept) */
     int32_t top_m;       /* 1..DSD_MAX_TOP_M */
     int32_t tree_mode;   /* dsd_tree_mode */
     const float* tau_override; /* device [B,k] or NULL: tau of node i whatever the key rule says */
@@ -176,6 +176,10 @@ int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void*
  * leaf, the additional token is drawn from the p that is left.  The relaxation (tau) is not
  * applied in this mode; key flags and NormMatch are still reported, node_accept and ratio only
  * for the nodes the walk tried (0 elsewhere).  A chain gives the same result as the strict rule.
+ * temperature = 0 is greedy verification (the t = 0.0 rows of Table 1): node i passes iff its
+ * token is the arg max of its parent's logits row (ties to the lower id), the additional token is
+ * the arg max of the row of the path's last node; draft_probs and uniforms are not read (may be
+ * NULL), nothing is relaxed, key flags and NormMatch are reported as 0, ratio as 1 / 0.
  *   accepted_len  device int32 [B]
  *   next_token    device int32 [B]
  *   accepted_path device int32 [B,k] node ids of the path, -1 padded; may be NULL

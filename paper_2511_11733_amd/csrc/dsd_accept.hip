@@ -809,12 +809,113 @@ lossless_walk_kernel(const float* __restrict__ logits, const float* __restrict__
     }
 }
 
+// ---------------------------------------------------------------------------- temperature 0
+// Greedy verification: the target is the one-hot on arg max logits (ties to the lower id).
+// row_argmax: per (sequence, row, slice) the best (value, id) key; greedy_decide: per sequence the
+// arg max of every row, the nodes whose token equals their parent's arg max, the path (as decide_kernel)
+// and the arg max of the last node's row as the additional token.
+__global__ void __launch_bounds__(TPB)
+row_argmax_kernel(const float* __restrict__ logits, u64* __restrict__ part, int R, int V, int S) {
+    __shared__ u64 shu[TPB / WAVE];
+    const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+    const size_t row = ((size_t)b * R + r) * V;
+    u64 best = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = s * SLICE + threadIdx.x + j * TPB;
+        if (i < V) {
+            const u64 key = rank_key(logits[row + i], i);
+            best = key > best ? key : best;
+        }
+    }
+    best = block_max_u(best, shu);
+    if (threadIdx.x == 0) part[((size_t)b * R + r) * S + s] = best;
+}
+
+__global__ void __launch_bounds__(DECIDE_TPB)
+greedy_decide_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ parent, const u64* __restrict__ part,
+                     int tree_mode, int k, int S, int32_t* __restrict__ accepted_len, int32_t* __restrict__ next_token,
+                     int32_t* __restrict__ accepted_path, dsd_accept_stats st) {
+    __shared__ int par[DSD_MAX_K + 1], acc[DSD_MAX_K + 1], dep[DSD_MAX_K + 1], ok[DSD_MAX_K + 1], amax[DSD_MAX_K + 1];
+    const int b = blockIdx.x, i = threadIdx.x, R = k + 1;
+    if (i <= k) {
+        u64 best = 0;
+        for (int s = 0; s < S; ++s) {
+            const u64 key = part[((size_t)b * R + i) * S + s];
+            best = key > best ? key : best;
+        }
+        amax[i] = key_id(best);
+        int p = 0;
+        if (i > 0) {
+            p = parent ? parent[i - 1] : i - 1;
+            p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
+        }
+        par[i] = p;
+    }
+    if (accepted_path && i < k) accepted_path[(size_t)b * k + i] = -1;
+    __syncthreads();
+    if (i <= k) {
+        const int a = i == 0 ? 1 : (tokens[(size_t)b * k + i - 1] == amax[par[i]] ? 1 : 0);
+        acc[i] = a;
+        if (i > 0) {
+            const size_t nidx = (size_t)b * k + i - 1;
+            if (st.node_accept) st.node_accept[nidx] = a;
+            if (st.ratio) st.ratio[nidx] = a ? 1.0 : 0.0;
+            if (st.key_flags) st.key_flags[nidx] = 0;
+            if (st.norm_match) st.norm_match[nidx] = 0.0;
+        }
+    }
+    __syncthreads();
+    if (i <= k) {
+        int d = 0, good = acc[i];
+        for (int n = i; n != 0; n = par[n]) {
+            ++d;
+            good &= acc[par[n]];
+        }
+        dep[i] = d;
+        ok[i] = good;
+    }
+    __syncthreads();
+    if (i != 0) return;
+    int vstar = 0;
+    if (tree_mode == DSD_TREE_LONGEST) {
+        for (int c = 1; c <= k; ++c)
+            if (ok[c] && dep[c] > dep[vstar]) vstar = c;
+    } else {
+        for (;;) {
+            int nxt = 0;
+            for (int c = vstar + 1; c <= k; ++c)
+                if (par[c] == vstar && acc[c]) { nxt = c; break; }
+            if (!nxt) break;
+            vstar = nxt;
+        }
+    }
+    const int a = dep[vstar];
+    accepted_len[b] = a;
+    if (accepted_path)
+        for (int n = vstar, j = a - 1; n != 0; n = par[n], --j) accepted_path[(size_t)b * k + j] = n;
+    next_token[b] = amax[vstar];
+}
+
 int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                   const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k, int V,
                   int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path, const dsd_accept_stats* stats) {
     const int R = k + 1;
     const int S = (V + SLICE - 1) / SLICE;
     const size_t BR = (size_t)B * R, BK = (size_t)B * k;
+    if (prm->temperature == 0.0) {
+        DSD_TRY(dsd_ws_reserve(ctx, BR * S * 8 + 256));
+        u64* part = (u64*)ctx->ws;
+        dsd_accept_stats st0 = {nullptr, nullptr, nullptr, nullptr};
+        if (stats) st0 = *stats;
+        if (B > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
+        ProfScope ps(ctx, DSD_KC_ACCEPT);
+        row_argmax_kernel<<<dim3(S, R, B), TPB, 0, ctx->stream>>>(logits, part, R, V, S);
+        greedy_decide_kernel<<<B, DECIDE_TPB, 0, ctx->stream>>>(draft_tokens, parent, part, prm->tree_mode, k, S, accepted_len,
+                                                                 next_token, accepted_path, st0);
+        DSD_HIP(hipGetLastError());
+        return DSD_OK;
+    }
     size_t need = (BR * S * 2 + BR * 2 + BK * 4 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
                   BR * S * MAXM * 8 * 2 + (2 * BK + 2 * (size_t)B) * 4 + 32 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));

@@ -358,13 +358,15 @@ extern "C" int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_
                           const int32_t* parent, const float* uniforms, const dsd_accept_params* p, int B, int k,
                           int V, int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path,
                           const dsd_accept_stats* stats) {
-    if (!ctx || !logits || !draft_probs || !draft_tokens || !uniforms || !p || !accepted_len || !next_token)
+    const bool greedy = p && p->temperature == 0.0;      // draft_probs and uniforms are not read then
+    if (!ctx || !logits || (!draft_probs && !greedy) || !draft_tokens || (!uniforms && !greedy) || !p || !accepted_len ||
+        !next_token)
         DSD_FAIL(DSD_EINVAL, "dsd_accept: NULL argument");
     if (B < 1 || k < 1 || k > DSD_MAX_K || V < 1) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d k=%d V=%d", B, k, V);
     if (p->top_m < 1 || p->top_m > DSD_MAX_TOP_M || p->top_m > V)
         DSD_FAIL(DSD_ESHAPE, "dsd_accept: top_m=%d (limit %d, V=%d)", p->top_m, DSD_MAX_TOP_M, V);
     if (!(p->tau >= 0.0 && p->tau <= 1.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: tau=%g outside [0,1]", p->tau);
-    if (!(p->temperature > 0.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: temperature=%g", p->temperature);
+    if (!(p->temperature >= 0.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: temperature=%g", p->temperature);
     if (p->tree_mode != DSD_TREE_LONGEST && p->tree_mode != DSD_TREE_FIRST_ACCEPTED && p->tree_mode != DSD_TREE_LOSSLESS)
         DSD_FAIL(DSD_EINVAL, "dsd_accept: tree_mode=%d", p->tree_mode);
     DSD_HIP(hipSetDevice(ctx->device));

@@ -147,6 +147,35 @@ def test_lossless_tree_rule(ctx):
     run_case(ctx, lg, q, toks, W.ranked_tree_parents((3, 2, 2), 10), u, dict(tree_mode=2), "lossless, vocabulary 128256")
 
 
+def test_greedy_verification_at_temperature_zero(ctx):
+    rng = np.random.default_rng(41)
+    for what, parent, B, V in (("chain", None, 9, 5000), ("tree", W.ranked_tree_parents(), 5, 128256),
+                               ("small tree", [0, 0, 1, 1, 2], 30, 300)):
+        k = 6 if parent is None else len(parent)
+        lg, q, toks, u = make_rows(int(rng.integers(1 << 30)), B, k, V, parent=parent)
+        par = list(range(k)) if parent is None else [int(p) for p in parent]
+        for b in range(B):                    # most drafts hit the arg max of their parent's row, some do not
+            for i in range(1, k + 1):
+                if rng.random() < 0.7:
+                    toks[b, i - 1] = int(np.argmax(lg[b, par[i - 1]]))
+        lg[0, 0, 7] = lg[0, 0].max()          # a tie in the root row of sequence 0: the lower id wins
+        lg[0, 0, 3] = lg[0, 0, 7]
+        for mode in (0, 1, 2):
+            ora, g, ex, near = run_case(ctx, lg, q, toks, parent, u, dict(temperature=0.0, tree_mode=mode), f"greedy {what} mode {mode}")
+            assert ex == 0 and ora.accepted_len.max() >= 2
+    # draft_probs and uniforms may be NULL
+    t = torch.from_numpy(lg).to("cuda:0")
+    tk = torch.from_numpy(toks).to("cuda:0")
+    pr = torch.from_numpy(np.asarray(par, dtype=np.int32)).to("cuda:0")
+    alen = torch.zeros(B, dtype=torch.int32, device="cuda:0")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda:0")
+    H.D.dsd_accept(ctx, t, None, tk, pr, None, H.D.accept_params(temperature=0.0), B, k, V, alen, nxt, None)
+    torch.cuda.synchronize()
+    ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, par, u, O.AcceptParams(temperature=0.0))
+    np.testing.assert_array_equal(alen.cpu().numpy(), ora.accepted_len)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), ora.next_token)
+
+
 def test_k_max_chain(ctx):
     lg, q, toks, u = make_rows(15, 2, 64, 1000, noise=0.1)
     ora, *_ = run_case(ctx, lg, q, toks, None, u, dict(tau=0.3), "k=64")
