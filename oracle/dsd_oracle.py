@@ -213,6 +213,13 @@ TREE_FIRST_ACCEPTED = 1
 TREE_LOSSLESS = 2      # recursive rejection over siblings drawn without replacement (see accept_lossless)
 
 
+# Readings of the two loosely specified ingredients of the key rule (section 2.3):
+NM_TOP_M = 0       # NormMatch = share of the top-M ids of P_t found in the top-M ids of q (the paper's example)
+NM_OVERLAP = 1     # NormMatch = sum_v min(P_t(v), q(v)) = 1 - total variation distance of the two rows
+H_TOKEN = 0        # H_m = -ln P_m(y): cross entropy of the drafted token under model m
+H_ROW = 1          # H_m = -sum_v P_m(v) ln P_m(v): Shannon entropy of model m's row
+
+
 @dataclass
 class AcceptParams:
     lambda1: float = np.inf       # key if H_d > lambda1 * H_t
@@ -222,6 +229,8 @@ class AcceptParams:
     top_m: int = 8                # support size of NormMatch
     temperature: float = 1.0
     tree_mode: int = TREE_LONGEST
+    norm_match_kind: int = 0      # NM_TOP_M or NM_OVERLAP
+    entropy_kind: int = 0         # H_TOKEN or H_ROW
 
 
 @dataclass
@@ -256,13 +265,39 @@ def norm_match(pt: np.ndarray, q: np.ndarray, M: int) -> float:
     return len(set(top_m_ids(pt, M).tolist()) & set(top_m_ids(q, M).tolist())) / float(M)
 
 
-def is_key(pt_y: float, q_y: float, nm: float, prm: AcceptParams) -> bool:
-    """Eq. "Key": any one of the three criteria makes the token a key token.  H_m(y) is the
-    cross entropy of the drafted token under model m, -ln P_m(y); the first criterion is
-    used in product form so that H_t = 0 needs no division."""
+def norm_match_overlap(pt: np.ndarray, q: np.ndarray) -> float:
+    """sum_v min(P_t(v), q(v)): the mass the two rows share (1 - total variation distance)."""
+    return float(np.minimum(pt, q).sum())
+
+
+def row_entropy(p: np.ndarray) -> float:
+    """Shannon entropy -sum_v p(v) ln p(v) in nats, 0 ln 0 = 0."""
+    nz = p[p > 0]
+    return float(-(nz * np.log(nz)).sum())
+
+
+def row_norm_match(pt: np.ndarray, q: np.ndarray, prm: "AcceptParams") -> float:
+    return norm_match_overlap(pt, q) if prm.norm_match_kind == NM_OVERLAP else norm_match(pt, q, prm.top_m)
+
+
+def key_entropies(pt: np.ndarray, q: np.ndarray, y: int, prm: "AcceptParams"):
+    """(H_t, H_d) of the first key criterion under the chosen reading."""
+    if prm.entropy_kind == H_ROW:
+        return row_entropy(pt), row_entropy(q)
     with np.errstate(divide="ignore", invalid="ignore"):
-        h_t = -np.log(F64(pt_y))
-        h_d = -np.log(F64(q_y))
+        return float(-np.log(F64(pt[y]))), float(-np.log(F64(q[y])))
+
+
+def is_key(pt_y: float, q_y: float, nm: float, prm: AcceptParams, h=None) -> bool:
+    """Eq. "Key": any one of the three criteria makes the token a key token.  H_m is by default the
+    cross entropy of the drafted token under model m, -ln P_m(y) (h = (H_t, H_d) overrides it, see
+    key_entropies); the first criterion is used in product form so that H_t = 0 needs no division."""
+    with np.errstate(divide="ignore", invalid="ignore"):
+        if h is None:
+            h_t = -np.log(F64(pt_y))
+            h_d = -np.log(F64(q_y))
+        else:
+            h_t, h_d = F64(h[0]), F64(h[1])
         c1 = bool(h_d > prm.lambda1 * h_t)
     c2 = bool(abs(pt_y - q_y) > prm.lambda2)
     c3 = bool(nm < prm.lambda3)
@@ -341,16 +376,19 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
             pt = target_row(p)
             q = draft_probs[b, p].astype(F64)
             if p not in nm_rows:
-                nm_rows[p] = norm_match(pt, q, prm.top_m)
+                nm_rows[p] = row_norm_match(pt, q, prm)
                 # top-M boundary gaps (a swap across the boundary could change NormMatch)
-                for row in (pt, q):
-                    srt = np.sort(row)[::-1]
-                    if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
-                        out.near_tie[b] |= 2
+                if prm.norm_match_kind == NM_TOP_M:
+                    for row in (pt, q):
+                        srt = np.sort(row)[::-1]
+                        if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
+                            out.near_tie[b] |= 2
+                elif np.isfinite(prm.lambda3) and abs(nm_rows[p] - prm.lambda3) < 1e-6:
+                    out.near_tie[b] |= 2
             nm = nm_rows[p]
-            key = is_key(pt[y], q[y], nm, prm)
+            h_t, h_d = key_entropies(pt, q, y, prm)
+            key = is_key(pt[y], q[y], nm, prm, (h_t, h_d))
             with np.errstate(divide="ignore", invalid="ignore"):
-                h_t, h_d = -np.log(pt[y]), -np.log(q[y])
                 if np.isfinite(prm.lambda1) and np.isfinite(h_t) and np.isfinite(h_d) and \
                         abs(h_d - prm.lambda1 * h_t) < 1e-3 * abs(prm.lambda1 * h_t):
                     out.near_tie[b] |= 2
@@ -456,15 +494,17 @@ def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: n
             y = int(draft_tokens[b, i - 1])
             pt = softmax_row(logits[b, p_row], prm.temperature)
             q = draft_probs[b, p_row].astype(F64)
-            nm = norm_match(pt, q, prm.top_m)
-            out.key[b, i - 1] = is_key(pt[y], q[y], nm, prm)
+            nm = row_norm_match(pt, q, prm)
+            h_t, h_d = key_entropies(pt, q, y, prm)
+            out.key[b, i - 1] = is_key(pt[y], q[y], nm, prm, (h_t, h_d))
             out.norm_match[b, i - 1] = nm
-            srt_rows = (np.sort(pt)[::-1], np.sort(q)[::-1])
-            for srt in srt_rows:
-                if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
-                    out.near_tie[b] |= 2
+            if prm.norm_match_kind == NM_TOP_M:
+                for srt in (np.sort(pt)[::-1], np.sort(q)[::-1]):
+                    if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
+                        out.near_tie[b] |= 2
+            elif np.isfinite(prm.lambda3) and abs(nm - prm.lambda3) < 1e-6:
+                out.near_tie[b] |= 2
             with np.errstate(divide="ignore", invalid="ignore"):
-                h_t, h_d = -np.log(pt[y]), -np.log(q[y])
                 if np.isfinite(prm.lambda1) and np.isfinite(h_t) and np.isfinite(h_d) and \
                         abs(h_d - prm.lambda1 * h_t) < 1e-3 * abs(prm.lambda1 * h_t):
                     out.near_tie[b] |= 2

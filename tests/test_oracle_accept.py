@@ -598,3 +598,51 @@ def test_greedy_edge_cases():
     for mode in (O.TREE_LONGEST, O.TREE_FIRST_ACCEPTED, O.TREE_LOSSLESS):
         r = O.accept(lo, np.full((1, 6, 5), 0.2), toks, par, np.zeros((1, 6)), O.AcceptParams(temperature=0.0, tree_mode=mode))
         assert list(r.accepted_path[0][:2]) == [2, 5] and r.accepted_len[0] == 2 and r.next_token[0] == 1
+
+
+# ------------------------------------------------------------------ variants of the key rule's ingredients
+def test_norm_match_overlap_and_row_entropy_closed_forms():
+    rng = np.random.default_rng(51)
+    p, q = rand_dist(rng, 50), rand_dist(rng, 50)
+    assert O.norm_match_overlap(p, p) == pytest.approx(1.0)
+    assert O.norm_match_overlap(p, q) == pytest.approx(1.0 - 0.5 * np.abs(p - q).sum())   # 1 - total variation
+    a = np.array([0.5, 0.5, 0.0, 0.0]); b = np.array([0.0, 0.0, 0.3, 0.7])
+    assert O.norm_match_overlap(a, b) == 0.0
+    assert O.row_entropy(np.full(64, 1 / 64)) == pytest.approx(np.log(64))
+    assert O.row_entropy(np.array([0.0, 1.0, 0.0])) == 0.0
+    assert O.row_entropy(p) == pytest.approx(float(stats.entropy(p)))                       # scipy, natural log
+
+
+def test_key_rule_variants_switch_the_criteria():
+    V = 6
+    pt = np.array([0.70, 0.10, 0.08, 0.06, 0.04, 0.02])
+    q = np.array([0.10, 0.60, 0.10, 0.10, 0.05, 0.05])
+    rows, qrows = [logits_of(pt), logits_of(pt)], [q, q]
+    base = dict(tau=0.5)
+    # overlap reading of NormMatch: sum min = 0.10+0.10+0.08+0.06+0.04+0.02 = 0.40
+    for lam3, want in ((0.39, False), (0.41, True)):
+        prm = O.AcceptParams(lambda3=lam3, norm_match_kind=O.NM_OVERLAP, **base)
+        r = run1(rows, qrows, [2], [0.5, 0.5], prm)
+        assert bool(r.key[0, 0]) == want and r.norm_match[0, 0] == pytest.approx(0.40)
+        assert r.tau_used[0, 0] == (0.0 if want else 0.5)
+    # row-entropy reading of the first criterion: H_d / H_t is a property of the rows, not of the token
+    ht, hd = O.row_entropy(pt), O.row_entropy(q)
+    for lam1, want in ((hd / ht * 0.99, True), (hd / ht * 1.01, False)):
+        for y in (0, 3):
+            prm = O.AcceptParams(lambda1=lam1, entropy_kind=O.H_ROW, **base)
+            assert bool(run1(rows, qrows, [y], [0.5, 0.5], prm).key[0, 0]) == want
+
+
+def test_accept_rate_grows_with_tau():
+    """The relaxation knob: with no key tokens the per-token accept probability sum_v min(P~, q) grows
+    from 1 - TV(P_t, q) at tau = 0 to 1 at tau = 1 (the trade-off of Table 1's ablation)."""
+    rng = np.random.default_rng(61)
+    V = 40
+    pt, q = rand_dist(rng, V, 1.5), rand_dist(rng, V, 0.8)
+    prev = -1.0
+    for tau in (0.0, 0.1, 0.2, 0.4, 0.8, 1.0):
+        alpha = float(np.minimum(O.softened_target(pt, q, tau), q).sum())
+        assert alpha >= prev - 1e-12
+        prev = alpha
+    assert prev == pytest.approx(1.0)
+    assert float(np.minimum(pt, q).sum()) == pytest.approx(O.norm_match_overlap(pt, q))
