@@ -43,6 +43,11 @@ enum dsd_status {
 };
 
 enum dsd_dtype { DSD_F32 = 0, DSD_BF16 = 1 };
+/* Other readings of two loosely specified ingredients of the key rule (section 2.3):
+ * DSD_NM_OVERLAP: NormMatch(p) = sum_v min(P_t(v), q_p(v)), the mass the rows share (1 - total variation);
+ * DSD_H_ROW: H_d, H_t = Shannon entropies -sum_v P ln P of the draft row and of the target row. */
+enum dsd_norm_match_kind { DSD_NM_TOP_M = 0, DSD_NM_OVERLAP = 1 };
+enum dsd_entropy_kind { DSD_H_TOKEN = 0, DSD_H_ROW = 1 };
 enum dsd_tree_mode { DSD_TREE_LONGEST = 0, DSD_TREE_FIRST_ACCEPTED = 1, DSD_TREE_LOSSLESS = 2 };
 
 #define DSD_MAX_K 64      /* drafted rows per sequence (tree masks are 64-bit rows) */
@@ -82,6 +87,8 @@ typedef struct dsd_accept_params {
     int32_t top_m;       /* 1..DSD_MAX_TOP_M */
     int32_t tree_mode;   /* dsd_tree_mode */
     const float* tau_override; /* device [B,k] or NULL: tau of node i whatever the key rule says */
+    int32_t norm_match_kind;   /* dsd_norm_match_kind; 0 = the top_m overlap above */
+    int32_t entropy_kind;      /* dsd_entropy_kind; 0 = the token cross entropies above */
 } dsd_accept_params;
 
 /* Optional per-node outputs of dsd_accept (device pointers, each may be NULL). */

@@ -152,6 +152,9 @@ struct AcceptWs {
     u64* part_top_q;    // [B][R][S][MAXM]
     double* row_lse;    // [B][R]
     double* row_nm;     // [B][R]
+    double* row_ht;     // [B][R]  Shannon entropy of the target row   (DSD_H_ROW)
+    double* row_hd;     // [B][R]  Shannon entropy of the draft row    (DSD_H_ROW)
+    double* part_x;     // [B][R][S][3] per-slice sum min(P_t, q), -sum P_t ln P_t, -sum q ln q
     double* node_tau;   // [B][k]
     double* node_lnpt;  // [B][k]  ln P_t(y)
     double* node_q;     // [B][k]  q(y)
@@ -293,6 +296,57 @@ row_merge_kernel(AcceptWs ws, int R, int S, int top_m, int cand_lds) {
     }
 }
 
+// Row quantities of the other readings of the key rule (only launched when one is selected; needs
+// the rows' log-sum-exp): per slice sum min(P_t, q), -sum P_t ln P_t, -sum q ln q (fp32 terms, fp64
+// sums), then per row their totals: NormMatch := the overlap if asked for, and the two entropies.
+__global__ void __launch_bounds__(TPB)
+row_extra_kernel(const float* __restrict__ logits, const float* __restrict__ qp, AcceptWs ws, int R, int V, int S,
+                 double inv_temp) {
+    __shared__ double shd[TPB / WAVE];
+    const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+    const size_t row = ((size_t)b * R + r) * V;
+    const double lse = ws.row_lse[(size_t)b * R + r];
+    float ov = 0.f, ht = 0.f, hd = 0.f;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = s * SLICE + threadIdx.x + j * TPB;
+        if (i < V) {
+            const float ln_p = (float)((double)logits[row + i] * inv_temp - lse);
+            const float p = expf(ln_p), q = qp[row + i];
+            ov += fminf(p, q);
+            if (p > 0.f) ht -= p * ln_p;
+            if (q > 0.f) hd -= q * logf(q);
+        }
+    }
+    const double sov = block_sum_d((double)ov, shd), sht = block_sum_d((double)ht, shd), shd_ = block_sum_d((double)hd, shd);
+    if (threadIdx.x == 0) {
+        double* o = ws.part_x + (((size_t)b * R + r) * S + s) * 3;
+        o[0] = sov;
+        o[1] = sht;
+        o[2] = shd_;
+    }
+}
+__global__ void __launch_bounds__(WAVE)
+row_extra_merge_kernel(AcceptWs ws, int R, int S, int overlap_is_norm_match) {
+    const int r = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const size_t ridx = (size_t)b * R + r;
+    double ov = 0.0, ht = 0.0, hd = 0.0;
+    for (int s = lane; s < S; s += WAVE) {
+        const double* o = ws.part_x + (ridx * S + s) * 3;
+        ov += o[0];
+        ht += o[1];
+        hd += o[2];
+    }
+    ov = wave_sum_d(ov);
+    ht = wave_sum_d(ht);
+    hd = wave_sum_d(hd);
+    if (lane == 0) {
+        if (overlap_is_norm_match) ws.row_nm[ridx] = ov;
+        ws.row_ht[ridx] = ht;
+        ws.row_hd[ridx] = hd;
+    }
+}
+
 __global__ void __launch_bounds__(TPB)
 node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const int32_t* __restrict__ tokens,
                  const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params prm, int k, int V, int S,
@@ -310,7 +364,11 @@ node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     const double pt_y = exp(ln_pt);
     const double q_y = (double)qp[row + y];
     // key-token rule: any of the three criteria
-    const double h_t = -ln_pt, h_d = -log(q_y);
+    double h_t = -ln_pt, h_d = -log(q_y);
+    if (prm.entropy_kind == DSD_H_ROW) {
+        h_t = ws.row_ht[(size_t)b * R + p];
+        h_d = ws.row_hd[(size_t)b * R + p];
+    }
     const bool key = (h_d > prm.lambda1 * h_t) || (fabs(pt_y - q_y) > prm.lambda2) ||
                      (ws.row_nm[(size_t)b * R + p] < prm.lambda3);
     double tau = key ? 0.0 : prm.tau;
@@ -916,7 +974,7 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
         DSD_HIP(hipGetLastError());
         return DSD_OK;
     }
-    size_t need = (BR * S * 2 + BR * 2 + BK * 4 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
+    size_t need = (BR * S * 5 + BR * 4 + BK * 4 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
                   BR * S * MAXM * 8 * 2 + (2 * BK + 2 * (size_t)B) * 4 + 32 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
     WsBump bump{ctx->ws, 0};
@@ -927,6 +985,9 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     ws.part_top_q = bump.take<u64>(BR * S * MAXM);
     ws.row_lse = bump.take<double>(BR);
     ws.row_nm = bump.take<double>(BR);
+    ws.row_ht = bump.take<double>(BR);
+    ws.row_hd = bump.take<double>(BR);
+    ws.part_x = bump.take<double>(BR * S * 3);
     ws.node_tau = bump.take<double>(BK);
     ws.node_lnpt = bump.take<double>(BK);
     ws.node_q = bump.take<double>(BK);
@@ -951,6 +1012,10 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     const size_t cand_bytes = (size_t)2 * S * prm->top_m * sizeof(u64);
     const int cand_lds = cand_bytes <= 48 * 1024;
     row_merge_kernel<<<dim3(R, B), WAVE, cand_lds ? cand_bytes : 0, s>>>(ws, R, S, prm->top_m, cand_lds);
+    if (prm->norm_match_kind == DSD_NM_OVERLAP || prm->entropy_kind == DSD_H_ROW) {
+        row_extra_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
+        row_extra_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->norm_match_kind == DSD_NM_OVERLAP ? 1 : 0);
+    }
     if (prm->tree_mode == DSD_TREE_LOSSLESS) {
         // no relaxation in this mode: node_soft only evaluates the key rule (reported), then the walk
         dsd_accept_params strict = *prm;

@@ -366,6 +366,9 @@ extern "C" int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_
     if (p->top_m < 1 || p->top_m > DSD_MAX_TOP_M || p->top_m > V)
         DSD_FAIL(DSD_ESHAPE, "dsd_accept: top_m=%d (limit %d, V=%d)", p->top_m, DSD_MAX_TOP_M, V);
     if (!(p->tau >= 0.0 && p->tau <= 1.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: tau=%g outside [0,1]", p->tau);
+    if ((p->norm_match_kind != DSD_NM_TOP_M && p->norm_match_kind != DSD_NM_OVERLAP) ||
+        (p->entropy_kind != DSD_H_TOKEN && p->entropy_kind != DSD_H_ROW))
+        DSD_FAIL(DSD_EINVAL, "dsd_accept: norm_match_kind=%d entropy_kind=%d", p->norm_match_kind, p->entropy_kind);
     if (!(p->temperature >= 0.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: temperature=%g", p->temperature);
     if (p->tree_mode != DSD_TREE_LONGEST && p->tree_mode != DSD_TREE_FIRST_ACCEPTED && p->tree_mode != DSD_TREE_LOSSLESS)
         DSD_FAIL(DSD_EINVAL, "dsd_accept: tree_mode=%d", p->tree_mode);

@@ -42,7 +42,7 @@ class ModelDesc(C.Structure):
 class AcceptParams(C.Structure):
     _fields_ = [("lambda1", C.c_double), ("lambda2", C.c_double), ("lambda3", C.c_double), ("tau", C.c_double),
                 ("temperature", C.c_double), ("top_m", C.c_int32), ("tree_mode", C.c_int32),
-                ("tau_override", C.c_void_p)]
+                ("tau_override", C.c_void_p), ("norm_match_kind", C.c_int32), ("entropy_kind", C.c_int32)]
 
 
 class AcceptStats(C.Structure):
@@ -257,6 +257,7 @@ def dsd_kv_commit(ctx: Context, kv: KVCache, accepted_len: torch.Tensor, accepte
 
 
 def accept_params(lambda1=float("inf"), lambda2=float("inf"), lambda3=float("-inf"), tau=0.0, temperature=1.0,
-                  top_m=8, tree_mode=DSD_TREE_LONGEST, tau_override: Optional[torch.Tensor] = None) -> AcceptParams:
+                  top_m=8, tree_mode=DSD_TREE_LONGEST, tau_override: Optional[torch.Tensor] = None,
+                  norm_match_kind=0, entropy_kind=0) -> AcceptParams:
     return AcceptParams(lambda1, lambda2, lambda3, tau, temperature, top_m, tree_mode,
-                        _ptr(tau_override, torch.float32, "tau_override"))
+                        _ptr(tau_override, torch.float32, "tau_override"), norm_match_kind, entropy_kind)

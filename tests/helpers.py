@@ -147,4 +147,5 @@ def compare_accept(gpu: dict, ora, what: str):
 def oracle_prm(O, prm: dict):
     return O.AcceptParams(lambda1=prm.get("lambda1", np.inf), lambda2=prm.get("lambda2", np.inf),
                           lambda3=prm.get("lambda3", -np.inf), tau=prm.get("tau", 0.0), top_m=prm.get("top_m", 8),
-                          temperature=prm.get("temperature", 1.0), tree_mode=prm.get("tree_mode", 0))
+                          temperature=prm.get("temperature", 1.0), tree_mode=prm.get("tree_mode", 0),
+                          norm_match_kind=prm.get("norm_match_kind", 0), entropy_kind=prm.get("entropy_kind", 0))
