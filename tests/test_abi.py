@@ -30,5 +30,5 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(D.ModelDesc) == 12 * 4
-    assert ctypes.sizeof(D.AcceptParams) == 5 * 8 + 2 * 4 + 8
+    assert ctypes.sizeof(D.AcceptParams) == 5 * 8 + 2 * 4 + 8 + 2 * 4
     assert ctypes.sizeof(D.AcceptStats) == 4 * 8
