@@ -4,9 +4,9 @@
 // operand is no longer negligible: every weight fragment meets 2*MT activation fragments (hi + lo
 // bf16 of MT 16-row tiles).  So the activations are shared through LDS and only the weights come
 // straight from HBM into registers:
-//   * a workgroup of 4 waves owns 128 output columns (each wave two 16-column tiles) over one
-//     contiguous slice of K (grid.y splits K when a matrix has too few column blocks to fill the
-//     chip; partial results are then added atomically into an fp32 buffer);
+//   * a workgroup of 4 (or 8) computing waves owns 128 (256) output columns, each wave two
+//     16-column tiles, over one contiguous slice of K (grid.y splits K when a matrix has too few
+//     column blocks to fill the chip; partial results are then added atomically into an fp32 buffer);
 //   * the activations are converted ONCE per GEMM by a small kernel of their own (gain, hi/lo
 //     split, A-operand order, sum of squares for the RMSNorm scale) into a panel in global memory;
 //     doing that inside every workgroup cost more vector ALU time than the matrix cores had work;
@@ -15,13 +15,14 @@
 //     buffered).  Vector memory loads of one wave complete in order, so a wave that fetched the
 //     panel itself would have to drain its older weight loads at every chunk; as it is, the only
 //     things a computing wave ever waits for are its own weight stream and the workgroup barrier;
-//   * every computing wave keeps its next 32 weight fragments in flight in a register FIFO, issued
-//     by hand (inline asm + explicit s_waitcnt counts, see gload16 / vm_wait).
+//   * every computing wave keeps its next 8 or 16 weight fragments in flight in a register FIFO,
+//     issued by hand (inline asm + explicit s_waitcnt counts, see gload16 / vm_wait); a read stream
+//     of this kind saturates HBM with 16 KiB in flight per compute unit, so the depth is set by the
+//     registers the row count leaves, not by latency.
 #include "dsd_bf16_dev.h"
 
 #define TP 4             // panel-fetching waves per workgroup
 #define NTW 2            // 16-column tiles per computing wave
-#define TCH 128          // K per panel chunk: 4 k-steps
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void gload16(u32x4& dst, const void* ptr) {
