@@ -298,30 +298,41 @@ __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ pane
 }
 
 // q, k, v rows accumulated by the split-K QKV GEMM -> RMSNorm scale, rotary embedding, cache append.
-// One block per row; the accumulator row is cleared for the next layer.
+// Block (row, part): the heads are dealt out over gridDim.y blocks; the row's 64 rotation angles are
+// the same for every head, so each block works them out once (fp64) into LDS.  The accumulator row
+// is cleared for the next layer.
 __global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc, const float* __restrict__ ssq,
                                                          float* __restrict__ q, bf16_t* __restrict__ kc,
                                                          bf16_t* __restrict__ vc, KvGeom g,
                                                          const int32_t* __restrict__ len,
                                                          const int32_t* __restrict__ depth, int k, int Hq, int d,
                                                          float eps, float theta) {
+    __shared__ float s_cs[64], s_sn[64];
     const int m = blockIdx.x, b = m / k, t = m % k;
     const float rstd = 1.0f / sqrtf(ssq[m] / (float)d + eps);
     const int L = len[b];
     const int slot = L + t;
-    const double pos = (double)(L + (depth ? depth[t] : t));
+    if (threadIdx.x < 64) {
+        const double pos = (double)(L + (depth ? depth[t] : t));
+        const double inv = pow((double)theta, -2.0 * (double)threadIdx.x / 128.0);
+        double sn, cs;
+        sincos(pos * inv, &sn, &cs);
+        s_cs[threadIdx.x] = (float)cs;
+        s_sn[threadIdx.x] = (float)sn;
+    }
+    __syncthreads();
     const int heads = Hq + 2 * g.Hkv;
+    const int per = (heads + gridDim.y - 1) / gridDim.y;
+    const int h0 = blockIdx.y * per, h1 = min(h0 + per, heads);
     float* row = acc + (size_t)m * heads * 128;
-    for (int i = threadIdx.x; i < heads * 64; i += 256) {
+    for (int i = h0 * 64 + threadIdx.x; i < h1 * 64; i += 256) {
         const int head = i >> 6, e = i & 63;
         const float lo = row[head * 128 + e] * rstd, hi = row[head * 128 + e + 64] * rstd;
         row[head * 128 + e] = 0.f;
         row[head * 128 + e + 64] = 0.f;
         if (head < Hq + g.Hkv) {
-            const double inv = pow((double)theta, -2.0 * (double)e / 128.0);
-            double sn, cs;
-            sincos(pos * inv, &sn, &cs);
-            const float r0 = lo * (float)cs - hi * (float)sn, r1 = hi * (float)cs + lo * (float)sn;
+            const float cs = s_cs[e], sn = s_sn[e];
+            const float r0 = lo * cs - hi * sn, r1 = hi * cs + lo * sn;
             if (head < Hq) {
                 q[((size_t)m * Hq + head) * 128 + e] = r0;
                 q[((size_t)m * Hq + head) * 128 + e + 64] = r1;
@@ -385,17 +396,19 @@ static int choose_twc(int M, int n_tiles16, int n_cu) {
 
 // K split so that a matrix with few column blocks still fills the chip; every slice a multiple of
 // 16 k-steps.  Returns 0 if K cannot be cut that way.
-static int choose_ksplit(int KS, int n_blocks, int n_cu) {
+static int choose_ksplit(int KS, int n_blocks, int slots) {
     if (KS % 16) return 0;
     const int units = KS / 16;
     int best = 1;
     for (int sp = 1; sp <= units; ++sp) {
         if (units % sp) continue;
         best = sp;
-        if ((long)n_blocks * sp >= n_cu) break;
+        if ((long)n_blocks * sp >= slots) break;
     }
     return best;
 }
+// workgroups of the tiled kernel the chip holds at once: two per compute unit up to 3 row tiles
+static int tiled_slots(int M, int twc, int n_cu) { return (twc == 4 && (M + 15) / 16 <= 3) ? 2 * n_cu : n_cu; }
 
 int tiled_supported(const dsd_model_desc* d) {
     return mfma_supported(d) && d->d_model % 512 == 0 && (d->n_q_heads * d->head_dim) % 512 == 0 && d->d_ffn % 512 == 0;
@@ -419,7 +432,7 @@ int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, const float* a, float* x, int
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     const int twc = choose_twc(M, N / 16, ctx->n_cu);
     const int nb = ceil_div(N / 16, twc * NTW);
-    const int sp = choose_ksplit(p.KS, nb, ctx->n_cu);
+    const int sp = choose_ksplit(p.KS, nb, tiled_slots(M, twc, ctx->n_cu));
     p.ks_per_split = p.KS / sp;
     return tiled_dispatch<TE_ATOMIC>(ctx->stream, p, twc, nb, sp);
 }
@@ -434,10 +447,10 @@ int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* g
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     const int twc = choose_twc(M, N / 16, ctx->n_cu);
     const int nb = ceil_div(N / 16, twc * NTW);
-    const int sp = choose_ksplit(p.KS, nb, ctx->n_cu);
+    const int sp = choose_ksplit(p.KS, nb, tiled_slots(M, twc, ctx->n_cu));
     p.ks_per_split = p.KS / sp;
     DSD_TRY((tiled_dispatch<TE_ATOMIC>(ctx->stream, p, twc, nb, sp)));
-    qkv_finish_kernel<<<M, 256, 0, ctx->stream>>>(acc, ssq, q, kc, vc, g, len, depth, k, Hq, K, eps, theta);
+    qkv_finish_kernel<<<dim3(M, 4), 256, 0, ctx->stream>>>(acc, ssq, q, kc, vc, g, len, depth, k, Hq, K, eps, theta);
     return DSD_OK;
 }
 
