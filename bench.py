@@ -178,6 +178,20 @@ def main():
         t1 = time.perf_counter()
         ms = (t1 - t0) * 1e3 / args.steps
 
+        # spread of the step latency: event pairs around every step of one more pass (the events sit on
+        # the library's stream, which is torch's current stream here)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in evs:
+            e0.record()
+            step()
+            e1.record()
+        stream.synchronize()
+        lat = np.sort(np.array([e0.elapsed_time(e1) for e0, e1 in evs]))
+        pct = {q: float(lat[min(len(lat) - 1, int(round(q / 100.0 * (len(lat) - 1))))]) for q in (10, 50, 90)}
+        committed = None
+        if m.has_head:
+            committed = float((alen.sum().item() + B)) / (ms * 1e-3)    # accepted tokens + the extra one per sequence
+
         # per-kernel-class durations from HIP events on the library's stream: a second pass over the
         # same K steps (the events cost a little per launch, so the timed region above runs without)
         ctx.profile_enable(True)
@@ -243,6 +257,8 @@ def main():
                                + (f" accept={args.tree_mode}" if m.has_head and args.tree_mode != "longest" else "")
                                + (f" T={args.temperature:g}" if m.has_head and args.temperature != 1.0 else "")},
         "verify_step_latency_ms": ms,
+        "step_latency_ms_p10_p50_p90": [round(pct[10], 5), round(pct[50], 5), round(pct[90], 5)],
+        "committed_tokens_per_s": committed,
         "stage_algorithmic_GB": total_bytes / 1e9,
         "stage_achieved_GBps": (total_bytes + accept_bytes) / (ms * 1e-3) / 1e9,
         "stage_frac_of_hbm_peak": (total_bytes + accept_bytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
