@@ -37,6 +37,41 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     // D[4*(lane/16)+i][lane%16] += sum_k A[lane%16][8*(lane/16)+k] * B[8*(lane/16)+k][lane%16]
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
+// The weight GEMMs run on the fp16 form of the same instruction: the weights are stored as fp16
+// (exact for every bf16 value of magnitude 2^-17 .. 65504, see tile_weights_kernel) and the
+// activations enter with fp16's 11 significant bits, which one operand plane of bf16 cannot give.
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+#define F16_MAX 65504.0f
+// round to nearest; magnitudes beyond the fp16 range saturate instead of becoming infinite
+__device__ __forceinline__ unsigned pack_f16(float a, float b) {
+    f32x2 v = {__builtin_fminf(__builtin_fmaxf(a, -F16_MAX), F16_MAX), __builtin_fminf(__builtin_fmaxf(b, -F16_MAX), F16_MAX)};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, f16x2));
+}
+__device__ __forceinline__ f16x8 pack8h(const float* f) {
+    uint4 u = {pack_f16(f[0], f[1]), pack_f16(f[2], f[3]), pack_f16(f[4], f[5]), pack_f16(f[6], f[7])};
+    return __builtin_bit_cast(f16x8, u);
+}
+// v = hi + lo with both halves fp16, ~21 significant bits.  hi is v rounded toward zero, which maps
+// magnitudes beyond the fp16 range to the largest finite value at no cost (no clamp); lo carries the
+// remainder (less than one unit in hi's last place), so the direction of hi's rounding is immaterial.
+__device__ __forceinline__ unsigned pack_f16_rtz(float a, float b) {
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+__device__ __forceinline__ void split8h(const float* v, f16x8* hi, f16x8* lo) {
+    const uint4 hu = {pack_f16_rtz(v[0], v[1]), pack_f16_rtz(v[2], v[3]), pack_f16_rtz(v[4], v[5]), pack_f16_rtz(v[6], v[7])};
+    const f16x8 h = __builtin_bit_cast(f16x8, hu);
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = v[i] - (float)h[i];
+    const uint4 lu = {pack_f16_rtz(r[0], r[1]), pack_f16_rtz(r[2], r[3]), pack_f16_rtz(r[4], r[5]), pack_f16_rtz(r[6], r[7])};
+    *hi = h;
+    *lo = __builtin_bit_cast(f16x8, lu);
+}
+__device__ __forceinline__ f32x4 mfma16h(f16x8 a, f16x8 b, f32x4 c) {
+    // operand and result layout as mfma16
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
 // 8 bf16 gains (one 16-byte load) -> floats
 __device__ __forceinline__ void unpack_gain(uint4 gu, float* gf) {
     const unsigned gw[4] = {gu.x, gu.y, gu.z, gu.w};

@@ -1,14 +1,15 @@
 // Weight-streaming GEMM for 17..128 rows (B*k of the batched verification pass, section 2.1).
 //
 // With this many rows the pass is still bound by streaming the weights once, but the activation
-// operand is no longer negligible: every weight fragment meets 2*MT activation fragments (hi + lo
-// bf16 of MT 16-row tiles).  So the activations are shared through LDS and only the weights come
-// straight from HBM into registers:
+// operand is no longer negligible: every weight fragment meets MT activation fragments (one fp16
+// plane of MT 16-row tiles; two planes, as the kernels for up to 16 rows use, would make the matrix
+// cores the bound at 128 rows).  So the activations are shared through LDS and only the weights
+// come straight from HBM into registers:
 //   * a workgroup of 4 (or 8) computing waves owns 128 (256) output columns, each wave two
 //     16-column tiles, over one contiguous slice of K (grid.y splits K when a matrix has too few
 //     column blocks to fill the chip; partial results are then added atomically into an fp32 buffer);
-//   * the activations are converted ONCE per GEMM by a small kernel of their own (gain, hi/lo
-//     split, A-operand order, sum of squares for the RMSNorm scale) into a panel in global memory;
+//   * the activations are converted ONCE per GEMM by a small kernel of their own (gain, fp16,
+//     A-operand order, sum of squares for the RMSNorm scale) into a panel in global memory;
 //     doing that inside every workgroup cost more vector ALU time than the matrix cores had work;
 //   * the slice is walked in chunks of 128 columns of K; the workgroup has 4 more waves that do
 //     nothing but fetch the next chunk of the panel from global memory straight into LDS (double
@@ -41,7 +42,7 @@ struct TArgs {
     int KS;              // K / 32
     int ks_per_split;    // k-steps per workgroup, multiple of 16
     int M;
-    const uint4* panel;  // activations as hi/lo bf16 in A-operand order: [2][KS][MT][64] (act_panel_kernel)
+    const uint4* panel;  // activations as fp16 in A-operand order: [KS][MT][64] (act_panel_kernel)
     const float* ssq;    // [16*MT] sum of squares of every activation row, or NULL (no RMSNorm scale)
     float eps;
     float* out;          // TE_ATOMIC: [M][N] fp32, += ;  TE_SWIGLU: h [M][N];  TE_LOGITS: logits
@@ -52,17 +53,13 @@ struct TArgs {
 };
 
 // fetching wave ks (0..3) brings k-step ks of a chunk into the panel buffer at LDS byte address buf:
-// entry (ks*MT + mt)*64 + lane of both planes (hi at entry 0, lo at entry 4*MT*64)
+// entry (ks*MT + mt)*64 + lane
 template <int MT>
 __device__ __forceinline__ void tpanel_fetch(const TArgs& p, int ks_abs, unsigned buf, int ks) {
     const int lane = threadIdx.x & 63;
-    const uint4* hi = p.panel + ((size_t)(ks_abs + ks) * MT) * 64 + lane;
-    const uint4* lo = hi + (size_t)p.KS * MT * 64;
+    const uint4* src = p.panel + ((size_t)(ks_abs + ks) * MT) * 64 + lane;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        gload16_lds(buf + ((ks * MT + i) * 64) * 16, hi + i * 64);
-        gload16_lds(buf + ((4 * MT + ks * MT + i) * 64) * 16, lo + i * 64);
-    }
+    for (int i = 0; i < MT; ++i) gload16_lds(buf + ((ks * MT + i) * 64) * 16, src + i * 64);
 }
 
 // Next k-step of the weight stream; past the end of the slice (the last turn of refills, never
@@ -81,21 +78,16 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restr
                                          const uint4* (&w)[NTW], int& left, int lane) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 ahi[MT], alo[MT];
+        f16x8 a[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            ahi[mt] = __builtin_bit_cast(bf16x8, panel[(ks * MT + mt) * 64 + lane]);
-            alo[mt] = __builtin_bit_cast(bf16x8, panel[4 * MT * 64 + (ks * MT + mt) * 64 + lane]);
-        }
+        for (int mt = 0; mt < MT; ++mt) a[mt] = __builtin_bit_cast(f16x8, panel[(ks * MT + mt) * 64 + lane]);
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
             const int slot = S0 + ks * NTW + nt;
             vm_wait<NF - 1>(fifo[slot]);
-            const bf16x8 b = __builtin_bit_cast(bf16x8, fifo[slot]);
+            const f16x8 b = __builtin_bit_cast(f16x8, fifo[slot]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(ahi[mt], b, acc[mt][nt]);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(alo[mt], b, acc[mt][nt]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16h(a[mt], b, acc[mt][nt]);
             // refill one FIFO turn ahead; past the end of the slice keep re-reading the last fragment
             gload16(fifo[slot], w[nt]);
         }
@@ -103,7 +95,7 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restr
     }
 }
 
-// The same for 6 or 8 row tiles, where one k-step is 24..32 matrix instructions behind 12..16 LDS
+// The same for 6 or 8 row tiles, where one k-step is 12..16 matrix instructions behind 6..8 LDS
 // reads: the row tiles are taken in two halves and the activation fragments of the next half are
 // requested before the matrix instructions of the current one, so that LDS latency hides behind
 // them (a computing wave has no partner on its SIMD to do that for it).  A weight fragment is used
@@ -113,13 +105,10 @@ template <int MT, int NF, int S0>
 __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* __restrict__ panel,
                                                 f32x4 (&acc)[MT][NTW], const uint4* (&w)[NTW], int& left, int lane) {
     constexpr int H = MT / 2;
-    bf16x8 a[2][2 * H];                               // [buffer][hi of H tiles, lo of H tiles]
+    f16x8 a[2][H];                                    // [buffer][row tile of the half]
     auto fetch = [&](int buf, int ks, int half) {
 #pragma unroll
-        for (int m = 0; m < H; ++m) {
-            a[buf][m] = __builtin_bit_cast(bf16x8, panel[(ks * MT + half * H + m) * 64 + lane]);
-            a[buf][H + m] = __builtin_bit_cast(bf16x8, panel[4 * MT * 64 + (ks * MT + half * H + m) * 64 + lane]);
-        }
+        for (int m = 0; m < H; ++m) a[buf][m] = __builtin_bit_cast(f16x8, panel[(ks * MT + half * H + m) * 64 + lane]);
     };
     fetch(0, 0, 0);
 #pragma unroll
@@ -133,11 +122,9 @@ __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* 
                 if (nt == 0) vm_wait<NF - 1>(fifo[slot]);
                 else vm_wait<NF - 2>(fifo[slot]);
             }
-            const bf16x8 b = __builtin_bit_cast(bf16x8, fifo[slot]);
+            const f16x8 b = __builtin_bit_cast(f16x8, fifo[slot]);
 #pragma unroll
-            for (int m = 0; m < H; ++m) acc[half * H + m][nt] = mfma16(a[hs & 1][m], b, acc[half * H + m][nt]);
-#pragma unroll
-            for (int m = 0; m < H; ++m) acc[half * H + m][nt] = mfma16(a[hs & 1][H + m], b, acc[half * H + m][nt]);
+            for (int m = 0; m < H; ++m) acc[half * H + m][nt] = mfma16h(a[hs & 1][m], b, acc[half * H + m][nt]);
             if (half == 1) gload16(fifo[slot], w[nt]);
         }
         if (half == 1) tadvance(w, left);
@@ -149,16 +136,16 @@ __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* 
 // second launch bound is waves per SIMD: two resident workgroups for the smallest tiles.
 template <int MT, int TWC, int EPI>
 __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 : 2)) gemm_tiled_kernel(TArgs p) {
-    extern __shared__ uint4 lds[];                    // 2 panel buffers of 2 * 4*MT*64 uint4
+    extern __shared__ uint4 lds[];                    // 2 panel buffers of 4*MT*64 uint4
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int ks0 = blockIdx.y * p.ks_per_split;
     const int nchunk = p.ks_per_split / 4;
-    const size_t pbuf = (size_t)2 * 4 * MT * 64;
+    const size_t pbuf = (size_t)4 * MT * 64;
     if (wave >= TWC) {
         // low half of a flat pointer into LDS = its LDS byte address
         const unsigned lds_addr = (unsigned)(size_t)lds;
-        const unsigned pbuf_bytes = 2 * 4 * MT * 64 * 16;
+        const unsigned pbuf_bytes = 4 * MT * 64 * 16;
         // one barrier per chunk, matched by the computing waves below
         tpanel_fetch<MT>(p, ks0, lds_addr, wave - TWC);
         vm_wait_all<0>();
@@ -262,7 +249,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
 
 // Activations -> panel.  Block (chunk, mt) of 4 waves: wave w handles k-step 4*chunk + w, lane
 // (c = lane%16, g = lane/16) the 8 values k = 32ks + 8g .. +8 of row 16mt + c: multiplied by the gain
-// (if any), split into hi + lo bf16, stored at entry (ks*MT + mt)*64 + lane of the two planes.  With
+// (if any), rounded to fp16 (saturating), stored at entry (ks*MT + mt)*64 + lane.  With
 // a gain the sum of squares of every row is accumulated (atomically) for the RMSNorm scale.
 __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ panel, float* __restrict__ ssq,
                                                         const float* __restrict__ a,
@@ -290,11 +277,7 @@ __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ pane
         q += __shfl_xor(q, 32, WAVE);
         if (lane < 16) unsafeAtomicAdd(ssq + row, q);
     }
-    bf16x8 hi, lo;
-    split8(v, &hi, &lo);
-    const size_t e = ((size_t)ks * MT + mt) * 64 + lane;
-    panel[e] = __builtin_bit_cast(uint4, hi);
-    panel[(size_t)KS * MT * 64 + e] = __builtin_bit_cast(uint4, lo);
+    panel[((size_t)ks * MT + mt) * 64 + lane] = __builtin_bit_cast(uint4, pack8h(v));
 }
 
 // q, k, v rows accumulated by the split-K QKV GEMM -> RMSNorm scale, rotary embedding, cache append.
@@ -350,7 +333,7 @@ __global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc
 // ---------------------------------------------------------------------------- host side
 template <int MT, int TWC, int EPI>
 static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
-    const size_t lds = (size_t)2 * 2 * 4 * MT * 64 * 16;
+    const size_t lds = (size_t)2 * 4 * MT * 64 * 16;
     auto kern = gemm_tiled_kernel<MT, TWC, EPI>;
     // once per instantiation and process: the limit is a property of the function, and setting it
     // again on every call would put a non-stream call into a caller's graph capture

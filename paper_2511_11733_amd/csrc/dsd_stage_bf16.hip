@@ -4,15 +4,17 @@
 // The pass is bound by streaming the block's weights and the KV cache from HBM once; the k*B
 // activation rows are tiny.  Hence:
 //   * weights are re-tiled once (dsd_weights_create) into the exact operand order of
-//     v_mfma_f32_16x16x32_bf16, so that every wavefront load is one contiguous KiB;
+//     v_mfma_f32_16x16x32_f16, converted to fp16 (exact for bf16 magnitudes 2^-17 .. 65504), so that
+//     every wavefront load is one contiguous KiB;
 //   * a GEMM workgroup owns one (or a pair of) 16-column tiles and splits K over its waves,
 //     partial tiles meet in LDS, and the epilogue is fused: RMSNorm scale, rotary embedding +
 //     KV-cache append, SiLU*up, residual add, or fp32 logits;
 //   * RMSNorm never makes a pass of its own: x*g is applied while the A operand is loaded, the
 //     sum of squares is accumulated from those same loads, and 1/rms scales the output rows;
-//   * activations enter the matrix cores as a sum of two bf16 terms (hi + lo, two MFMAs per weight
-//     fragment): the weights stay bit-exact bf16, the activations keep ~16 mantissa bits, and
-//     the extra MFMA work is free while the pass is bandwidth bound;
+//   * up to 16 rows, activations enter the matrix cores as a sum of two fp16 terms (hi + lo, two
+//     MFMAs per weight fragment, ~22 significant bits; the extra MFMA work is free while the pass is
+//     bandwidth bound); from 17 rows on as one fp16 term (11 bits, see dsd_gemm_tiled.hip).  Queries
+//     and attention weights meet the bf16 cache as hi + lo bf16;
 //   * attention computes S^T = K Q^T so that the scores a lane holds are exactly the P^T operand
 //     of O^T = V^T P^T; V is cached transposed for that product (see KvGeom).
 #include <stdlib.h>
@@ -20,9 +22,12 @@
 #include "dsd_bf16_dev.h"
 
 // ============================================================================ weight tiling
-// dst fragment (nt, ks): lane l holds W[nt*16 + l%16][ks*32 + (l/16)*8 .. +8]
+// dst fragment (nt, ks): lane l holds W[nt*16 + l%16][ks*32 + (l/16)*8 .. +8], converted to fp16.
+// The conversion is exact for every bf16 value of magnitude 2^-17 .. 65504 (8 significant bits fit
+// into fp16's 11, and into its subnormals down to 2^-24 granularity); smaller ones round to the
+// nearest multiple of 2^-24.  A weight beyond the fp16 range (or not finite) is counted in *bad.
 __global__ void tile_weights_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K,
-                                    size_t dst_tile_off) {
+                                    size_t dst_tile_off, int* __restrict__ bad) {
     const int KS = K / 32;
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t total = (size_t)(N / 16) * KS * 64;
@@ -32,7 +37,13 @@ __global__ void tile_weights_kernel(uint4* __restrict__ dst, const bf16_t* __res
     const int ks = (int)(f % KS);
     const size_t nt = f / KS;
     const size_t s = (nt * 16 + (l & 15)) * (size_t)K + (size_t)ks * 32 + (l >> 4) * 8;
-    dst[dst_tile_off * KS * 64 + idx] = *(const uint4*)(src + s);
+    float v[8];
+    unpack_gain(*(const uint4*)(src + s), v);
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ok = ok && fabsf(v[i]) <= F16_MAX;      // false for NaN too
+    if (!ok) atomicAdd(bad, 1);
+    dst[dst_tile_off * KS * 64 + idx] = __builtin_bit_cast(uint4, pack8h(v));
 }
 
 int mfma_supported(const dsd_model_desc* d) {
@@ -40,10 +51,10 @@ int mfma_supported(const dsd_model_desc* d) {
            d->d_model % 16 == 0 && d->d_ffn % 16 == 0 && (!d->has_head || d->vocab % 16 == 0);
 }
 
-static int tile_into(dsd_ctx* ctx, void* dst, size_t dst_tile_off, const void* src, int N, int K) {
+static int tile_into(dsd_ctx* ctx, int* bad, void* dst, size_t dst_tile_off, const void* src, int N, int K) {
     const size_t total = (size_t)(N / 16) * (K / 32) * 64;
     tile_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, ctx->stream>>>((uint4*)dst, (const bf16_t*)src, N, K,
-                                                                              dst_tile_off);
+                                                                              dst_tile_off, bad);
     DSD_HIP(hipGetLastError());
     return DSD_OK;
 }
@@ -60,6 +71,9 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors) 
     const dsd_model_desc& D = w->desc;
     const int d = D.d_model, qd = D.n_q_heads * D.head_dim, kd = D.n_kv_heads * D.head_dim, F = D.d_ffn;
     int t = D.has_embed ? 1 : 0;
+    int* bad = nullptr;                               // weights that fp16 cannot hold
+    DSD_TRY(dev_alloc(w, 256, (void**)&bad));
+    DSD_HIP(hipMemsetAsync(bad, 0, 4, ctx->stream));
     for (int l = 0; l < D.n_layers; ++l) {
         LayerW& L = w->layers[l];
         const void* const* T = tensors + t;
@@ -69,23 +83,27 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors) 
         DSD_TRY(dev_alloc(w, (size_t)d * 2, &L.g2));
         DSD_HIP(hipMemcpyAsync(L.g2, T[5], (size_t)d * 2, hipMemcpyDeviceToDevice, ctx->stream));
         DSD_TRY(dev_alloc(w, (size_t)(qd + 2 * kd) * d * 2, &L.qkv_t));
-        DSD_TRY(tile_into(ctx, L.qkv_t, 0, T[1], qd, d));
-        DSD_TRY(tile_into(ctx, L.qkv_t, qd / 16, T[2], kd, d));
-        DSD_TRY(tile_into(ctx, L.qkv_t, (qd + kd) / 16, T[3], kd, d));
+        DSD_TRY(tile_into(ctx, bad, L.qkv_t, 0, T[1], qd, d));
+        DSD_TRY(tile_into(ctx, bad, L.qkv_t, qd / 16, T[2], kd, d));
+        DSD_TRY(tile_into(ctx, bad, L.qkv_t, (qd + kd) / 16, T[3], kd, d));
         DSD_TRY(dev_alloc(w, (size_t)d * qd * 2, &L.wo_t));
-        DSD_TRY(tile_into(ctx, L.wo_t, 0, T[4], d, qd));
+        DSD_TRY(tile_into(ctx, bad, L.wo_t, 0, T[4], d, qd));
         DSD_TRY(dev_alloc(w, (size_t)2 * F * d * 2, &L.gu_t));
-        DSD_TRY(tile_into(ctx, L.gu_t, 0, T[6], F, d));
-        DSD_TRY(tile_into(ctx, L.gu_t, F / 16, T[7], F, d));
+        DSD_TRY(tile_into(ctx, bad, L.gu_t, 0, T[6], F, d));
+        DSD_TRY(tile_into(ctx, bad, L.gu_t, F / 16, T[7], F, d));
         DSD_TRY(dev_alloc(w, (size_t)d * F * 2, &L.wd_t));
-        DSD_TRY(tile_into(ctx, L.wd_t, 0, T[8], d, F));
+        DSD_TRY(tile_into(ctx, bad, L.wd_t, 0, T[8], d, F));
     }
     if (D.has_head) {
         DSD_TRY(dev_alloc(w, (size_t)d * 2, &w->gf));
         DSD_HIP(hipMemcpyAsync(w->gf, tensors[t], (size_t)d * 2, hipMemcpyDeviceToDevice, ctx->stream));
         DSD_TRY(dev_alloc(w, (size_t)D.vocab * d * 2, &w->lm_t));
-        DSD_TRY(tile_into(ctx, w->lm_t, 0, tensors[t + 1], D.vocab, d));
+        DSD_TRY(tile_into(ctx, bad, w->lm_t, 0, tensors[t + 1], D.vocab, d));
     }
+    int n_bad = 0;
+    DSD_HIP(hipMemcpyAsync(&n_bad, bad, 4, hipMemcpyDeviceToHost, ctx->stream));
+    DSD_HIP(hipStreamSynchronize(ctx->stream));
+    if (n_bad) DSD_FAIL(DSD_EUNSUPPORTED, "%d weight fragments hold values that are not finite or exceed 65504 in magnitude", n_bad);
     if (persist_supported(&D)) DSD_TRY(persist_build_layer_table(w));
     return DSD_OK;
 }
@@ -114,11 +132,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
 
 #pragma unroll 4
     for (int ks = wave; ks < p.KS; ks += nw) {
-        bf16x8 bfrag[NT];
+        f16x8 bfrag[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bfrag[nt] = __builtin_bit_cast(bf16x8, wt[nt][(size_t)ks * 64]);
+        for (int nt = 0; nt < NT; ++nt) bfrag[nt] = __builtin_bit_cast(f16x8, wt[nt][(size_t)ks * 64]);
         const int kb = ks * 32 + g * 8;
-        bf16x8 ahi[MT], alo[MT];
+        f16x8 ahi[MT], alo[MT];
         float gf[8];
         if (AMODE == A_F32_GAIN) {
             const uint4 gu = *(const uint4*)(p.gain + kb);
@@ -147,14 +165,14 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
                     v[i] *= gf[i];
                 }
             }
-            split8(v, &ahi[mt], &alo[mt]);
+            split8h(v, &ahi[mt], &alo[mt]);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                acc[mt][nt] = mfma16(ahi[mt], bfrag[nt], acc[mt][nt]);
-                acc[mt][nt] = mfma16(alo[mt], bfrag[nt], acc[mt][nt]);
+                acc[mt][nt] = mfma16h(ahi[mt], bfrag[nt], acc[mt][nt]);
+                acc[mt][nt] = mfma16h(alo[mt], bfrag[nt], acc[mt][nt]);
             }
     }
 
@@ -491,7 +509,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
     float* qkv_acc = ws.take<float>((size_t)M * n_qkv);
     float* ssq_all = ws.take<float>(n_ssq);          // one row-sum-of-squares array per normalised GEMM input
-    void* panel = ws.take<float>(128 * kmax);         // activations as hi/lo bf16 in A-operand order
+    void* panel = ws.take<float>(64 * kmax);          // up to 128 rows of activations as fp16 in A-operand order
     hipStream_t s = ctx->stream;
     // split-K partial sums of the QKV projection meet in qkv_acc (every layer leaves it cleared again);
     // qkv_acc and ssq_all are adjacent: one fill

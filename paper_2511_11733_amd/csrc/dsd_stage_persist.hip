@@ -213,7 +213,7 @@ __device__ __forceinline__ void stamp(const PArgs& p, int& n) {
 
 // ---------------------------------------------------------------------------- GEMM phase
 // Activations reach the matrix cores through an LDS panel: 2048 columns of K at a time, for the
-// M <= 8 rows in use, already multiplied by the RMSNorm gain, split into hi + lo bf16 and laid
+// M <= 8 rows in use, already multiplied by the RMSNorm gain, split into hi + lo fp16 and laid
 // out in A-operand order (entry ((ks*4 + g)*M + r)*2 + {hi, lo}: the 8 values k = 32ks + 8g .. +8
 // of row r).  Thread t of the workgroup owns k-group t of every chunk (ks = t/4, g = t%4): it
 // loads the raw rows of the NEXT chunk into registers when a chunk starts (those loads are older
@@ -266,8 +266,8 @@ __device__ __forceinline__ void panel_store(u32x4 (&P)[2 * MAXM], u32x4& G, uint
                 }
                 if (count) ssq[r] += q;
             }
-            bf16x8 hi, lo;
-            split8(v, &hi, &lo);
+            f16x8 hi, lo;
+            split8h(v, &hi, &lo);
             dst[2 * r] = __builtin_bit_cast(uint4, hi);
             dst[2 * r + 1] = __builtin_bit_cast(uint4, lo);
         }
@@ -282,15 +282,15 @@ __device__ __forceinline__ void consume8(u32x4 (&fifo)[FIFO], WIter& it, const u
     for (int j = 0; j < 8; ++j) {
         const int ks = wave + PW * (j0 + j);
         const uint4* src = panel + ((size_t)(ks * 4 + g) * M + r) * 2;
-        const bf16x8 hi = __builtin_bit_cast(bf16x8, src[0]);
-        const bf16x8 lo = __builtin_bit_cast(bf16x8, src[1]);
+        const f16x8 hi = __builtin_bit_cast(f16x8, src[0]);
+        const f16x8 lo = __builtin_bit_cast(f16x8, src[1]);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int slot = S0 + j * NT + nt;
             vm_wait<FIFO - 1>(fifo[slot]);      // at most the 15 younger refills may still be in flight
-            const bf16x8 b = __builtin_bit_cast(bf16x8, fifo[slot]);
-            acc[nt] = mfma16(hi, b, acc[nt]);
-            acc[nt] = mfma16(lo, b, acc[nt]);
+            const f16x8 b = __builtin_bit_cast(f16x8, fifo[slot]);
+            acc[nt] = mfma16h(hi, b, acc[nt]);
+            acc[nt] = mfma16h(lo, b, acc[nt]);
             asm volatile("" : "+v"(acc[nt]) : "v"(fifo[slot]));   // the refill below must not overtake the reads
             it.fetch(fifo[slot]);
         }

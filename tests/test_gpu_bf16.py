@@ -174,8 +174,10 @@ def test_shape_errors():
 def test_stage_replays_from_a_hip_graph():
     """Once the workspace has its size the call issues only kernels on the context's stream, so a caller
     may capture it; every replay (with eager work and synchronisations in between) must reproduce the
-    eager result: bit for bit where the arithmetic is ordered (<= 16 rows), to 1e-4 where K-split sums
-    meet by atomics (more rows)."""
+    eager result: bit for bit where the arithmetic is ordered (<= 16 rows).  With more rows K-split sums
+    meet by atomics, so their last bit depends on the order of arrival, and a sum that moves by one
+    bit can carry the next GEMM's fp16 operand across a rounding boundary (2^-11 relative on that one
+    activation): two runs then agree to a tenth of the parity tolerance, not to fp32 rounding."""
     for name, B, k in (("graph_m5", 1, 5), ("graph_m40", 5, 8)):
         cfg, m, w, K, V, hid, parent, lens = mini(name, B=B, k=k, lens=[70 + 9 * b for b in range(B)], head=True,
                                                   V=4112, L=2)
@@ -207,6 +209,6 @@ def test_stage_replays_from_a_hip_graph():
                 if B * k <= 16:
                     assert torch.equal(out, out_ref) and torch.equal(lg, lg_ref), f"{name}: replay {rep} differs"
                 else:
-                    H.assert_close(H.to_np64(lg), H.to_np64(lg_ref), H.TOL["f32"], f"{name} logits, replay {rep}")
+                    H.assert_close(H.to_np64(lg), H.to_np64(lg_ref), H.TOL["bf16"] / 10, f"{name} logits, replay {rep}")
                 run()                                         # eager work between the replays
                 stream.synchronize()
