@@ -7,9 +7,13 @@
 // come straight from HBM into registers:
 //   * a workgroup of 4 (or 8) computing waves owns 128 (256) output columns, each wave two
 //     16-column tiles, over one contiguous slice of K (grid.y splits K when a matrix has too few
-//     column blocks to fill the chip; partial results are then added atomically into an fp32 buffer);
-//   * the activations are converted ONCE per GEMM by a small kernel of their own (gain, fp16,
-//     A-operand order, sum of squares for the RMSNorm scale) into a panel in global memory;
+//     column blocks to fill the chip; every slice then stores its partial result with plain stores
+//     into a buffer of its own and the kernel that reads the result next adds the slices up in a
+//     fixed order: fp32 atomics run at about a quarter of the rate of plain stores on this chip, and
+//     their order of arrival would make the last bits of the result differ from run to run);
+//   * the activations are converted ONCE per GEMM by a small kernel of their own (sum of the
+//     previous GEMM's K slices into the residual stream, gain, fp16, A-operand order, sums of
+//     squares for the RMSNorm scale) into a panel in global memory;
 //     doing that inside every workgroup cost more vector ALU time than the matrix cores had work;
 //   * the slice is walked in chunks of 128 columns of K; the workgroup has 4 more waves that do
 //     nothing but fetch the next chunk of the panel from global memory straight into LDS (double
@@ -35,7 +39,7 @@ template <int N>
 __device__ __forceinline__ void vm_wait(u32x4& r) {
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(N));
 }
-enum { TE_ATOMIC = 0, TE_SWIGLU = 1, TE_LOGITS = 2 };
+enum { TE_PARTIAL = 0, TE_SWIGLU = 1, TE_LOGITS = 2 };
 
 struct TArgs {
     const uint4* Wt;     // tiled weights
@@ -43,9 +47,10 @@ struct TArgs {
     int ks_per_split;    // k-steps per workgroup, multiple of 16
     int M;
     const uint4* panel;  // activations as fp16 in A-operand order: [KS][MT][64] (act_panel_kernel)
-    const float* ssq;    // [16*MT] sum of squares of every activation row, or NULL (no RMSNorm scale)
+    const float* ssq;    // [n_ssq][128] partial sums of squares of every activation row (act_panel_kernel)
+    int n_ssq;
     float eps;
-    float* out;          // TE_ATOMIC: [M][N] fp32, += ;  TE_SWIGLU: h [M][N];  TE_LOGITS: logits
+    float* out;          // TE_PARTIAL: [gridDim.y][M][N] fp32;  TE_SWIGLU: h [M][N];  TE_LOGITS: logits
     int N;
     int up_tile_off;     // TE_SWIGLU: F/16
     int rows_per_seq;    // TE_LOGITS
@@ -136,7 +141,7 @@ __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* 
 // second launch bound is waves per SIMD: two resident workgroups for the smallest tiles.
 template <int MT, int TWC, int EPI>
 __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 : 2)) gemm_tiled_kernel(TArgs p) {
-    extern __shared__ uint4 lds[];                    // 2 panel buffers of 4*MT*64 uint4
+    extern __shared__ uint4 lds[];                    // 2 panel buffers of 4*MT*64 uint4, a table of 128 floats
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int ks0 = blockIdx.y * p.ks_per_split;
@@ -151,8 +156,26 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
         vm_wait_all<0>();
         __syncthreads();
         for (int ch = 0; ch < nchunk; ++ch) {
-            if (ch + 1 < nchunk)
+            if (ch + 1 < nchunk) {
                 tpanel_fetch<MT>(p, ks0 + (ch + 1) * 4, lds_addr + ((ch & 1) ^ 1) * pbuf_bytes, wave - TWC);
+            } else if (EPI != TE_PARTIAL) {
+                // nothing left to fetch: while the computing waves work through the last chunk, add up
+                // the rows' sums of squares (in a fixed order: two lanes per row, four running sums
+                // each; n_ssq is a multiple of 4) into a table of 1/rms behind the panel buffers; the
+                // last barrier hands it over
+                float* rs = (float*)(lds + 2 * pbuf);
+                const int t = threadIdx.x - TWC * 64, r = t >> 1;
+                if (r < 16 * MT) {
+                    float q[4] = {0.f, 0.f, 0.f, 0.f};
+                    for (int j = (t & 1) * 4; j < p.n_ssq; j += 8) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) q[u] += p.ssq[(j + u) * 128 + r];
+                    }
+                    float sq = (q[0] + q[1]) + (q[2] + q[3]);
+                    sq += __shfl_xor(sq, 1, WAVE);
+                    if (!(t & 1)) rs[r] = 1.0f / sqrtf(sq / (float)(p.KS * 32) + p.eps);
+                }
+            }
             vm_wait_all<0>();
             __syncthreads();
         }
@@ -214,29 +237,30 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
 #pragma unroll
     for (int i = 0; i < NF; ++i) asm volatile("" : "+v"(fifo[i]));
 
-    float rstd[MT][4];
+    // 1/rms of this lane's rows, from the table the fetching waves left behind the panel buffers
+    f32x4 rstd[MT];
+    if (EPI != TE_PARTIAL) {
+        const float* rs = (const float*)(lds + 2 * pbuf);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            rstd[mt][i] = (EPI != TE_ATOMIC && p.ssq)
-                              ? 1.0f / sqrtf(p.ssq[mt * 16 + g * 4 + i] / (float)(p.KS * 32) + p.eps) : 1.f;
+        for (int mt = 0; mt < MT; ++mt) rstd[mt] = *(const f32x4*)(rs + mt * 16 + g * 4);
+    }
+    float* part = p.out + (size_t)blockIdx.y * p.M * p.N;      // TE_PARTIAL: this K slice's own buffer
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = mt * 16 + g * 4 + i;
             if (m >= p.M) continue;
-            if (EPI == TE_ATOMIC) {
+            if (EPI == TE_PARTIAL) {
 #pragma unroll
                 for (int nt = 0; nt < NTW; ++nt)
-                    if (live[nt]) unsafeAtomicAdd(p.out + (size_t)m * p.N + tile[nt] * 16 + c, acc[mt][nt][i]);
+                    if (live[nt]) part[(size_t)m * p.N + tile[nt] * 16 + c] = acc[mt][nt][i];
             } else if (EPI == TE_SWIGLU) {
 #pragma unroll
                 for (int nt = 0; nt < NTW; nt += 2)
                     if (live[nt]) {
                         const float gate = acc[mt][nt][i] * rstd[mt][i], up = acc[mt][nt + 1][i] * rstd[mt][i];
-                        p.out[(size_t)m * p.N + tile[nt] * 16 + c] = gate / (1.0f + __expf(-gate)) * up;
+                        p.out[(size_t)m * p.N + tile[nt] * 16 + c] = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
                     }
             } else {
                 float* row = p.out + (size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N;
@@ -248,19 +272,50 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
 }
 
 // Activations -> panel.  Block (chunk, mt) of 4 waves: wave w handles k-step 4*chunk + w, lane
-// (c = lane%16, g = lane/16) the 8 values k = 32ks + 8g .. +8 of row 16mt + c: multiplied by the gain
-// (if any), rounded to fp16 (saturating), stored at entry (ks*MT + mt)*64 + lane.  With
-// a gain the sum of squares of every row is accumulated (atomically) for the RMSNorm scale.
+// (c = lane%16, g = lane/16) the 8 values k = 32ks + 8g .. +8 of row 16mt + c.  If the GEMM before
+// left n_part K slices of a residual update behind (part[s][M][K]), they are added to the values
+// first, slice 0 first, and the sum is stored back: that is the residual stream's update.  Then
+// the values are multiplied by the gain (if any), rounded to fp16 (saturating) and stored at entry
+// (ks*MT + mt)*64 + lane.  With a gain the block's share of every row's sum of squares goes to
+// ssq[chunk][128]; whoever needs the RMSNorm scale adds the chunks up in order.
 __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ panel, float* __restrict__ ssq,
-                                                        const float* __restrict__ a,
-                                                        const bf16_t* __restrict__ gain, int M, int K, int MT) {
+                                                        float* __restrict__ a, const bf16_t* __restrict__ gain,
+                                                        const float* __restrict__ part, int n_part, int M, int K,
+                                                        int MT) {
+    __shared__ float s_q[4][16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4, mt = blockIdx.y;
-    const int ks = blockIdx.x * 4 + wave, KS = K / 32;
+    const int ks = blockIdx.x * 4 + wave;
     const int row = mt * 16 + c, kb = ks * 32 + g * 8;
     float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (row < M) {
-        const float4 v0 = *(const float4*)(a + (size_t)row * K + kb), v1 = *(const float4*)(a + (size_t)row * K + kb + 4);
+        float* src = a + (size_t)row * K + kb;
+        float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
+        if (n_part > 0) {
+            const float* ps = part + (size_t)row * K + kb;
+            const size_t slice = (size_t)M * K;
+            int sl = 0;
+            for (; sl + 4 <= n_part; sl += 4, ps += 4 * slice) {      // four slices in flight, added in slice order
+                float4 p0[4], p1[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    p0[u] = *(const float4*)(ps + u * slice);
+                    p1[u] = *(const float4*)(ps + u * slice + 4);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    v0.x += p0[u].x; v0.y += p0[u].y; v0.z += p0[u].z; v0.w += p0[u].w;
+                    v1.x += p1[u].x; v1.y += p1[u].y; v1.z += p1[u].z; v1.w += p1[u].w;
+                }
+            }
+            for (; sl < n_part; ++sl, ps += slice) {
+                const float4 q0 = *(const float4*)ps, q1 = *(const float4*)(ps + 4);
+                v0.x += q0.x; v0.y += q0.y; v0.z += q0.z; v0.w += q0.w;
+                v1.x += q1.x; v1.y += q1.y; v1.z += q1.z; v1.w += q1.w;
+            }
+            *(float4*)src = v0;
+            *(float4*)(src + 4) = v1;
+        }
         v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
         v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
     }
@@ -275,24 +330,41 @@ __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ pane
         }
         q += __shfl_xor(q, 16, WAVE);
         q += __shfl_xor(q, 32, WAVE);
-        if (lane < 16) unsafeAtomicAdd(ssq + row, q);
+        if (lane < 16) s_q[wave][lane] = q;
+        __syncthreads();
+        if (threadIdx.x < 16)
+            ssq[blockIdx.x * 128 + mt * 16 + threadIdx.x] =
+                ((s_q[0][threadIdx.x] + s_q[1][threadIdx.x]) + s_q[2][threadIdx.x]) + s_q[3][threadIdx.x];
     }
     panel[((size_t)ks * MT + mt) * 64 + lane] = __builtin_bit_cast(uint4, pack8h(v));
 }
 
-// q, k, v rows accumulated by the split-K QKV GEMM -> RMSNorm scale, rotary embedding, cache append.
-// Block (row, part): the heads are dealt out over gridDim.y blocks; the row's 64 rotation angles are
-// the same for every head, so each block works them out once (fp64) into LDS.  The accumulator row
-// is cleared for the next layer.
-__global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc, const float* __restrict__ ssq,
+// x[M][K] += sum of n_part K slices, in order (the residual update when no panel kernel follows)
+__global__ void __launch_bounds__(256) resid_reduce_kernel(float* __restrict__ x, const float* __restrict__ part,
+                                                           int n_part, size_t n) {
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n) return;
+    float4 v = *(const float4*)(x + i);
+    for (int sl = 0; sl < n_part; ++sl) {
+        const float4 p4 = *(const float4*)(part + (size_t)sl * n + i);
+        v.x += p4.x; v.y += p4.y; v.z += p4.z; v.w += p4.w;
+    }
+    *(float4*)(x + i) = v;
+}
+
+// K slices of the q, k, v rows (part[s][M][heads*128]) -> their sum in slice order, RMSNorm scale,
+// rotary embedding, cache append.  Block (row, share): the heads are dealt out over gridDim.y
+// blocks; the row's 64 rotation angles are the same for every head, so each block works them out
+// once (fp64) into LDS, and its second wave adds up the row's sums of squares.
+__global__ void __launch_bounds__(256) qkv_finish_kernel(const float* __restrict__ part, int n_part, int M,
+                                                         const float* __restrict__ ssq, int n_ssq,
                                                          float* __restrict__ q, bf16_t* __restrict__ kc,
                                                          bf16_t* __restrict__ vc, KvGeom g,
                                                          const int32_t* __restrict__ len,
                                                          const int32_t* __restrict__ depth, int k, int Hq, int d,
                                                          float eps, float theta) {
-    __shared__ float s_cs[64], s_sn[64];
+    __shared__ float s_cs[64], s_sn[64], s_rstd;
     const int m = blockIdx.x, b = m / k, t = m % k;
-    const float rstd = 1.0f / sqrtf(ssq[m] / (float)d + eps);
     const int L = len[b];
     const int slot = L + t;
     if (threadIdx.x < 64) {
@@ -302,17 +374,45 @@ __global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc
         sincos(pos * inv, &sn, &cs);
         s_cs[threadIdx.x] = (float)cs;
         s_sn[threadIdx.x] = (float)sn;
+    } else if (threadIdx.x < 128) {
+        const int lane = threadIdx.x - 64;
+        float sq = 0.f;
+        for (int j = lane; j < n_ssq; j += 64) sq += ssq[j * 128 + m];
+#pragma unroll
+        for (int o = 32; o; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
+        if (lane == 0) s_rstd = 1.0f / sqrtf(sq / (float)d + eps);
     }
     __syncthreads();
+    const float rstd = s_rstd;
     const int heads = Hq + 2 * g.Hkv;
     const int per = (heads + gridDim.y - 1) / gridDim.y;
     const int h0 = blockIdx.y * per, h1 = min(h0 + per, heads);
-    float* row = acc + (size_t)m * heads * 128;
+    const float* row = part + (size_t)m * heads * 128;
+    const size_t slice = (size_t)M * heads * 128;
     for (int i = h0 * 64 + threadIdx.x; i < h1 * 64; i += 256) {
         const int head = i >> 6, e = i & 63;
-        const float lo = row[head * 128 + e] * rstd, hi = row[head * 128 + e + 64] * rstd;
-        row[head * 128 + e] = 0.f;
-        row[head * 128 + e + 64] = 0.f;
+        float lo = 0.f, hi = 0.f;
+        const float* src = row + head * 128 + e;
+        int sl = 0;
+        for (; sl + 4 <= n_part; sl += 4) {            // four slices in flight, added in slice order
+            float l4[4], h4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                l4[u] = src[(sl + u) * slice];
+                h4[u] = src[(sl + u) * slice + 64];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                lo += l4[u];
+                hi += h4[u];
+            }
+        }
+        for (; sl < n_part; ++sl) {
+            lo += src[sl * slice];
+            hi += src[sl * slice + 64];
+        }
+        lo *= rstd;
+        hi *= rstd;
         if (head < Hq + g.Hkv) {
             const float cs = s_cs[e], sn = s_sn[e];
             const float r0 = lo * cs - hi * sn, r1 = hi * cs + lo * sn;
@@ -333,7 +433,7 @@ __global__ void __launch_bounds__(256) qkv_finish_kernel(float* __restrict__ acc
 // ---------------------------------------------------------------------------- host side
 template <int MT, int TWC, int EPI>
 static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit) {
-    const size_t lds = (size_t)2 * 4 * MT * 64 * 16;
+    const size_t lds = (size_t)2 * 4 * MT * 64 * 16 + 128 * 4;
     auto kern = gemm_tiled_kernel<MT, TWC, EPI>;
     // once per instantiation and process: the limit is a property of the function, and setting it
     // again on every call would put a non-stream call into a caller's graph capture
@@ -378,12 +478,13 @@ static int choose_twc(int M, int n_tiles16, int n_cu) {
 }
 
 // K split so that a matrix with few column blocks still fills the chip; every slice a multiple of
-// 16 k-steps.  Returns 0 if K cannot be cut that way.
+// 16 k-steps, at most TILED_MAX_KSPLIT slices (the partial-result buffer is sized for that many).
+// Returns 0 if K cannot be cut that way.
 static int choose_ksplit(int KS, int n_blocks, int slots) {
     if (KS % 16) return 0;
     const int units = KS / 16;
     int best = 1;
-    for (int sp = 1; sp <= units; ++sp) {
+    for (int sp = 1; sp <= units && sp <= TILED_MAX_KSPLIT; ++sp) {
         if (units % sp) continue;
         best = sp;
         if ((long)n_blocks * sp >= slots) break;
@@ -402,62 +503,76 @@ static int mt_of(int M) {
     return mt == 5 ? 6 : (mt == 7 ? 8 : mt);      // tile counts the kernel is built for
 }
 
-static void make_panel(dsd_ctx* ctx, uint4* panel, float* ssq, const float* a, const bf16_t* gain, int M, int K) {
+// x_pending > 0: that many K slices of a residual update wait in `part` and are folded into `a` first
+static void make_panel(dsd_ctx* ctx, uint4* panel, float* ssq, float* a, const bf16_t* gain, const float* part,
+                       int x_pending, int M, int K) {
     const int MT = mt_of(M);
-    act_panel_kernel<<<dim3(K / 128, MT), 256, 0, ctx->stream>>>(panel, ssq, a, gain, M, K, MT);
+    act_panel_kernel<<<dim3(K / 128, MT), 256, 0, ctx->stream>>>(panel, ssq, a, gain, part, x_pending, M, K, MT);
 }
 
-// x[M][N] += a[M][K] W^T   (atomic accumulation over the K slices)
-int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, const float* a, float* x, int M, int N, int K, void* panel) {
-    make_panel(ctx, (uint4*)panel, nullptr, a, nullptr, M, K);
+// K-sliced GEMM: part[s][M][N] = slice s of a[M][K] W^T; returns the number of slices in *n_part
+static int tiled_gemm_partial(dsd_ctx* ctx, const void* Wt, int M, int N, int K, const void* panel, float* part,
+                              int* n_part) {
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = x; p.N = N;
+    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = part; p.N = N;
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     const int twc = choose_twc(M, N / 16, ctx->n_cu);
     const int nb = ceil_div(N / 16, twc * NTW);
     const int sp = choose_ksplit(p.KS, nb, tiled_slots(M, twc, ctx->n_cu));
     p.ks_per_split = p.KS / sp;
-    return tiled_dispatch<TE_ATOMIC>(ctx->stream, p, twc, nb, sp);
+    *n_part = sp;
+    return tiled_dispatch<TE_PARTIAL>(ctx->stream, p, twc, nb, sp);
 }
 
-// acc[M][N] += (x*gain)[M][K] Wqkv^T, then finish (norm scale, rotary, append)
-int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* acc, int M, int N, int K,
-                   float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len, const int32_t* depth, int k,
-                   int Hq, float eps, float theta, void* panel, float* ssq) {
-    make_panel(ctx, (uint4*)panel, ssq, x, gain, M, K);
-    TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = acc; p.N = N;
-    if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    const int twc = choose_twc(M, N / 16, ctx->n_cu);
-    const int nb = ceil_div(N / 16, twc * NTW);
-    const int sp = choose_ksplit(p.KS, nb, tiled_slots(M, twc, ctx->n_cu));
-    p.ks_per_split = p.KS / sp;
-    DSD_TRY((tiled_dispatch<TE_ATOMIC>(ctx->stream, p, twc, nb, sp)));
-    qkv_finish_kernel<<<dim3(M, 4), 256, 0, ctx->stream>>>(acc, ssq, q, kc, vc, g, len, depth, k, Hq, K, eps, theta);
+// The K slices of a[M][K] W^T go to `part`; *n_part of them wait there to be added to the residual
+// stream by the next kernel that reads it (make_panel or tiled_resid_reduce).
+int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, float* a, float* part, int* n_part, int M, int N, int K, void* panel) {
+    make_panel(ctx, (uint4*)panel, nullptr, a, nullptr, nullptr, 0, M, K);
+    return tiled_gemm_partial(ctx, Wt, M, N, K, panel, part, n_part);
+}
+
+// x += the slices waiting in part
+int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, int M, int N) {
+    const size_t n = (size_t)M * N;
+    resid_reduce_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, ctx->stream>>>(x, part, n_part, n);
+    return DSD_OK;
+}
+
+// q, k, v = finish((x*gain)[M][K] Wqkv^T): norm scale, rotary, append.  x first takes the x_pending
+// slices waiting in part; the same buffer then carries the slices of the projection.
+int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, float* part, int x_pending, int M, int N,
+                   int K, float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len, const int32_t* depth,
+                   int k, int Hq, float eps, float theta, void* panel, float* ssq) {
+    make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
+    int sp = 0;
+    DSD_TRY(tiled_gemm_partial(ctx, Wt, M, N, K, panel, part, &sp));
+    qkv_finish_kernel<<<dim3(M, 4), 256, 0, ctx->stream>>>(part, sp, M, ssq, K / 128, q, kc, vc, g, len, depth, k, Hq, K,
+                                                          eps, theta);
     return DSD_OK;
 }
 
 // h[M][F] = silu(rms(x) Wg^T) * (rms(x) Wu^T)
-int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* h, int M, int F, int K,
-                      float eps, void* panel, float* ssq) {
+int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, const float* part, int x_pending,
+                      float* h, int M, int F, int K, float eps, void* panel, float* ssq) {
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    make_panel(ctx, (uint4*)panel, ssq, x, gain, M, K);
+    make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
-    p.eps = eps; p.out = h; p.N = F; p.up_tile_off = F / 16;
+    p.n_ssq = K / 128; p.eps = eps; p.out = h; p.N = F; p.up_tile_off = F / 16;
     // fused SiLU*up needs the whole K in one workgroup: no K split
     const int twc = choose_twc(M, 2 * (F / 16), ctx->n_cu);
     return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, twc, ceil_div(F / 16, twc * NTW / 2), 1);
 }
 
 // logits = rms(x; gf) Wlm^T
-int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, const float* x, const bf16_t* gain, float* logits, int M, int V,
-                      int K, float eps, int rows_per_seq, int64_t seq_stride, void* panel, float* ssq) {
+int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, const float* part, int x_pending,
+                      float* logits, int M, int V, int K, float eps, int rows_per_seq, int64_t seq_stride, void* panel,
+                      float* ssq) {
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    make_panel(ctx, (uint4*)panel, ssq, x, gain, M, K);
+    make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
-    p.eps = eps; p.out = logits; p.N = V; p.rows_per_seq = rows_per_seq; p.seq_stride = seq_stride;
+    p.n_ssq = K / 128; p.eps = eps; p.out = logits; p.N = V; p.rows_per_seq = rows_per_seq; p.seq_stride = seq_stride;
     const int twc = choose_twc(M, V / 16, ctx->n_cu);
     return tiled_dispatch<TE_LOGITS>(ctx->stream, p, twc, ceil_div(V / 16, twc * NTW), 1);
 }

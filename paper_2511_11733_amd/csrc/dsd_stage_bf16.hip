@@ -432,10 +432,6 @@ __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ o
 }
 
 // ============================================================================ small kernels
-__global__ void zero16_kernel(uint4* __restrict__ p, size_t n16) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
-}
 __global__ void rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__ h, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) x[i] = bf16_to_f32(h[i]);
@@ -495,8 +491,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
 
     const int n_qkv = (Hq + 2 * Hkv) * hd;
     const size_t kmax = (size_t)std::max(std::max(d, qd), F);
-    const size_t n_ssq = (size_t)128 * (2 * D.n_layers + 1);
-    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + (size_t)M * n_qkv * 4 +
+    // tiled path: K slices of one GEMM's result (up to TILED_MAX_KSPLIT of them), and per-chunk sums of squares
+    const size_t n_part = tiled ? (size_t)TILED_MAX_KSPLIT * M * std::max(d, n_qkv) : 0;
+    const size_t n_ssq = (size_t)128 * (d / 128 + 1);
+    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + n_part * 4 +
                   128 * kmax * 4 + n_ssq * 4 +
                   (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
@@ -507,18 +505,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     float* h = ws.take<float>((size_t)M * F);
     float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
     float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
-    float* qkv_acc = ws.take<float>((size_t)M * n_qkv);
-    float* ssq_all = ws.take<float>(n_ssq);          // one row-sum-of-squares array per normalised GEMM input
+    float* part = ws.take<float>(n_part);
+    float* ssq = ws.take<float>(n_ssq);              // [d/128][128]: sums of squares of the rows, per chunk of 128 columns
     void* panel = ws.take<float>(64 * kmax);          // up to 128 rows of activations as fp16 in A-operand order
     hipStream_t s = ctx->stream;
-    // split-K partial sums of the QKV projection meet in qkv_acc (every layer leaves it cleared again);
-    // qkv_acc and ssq_all are adjacent: one fill
-    // (a kernel rather than a memset, so that a caller may capture the call into a HIP graph)
-    if (tiled) {
-        const size_t n16 = (size_t)((char*)(ssq_all + n_ssq) - (char*)qkv_acc) / 16;
-        zero16_kernel<<<(unsigned)((n16 + 255) / 256), 256, 0, s>>>((uint4*)qkv_acc, n16);
-    }
-
+    int x_pending = 0;                                // K slices in `part` that the residual stream has not taken yet
     const size_t nx = (size_t)M * d;
     {
         ProfScope ps(ctx, DSD_KC_OTHER);
@@ -539,10 +530,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.theta = D.rope_theta;
         {
             ProfScope ps(ctx, DSD_KC_QKV);
-            if (tiled)
-                DSD_TRY(tiled_gemm_qkv(ctx, W.qkv_t, x, (const bf16_t*)W.g1, qkv_acc, M, n_qkv, d, q, kc, vc, g,
-                                       kv->len_dev, depth, k, Hq, D.rms_eps, D.rope_theta, panel, ssq_all + (size_t)128 * (2 * l)));
-            else
+            if (tiled) {
+                DSD_TRY(tiled_gemm_qkv(ctx, W.qkv_t, x, (const bf16_t*)W.g1, part, x_pending, M, n_qkv, d, q, kc, vc, g,
+                                       kv->len_dev, depth, k, Hq, D.rms_eps, D.rope_theta, panel, ssq));
+                x_pending = 0;
+            } else
                 DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
         }
         // attention
@@ -568,7 +560,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
-            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, att, x, M, d, qd, panel));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, att, part, &x_pending, M, d, qd, panel));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
@@ -577,22 +569,27 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.hout = h; a.N = F; a.up_tile_off = F / 16;
         {
             ProfScope ps(ctx, DSD_KC_GATEUP);
-            if (tiled)
-                DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, h, M, F, d, D.rms_eps, panel,
-                                          ssq_all + (size_t)128 * (2 * l + 1)));
-            else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
+            if (tiled) {
+                DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, part, x_pending, h, M, F, d, D.rms_eps,
+                                          panel, ssq));
+                x_pending = 0;
+            } else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
         }
         // x += h Wd^T
         a = GemmArgs();
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
-            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, h, x, M, d, F, panel));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, h, part, &x_pending, M, d, F, panel));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
     }
     if (hidden_out) {
         ProfScope ps(ctx, DSD_KC_OTHER);
+        if (x_pending) {
+            DSD_TRY(tiled_resid_reduce(ctx, x, part, x_pending, M, d));
+            x_pending = 0;
+        }
         rows_out_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>((bf16_t*)hidden_out, x, nx);
     }
     if (logits) {
@@ -601,8 +598,8 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.logits = logits; a.N = D.vocab; a.rows_per_seq = k; a.seq_stride = logits_seq_stride;
         ProfScope ps(ctx, DSD_KC_HEAD);
         if (tiled)
-            DSD_TRY(tiled_gemm_logits(ctx, w->lm_t, x, (const bf16_t*)w->gf, logits, M, D.vocab, d, D.rms_eps, k,
-                                      logits_seq_stride, panel, ssq_all + (size_t)128 * (2 * D.n_layers)));
+            DSD_TRY(tiled_gemm_logits(ctx, w->lm_t, x, (const bf16_t*)w->gf, part, x_pending, logits, M, D.vocab, d,
+                                      D.rms_eps, k, logits_seq_stride, panel, ssq));
         else
             DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
     }
