@@ -348,9 +348,13 @@ __device__ __forceinline__ void attn_run(const AttnArgs& p, int b, int hk, int r
 //   out[m][hq*128 + e] = sum_runs 2^(m_run - M) O_run[e] / sum_runs 2^(m_run - M) l_run
 // Called by a whole workgroup of at least 128 threads (all of them reach the barriers); threads
 // 0..127 each own one feature.  wgt: MAX_RUNS floats of LDS, red: 4 floats of LDS.
+// With `panel` the result goes out as fp16 in the A-operand order of the tiled GEMM for panel_mt
+// row tiles instead (element (row m, column kk) of entry ((kk/32)*MT + m/16)*64 + m%16 + 16*((kk/8)%4),
+// halfword kk%8), ready for the output projection.
 __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const float* __restrict__ part_o,
                                                  const float* __restrict__ part_ml, int n_runs, int rows_pad, int k,
-                                                 int G, int Hq, int Hkv, int r, int hk, int b, float* wgt, float* red) {
+                                                 int G, int Hq, int Hkv, int r, int hk, int b, float* wgt, float* red,
+                                                 unsigned short* __restrict__ panel = nullptr, int panel_mt = 0) {
     const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
     const bool on = e < 128;
     const size_t u0 = (size_t)(b * Hkv + hk) * n_runs;
@@ -386,7 +390,14 @@ __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const 
 #pragma unroll 8
         for (int s = 0; s < n_runs; ++s) num += wgt[s] * po[s * stride];
         const int t = r / G, hq = hk * G + r % G;
-        out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = num / den;
+        if (panel) {
+            const int m = b * k + t, kk = hq * 128 + e;
+            const size_t entry = ((size_t)(kk >> 5) * panel_mt + (m >> 4)) * 64 + (m & 15) + 16 * ((kk >> 3) & 3);
+            const float v = __builtin_fminf(__builtin_fmaxf(num / den, -F16_MAX), F16_MAX);
+            panel[entry * 8 + (kk & 7)] = __builtin_bit_cast(unsigned short, (_Float16)v);
+        } else {
+            out[((size_t)(b * k + t) * Hq + hq) * 128 + e] = num / den;
+        }
     }
     __syncthreads();   // wgt / red may be reused by the caller's next row
 }

@@ -50,7 +50,8 @@ struct TArgs {
     const float* ssq;    // [n_ssq][128] partial sums of squares of every activation row (act_panel_kernel)
     int n_ssq;
     float eps;
-    float* out;          // TE_PARTIAL: [gridDim.y][M][N] fp32;  TE_SWIGLU: h [M][N];  TE_LOGITS: logits
+    float* out;          // TE_PARTIAL: [gridDim.y][M][N] fp32;  TE_LOGITS: logits
+    unsigned short* panel_out;   // TE_SWIGLU: SiLU(gate)*up as fp16 in A-operand order, [N/32][MT][64] entries
     int N;
     int up_tile_off;     // TE_SWIGLU: F/16
     int rows_per_seq;    // TE_LOGITS
@@ -259,8 +260,14 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
 #pragma unroll
                 for (int nt = 0; nt < NTW; nt += 2)
                     if (live[nt]) {
+                        // the next GEMM's operand: row m, column kk of its K -> entry ((kk/32)*MT + m/16)*64 +
+                        // m%16 + 16*((kk/8)%4), halfword kk%8
                         const float gate = acc[mt][nt][i] * rstd[mt][i], up = acc[mt][nt + 1][i] * rstd[mt][i];
-                        p.out[(size_t)m * p.N + tile[nt] * 16 + c] = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+                        const float hv = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+                        const int kk = tile[nt] * 16 + c;
+                        const size_t entry = ((size_t)(kk >> 5) * MT + mt) * 64 + (g * 4 + i) + 16 * ((kk >> 3) & 3);
+                        p.panel_out[entry * 8 + (kk & 7)] =
+                            __builtin_bit_cast(unsigned short, (_Float16)__builtin_fminf(__builtin_fmaxf(hv, -F16_MAX), F16_MAX));
                     }
             } else {
                 float* row = p.out + (size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N;
@@ -521,6 +528,7 @@ static int mt_of(int M) {
     const int mt = (M + 15) / 16;
     return mt == 5 ? 6 : (mt == 7 ? 8 : mt);      // tile counts the kernel is built for
 }
+int tiled_row_tiles(int M) { return mt_of(M); }
 
 // x_pending > 0: that many K slices of a residual update wait in `part` and are folded into `a` first
 static void make_panel(dsd_ctx* ctx, uint4* panel, float* ssq, float* a, const bf16_t* gain, const float* part,
@@ -543,10 +551,10 @@ static int tiled_gemm_partial(dsd_ctx* ctx, const void* Wt, int M, int N, int K,
     return tiled_dispatch<TE_PARTIAL>(ctx->stream, p, twc, nb, sp);
 }
 
-// The K slices of a[M][K] W^T go to `part`; *n_part of them wait there to be added to the residual
-// stream by the next kernel that reads it (make_panel or tiled_resid_reduce).
-int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, float* a, float* part, int* n_part, int M, int N, int K, void* panel) {
-    make_panel(ctx, (uint4*)panel, nullptr, a, nullptr, nullptr, 0, M, K);
+// The K slices of a[M][K] W^T, a given as the operand panel its producer wrote (attention combine,
+// SiLU*up), go to `part`; *n_part of them wait there to be added to the residual stream by the next
+// kernel that reads it (make_panel or tiled_resid_reduce).
+int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, float* part, int* n_part, int M, int N, int K, const void* panel) {
     return tiled_gemm_partial(ctx, Wt, M, N, K, panel, part, n_part);
 }
 
@@ -572,12 +580,12 @@ int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, f
 
 // h[M][F] = silu(rms(x) Wg^T) * (rms(x) Wu^T)
 int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, const float* part, int x_pending,
-                      float* h, int M, int F, int K, float eps, void* panel, float* ssq) {
+                      void* panel_h, int M, int F, int K, float eps, void* panel, float* ssq) {
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
-    p.n_ssq = K / 128; p.eps = eps; p.out = h; p.N = F; p.up_tile_off = F / 16;
+    p.n_ssq = K / 128; p.eps = eps; p.panel_out = (unsigned short*)panel_h; p.N = F; p.up_tile_off = F / 16;
     // fused SiLU*up needs the whole K in one workgroup: no K split
     const int twc = choose_twc(M, 2 * (F / 16), ctx->n_cu);
     return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, twc, ceil_div(F / 16, twc * NTW / 2), 1);

@@ -425,10 +425,12 @@ static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int waves_per
 
 __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ out, const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml, int n_runs, int rows_pad,
-                                                          int k, int G, int Hq, int Hkv) {
+                                                          int k, int G, int Hq, int Hkv,
+                                                          unsigned short* __restrict__ panel, int panel_mt) {
     __shared__ float wgt[MAX_RUNS];
     __shared__ float red[4];
-    attn_combine_row(out, part_o, part_ml, n_runs, rows_pad, k, G, Hq, Hkv, blockIdx.x, blockIdx.y, blockIdx.z, wgt, red);
+    attn_combine_row(out, part_o, part_ml, n_runs, rows_pad, k, G, Hq, Hkv, blockIdx.x, blockIdx.y, blockIdx.z, wgt, red,
+                     panel, panel_mt);
 }
 
 // ============================================================================ small kernels
@@ -508,6 +510,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     float* part = ws.take<float>(n_part);
     float* ssq = ws.take<float>(n_ssq);              // [d/128][128]: sums of squares of the rows, per chunk of 128 columns
     void* panel = ws.take<float>(64 * kmax);          // up to 128 rows of activations as fp16 in A-operand order
+    void* panel_h = h;                                // SiLU*up goes straight into the operand panel of the down projection
     hipStream_t s = ctx->stream;
     int x_pending = 0;                                // K slices in `part` that the residual stream has not taken yet
     const size_t nx = (size_t)M * d;
@@ -553,14 +556,17 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         }
         {
         ProfScope ps(ctx, DSD_KC_ATTN_COMBINE);
-        attn_combine_kernel<<<dim3(rows, Hkv, B), 128, 0, s>>>(att, part_o, part_ml, n_runs, t.rows_pad, k, G, Hq, Hkv);
+        // more than 16 rows: straight into the operand panel of the output projection
+        attn_combine_kernel<<<dim3(rows, Hkv, B), 128, 0, s>>>(att, part_o, part_ml, n_runs, t.rows_pad, k, G, Hq, Hkv,
+                                                               tiled ? (unsigned short*)panel : nullptr,
+                                                               tiled ? tiled_row_tiles(M) : 0);
         }
         // x += attn Wo^T
         a = GemmArgs();
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
-            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, att, part, &x_pending, M, d, qd, panel));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, part, &x_pending, M, d, qd, panel));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
@@ -570,7 +576,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         {
             ProfScope ps(ctx, DSD_KC_GATEUP);
             if (tiled) {
-                DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, part, x_pending, h, M, F, d, D.rms_eps,
+                DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, part, x_pending, panel_h, M, F, d, D.rms_eps,
                                           panel, ssq));
                 x_pending = 0;
             } else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
@@ -580,7 +586,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
-            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, h, part, &x_pending, M, d, F, panel));
+            if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, part, &x_pending, M, d, F, panel_h));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
     }
