@@ -573,7 +573,9 @@ int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, f
     make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     int sp = 0;
     DSD_TRY(tiled_gemm_partial(ctx, Wt, M, N, K, panel, part, &sp));
-    qkv_finish_kernel<<<dim3(M, 4), 256, 0, ctx->stream>>>(part, sp, M, ssq, K / 128, q, kc, vc, g, len, depth, k, Hq, K,
+    // four heads (256 rotation pairs) per block: one pass of the block's threads, all slice loads in flight at once
+    const int heads = N / 128;
+    qkv_finish_kernel<<<dim3(M, (heads + 3) / 4), 256, 0, ctx->stream>>>(part, sp, M, ssq, K / 128, q, kc, vc, g, len, depth, k, Hq, K,
                                                           eps, theta);
     return DSD_OK;
 }
