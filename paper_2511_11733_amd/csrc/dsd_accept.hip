@@ -201,21 +201,101 @@ row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
         ws.part_m[pidx] = mx;
         ws.part_s[pidx] = sum;
     }
-    // top_m candidates of this slice, for the logits row and for the draft row.  Every wave first
-    // selects among its own 512 ids, without barriers, on the 32-bit order-preserving image of the
-    // values (0 = taken or out of range): top_m rounds of a wave-wide maximum; among equal values the
-    // lowest id wins, which inside a wave is the lowest j, then the lowest lane.  Wave 0 then merges
-    // the 4 lists (at most 64 candidates: one per lane) on the full (value, id) keys.
+    // top_m candidates of this slice, for the logits row (a = 0) and for the draft row (a = 1), on
+    // the 32-bit order-preserving image of the values (0 = out of range), ties to the lowest id.
+    // A threshold first: the slice is 16 groups of 16 lanes x 8 ids, and the top_m-th largest of
+    // the 16 group maxima cannot exceed the slice's top_m-th largest value (the maxima are top_m
+    // different ids at least that large), so everything that can be among the top_m lies at or
+    // above it.  Usually a dozen ids pass; they go to a list in LDS and one wave per row kind picks
+    // the top_m of them.  If more than 64 pass (many equal values), the slice falls back to
+    // selection rounds over all ids.
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    __shared__ unsigned sh_gm[2][16];
+    __shared__ int sh_n[2];
+    __shared__ u64 sh_cand[2][64];
     unsigned ot[EPT], oq[EPT];
+    unsigned gt = 0u, gq = 0u;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = base + threadIdx.x + j * TPB;
         ot[j] = i < V ? order_u32(lv[j]) : 0u;
         oq[j] = i < V ? order_u32(qv[j]) : 0u;
+        gt = ot[j] > gt ? ot[j] : gt;
+        gq = oq[j] > gq ? oq[j] : gq;
     }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+        const unsigned t = __shfl_xor(gt, o, WAVE), q = __shfl_xor(gq, o, WAVE);
+        gt = t > gt ? t : gt;
+        gq = q > gq ? q : gq;
+    }
+    if ((lane & 15) == 0) {
+        sh_gm[0][wave * 4 + (lane >> 4)] = gt;
+        sh_gm[1][wave * 4 + (lane >> 4)] = gq;
+    }
+    if (threadIdx.x < 2) sh_n[threadIdx.x] = 0;
+    __syncthreads();
+    unsigned thr[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        // rank of group maximum (lane & 15) among the 16, equal values in index order
+        const unsigned mine = sh_gm[a][lane & 15];
+        int rank = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const unsigned other = sh_gm[a][i];
+            rank += (other > mine || (other == mine && i < (lane & 15))) ? 1 : 0;
+        }
+        const unsigned long long holder = __ballot(rank == top_m - 1);      // one lane in each group of 16
+        thr[a] = __shfl(mine, __ffsll((long long)holder) - 1, WAVE);
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const unsigned (&o)[EPT] = a ? oq : ot;
+        unsigned long long mask[EPT];
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            mask[j] = __ballot(o[j] != 0u && o[j] >= thr[a]);
+            cnt += __popcll(mask[j]);
+        }
+        int at = 0;
+        if (lane == 0) at = atomicAdd(&sh_n[a], cnt);
+        at = __shfl(at, 0, WAVE);
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const int pos = at + __popcll(mask[j] & ((1ull << lane) - 1ull));
+            if (((mask[j] >> lane) & 1ull) && pos < 64) {
+                const int id = base + threadIdx.x + j * TPB;
+                sh_cand[a][pos] = ((u64)o[j] << 32) | (u64)(0xFFFFFFFFu - (unsigned)id);
+            }
+            at += __popcll(mask[j]);
+        }
+    }
+    __syncthreads();
+    const int n_t = sh_n[0], n_q = sh_n[1];
+    u64* out_t = ws.part_top_t + pidx * MAXM;
+    u64* out_q = ws.part_top_q + pidx * MAXM;
+    if (wave < 2) {
+        const int n = wave ? n_q : n_t;
+        if (n <= 64) {
+            u64 c = lane < n ? sh_cand[wave][lane] : 0ull;
+            u64* out = wave ? out_q : out_t;
+            for (int round = 0; round < top_m; ++round) {
+                const u64 w = wave_max_u(c);                  // 0 when the slice ran out of ids
+                c = c == w ? 0ull : c;
+                if (lane == 0) out[round] = w;
+            }
+        }
+    }
+    if (n_t <= 64 && n_q <= 64) return;                        // block-uniform
+    // Fallback.  Every wave selects among its own 512 ids, without barriers: top_m rounds of a
+    // wave-wide maximum; among equal values the lowest id wins, which inside a wave is the lowest j,
+    // then the lowest lane.  Wave 0 then merges the 4 lists (at most 64 candidates: one per lane) on
+    // the full (value, id) keys.
+    const bool redo_t = n_t > 64, redo_q = n_q > 64;
     for (int round = 0; round < top_m; ++round) {
-        const u64 wt = select_round(ot, base, lane), wq = select_round(oq, base, lane);
+        const u64 wt = redo_t ? select_round(ot, base, lane) : 0ull, wq = redo_q ? select_round(oq, base, lane) : 0ull;
         if (lane == 0) {
             sh_top[0][wave][round] = wt;
             sh_top[1][wave][round] = wq;
@@ -225,15 +305,13 @@ row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     if (wave == 0) {
         const int w = lane / MAXM, r = lane % MAXM;          // TPB/WAVE * MAXM = 64 candidates
         u64 ct = r < top_m ? sh_top[0][w][r] : 0ull, cq = r < top_m ? sh_top[1][w][r] : 0ull;
-        u64* out_t = ws.part_top_t + pidx * MAXM;
-        u64* out_q = ws.part_top_q + pidx * MAXM;
         for (int round = 0; round < top_m; ++round) {
             const u64 wt = wave_max_u(ct), wq = wave_max_u(cq);   // 0 when the slice ran out of ids
             ct = ct == wt ? 0ull : ct;
             cq = cq == wq ? 0ull : cq;
             if (lane == 0) {
-                out_t[round] = wt;
-                out_q[round] = wq;
+                if (redo_t) out_t[round] = wt;
+                if (redo_q) out_q[round] = wq;
             }
         }
     }

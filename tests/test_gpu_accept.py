@@ -82,6 +82,25 @@ def test_top_m_limits_and_temperature(ctx):
     run_case(ctx, lg, q, toks, None, u, dict(tau=0.3, temperature=0.7), "temperature")
 
 
+def test_heavy_ties_in_the_top_m_selection(ctx):
+    """Rows quantised to a handful of levels: hundreds of equal values in every slice of 2048 ids, so the
+    per-slice threshold lets more ids through than the candidate list holds and the selection falls
+    back to rounds over all ids.  Equal values go to the lower id on both sides, so NormMatch (compared
+    exactly in run_case) and every decision not flagged as a near tie must agree."""
+    B, k, V = 6, 4, 5000
+    lg, q, toks, u = make_rows(21, B, k, V)
+    lg = np.round(lg).astype(np.float32)
+    dl = np.round(np.log(q.astype(np.float64)))
+    q = np.exp(dl - dl.max(-1, keepdims=True))
+    q = (q / q.sum(-1, keepdims=True)).astype(np.float32)
+    assert len(np.unique(lg[0, 0])) < 16 and len(np.unique(q[0, 0])) < 32
+    for top_m in (1, 8, 16):
+        run_case(ctx, lg, q, toks, None, u, dict(tau=0.2, lambda3=0.3, top_m=top_m), f"quantised rows, top_m={top_m}")
+    # ties in the target row only: the draft row keeps the candidate-list path
+    lg2, q2, toks2, u2 = make_rows(22, B, k, V)
+    run_case(ctx, np.round(lg2).astype(np.float32), q2, toks2, None, u2, dict(tau=0.2, lambda3=0.3), "quantised target rows")
+
+
 def test_degenerate_cases(ctx):
     lg, q, toks, u = make_rows(9, 8, 4, 4100)
     # everything accepted -> bonus token from the last row
