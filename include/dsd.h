@@ -116,7 +116,11 @@ int dsd_set_stream(dsd_ctx* ctx, void* hip_stream);
  *   [gf[d], Wlm[V x d]]                                        if has_head
  * every matrix stored [out_features x in_features], all in desc->dtype.  The library copies
  * (and for bf16 re-tiles) them into buffers of its own and synchronises before returning;
- * the caller may free its tensors afterwards. */
+ * the caller may free its tensors afterwards.
+ * The matrix-core path holds bf16 projection weights as fp16, which is exact for every bf16
+ * value of magnitude 2^-17 .. 65504 (smaller ones round to a multiple of 2^-24).
+ * Errors: DSD_EUNSUPPORTED if a bf16 projection weight is not finite or exceeds 65504 in
+ * magnitude; DSD_ENOMEM; DSD_EINVAL / DSD_ESHAPE for a bad description or tensor count. */
 int dsd_weights_create(dsd_ctx* ctx, const dsd_model_desc* desc, const void* const* tensors,
                        int n_tensors, dsd_weights** out);
 int dsd_weights_destroy(dsd_ctx* ctx, dsd_weights* w);
@@ -153,6 +157,9 @@ int dsd_kv_get_len(dsd_ctx* ctx, const dsd_kv* kv, int32_t* host_len, int B);
  * Row t of sequence b sits at position len[b] + depth[t]; its rotated key and its value are
  * written to cache slot len[b] + t of every layer; it attends to slots [0, len[b]) and to the
  * drafted rows its mask allows.  Lengths are not advanced: see dsd_kv_commit.
+ * Every sum is taken in a fixed order: the same call on the same inputs and cache contents
+ * writes the same bits.  On the matrix-core path activations enter the projections as fp16
+ * (11 significant bits or more); magnitudes beyond 65504 at those points saturate.
  * Errors: DSD_ESHAPE if B > max_batch, k > DSD_MAX_K or max(len) + k > max_slots. */
 int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
                      const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth,
