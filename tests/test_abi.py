@@ -32,3 +32,21 @@ def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(D.ModelDesc) == 12 * 4
     assert ctypes.sizeof(D.AcceptParams) == 5 * 8 + 2 * 4 + 8 + 2 * 4
     assert ctypes.sizeof(D.AcceptStats) == 4 * 8
+
+
+def test_bf16_values_convert_to_fp16_without_loss_in_the_stated_range():
+    """The matrix-core path stores bf16 projection weights as fp16 and calls that exact for magnitudes
+    2^-17 .. 65504; smaller ones may move by at most half of fp16's subnormal spacing (2^-25).  Checked
+    over every bf16 bit pattern."""
+    import numpy as np
+    bits = np.arange(1 << 16, dtype=np.uint32)
+    v = (bits << 16).view(np.float32)
+    fin = np.isfinite(v)
+    mag = np.abs(v)
+    with np.errstate(over="ignore"):
+        back = v.astype(np.float16).astype(np.float32)
+    exact = fin & ((mag == 0) | ((mag >= 2.0 ** -17) & (mag <= 65504.0)))
+    assert exact.sum() == 33 * 128 * 2 + 2          # exponents -17 .. 15, both signs, and the two zeros
+    np.testing.assert_array_equal(back[exact], v[exact])
+    small = fin & (mag < 2.0 ** -17)
+    assert np.abs(back[small].astype(np.float64) - v[small].astype(np.float64)).max() <= 2.0 ** -25

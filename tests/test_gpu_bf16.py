@@ -231,3 +231,24 @@ def test_repeated_runs_are_bit_identical_at_128_rows():
     for rep in range(1, 4):
         assert torch.equal(results[rep][0], results[0][0]) and torch.equal(results[rep][1], results[0][1]), f"run {rep} differs"
 
+
+def test_weights_beyond_the_fp16_range_are_refused():
+    """The matrix-core path keeps bf16 projection weights as fp16; a value it cannot hold (beyond 65504,
+    infinite, NaN) makes dsd_weights_create fail instead of saturating silently.  Tiny values are fine."""
+    cfg, m, w, K, V, hid, parent, lens = mini("range", B=1, k=2, lens=[8])
+    w = dict(w)
+
+    def bf16_bits(x):
+        return np.uint16(np.float32(x).view(np.uint32) >> 16)
+
+    for bad in (1.0e5, -7.0e4, np.inf, np.nan):
+        wb = dict(w)
+        wb["l1.wd"] = w["l1.wd"].copy()
+        wb["l1.wd"][3, 5] = bf16_bits(bad)
+        with pytest.raises(H.D.DsdError, match="65504"):
+            H.GpuStage(m, wb, 1, 16)
+    ok = dict(w)
+    ok["l0.wq"] = w["l0.wq"].copy()
+    ok["l0.wq"][0, :4] = [bf16_bits(65280.0), bf16_bits(-65280.0), bf16_bits(2.0 ** -20), bf16_bits(0.0)]
+    H.GpuStage(m, ok, 1, 16)
+
