@@ -109,10 +109,9 @@ struct GemmArgs {
     bf16_t* vc;           // this layer's V cache
     KvGeom g;
     const int32_t* len;
-    const int32_t* depth;
+    const float2* rope;   // [M][64] (cos, sin) of every row's rotation angles (rope_table_kernel)
     int k;
     int Hq;
-    float theta;
 };
 
 // column tiles a workgroup / unit owns
@@ -163,12 +162,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, const int (&til
             const int L = p.len[b];
             const int slot = L + t;
             if (head < p.Hq + p.g.Hkv) {
-                const double pos = (double)(L + (p.depth ? p.depth[t] : t));
-                const double inv = pow((double)p.theta, -2.0 * (double)e / (double)hd);
-                double sn, cs;
-                sincos(pos * inv, &sn, &cs);
-                const float r0 = lo * (float)cs - hi * (float)sn;
-                const float r1 = hi * (float)cs + lo * (float)sn;
+                const float2 cs = p.rope[m * 64 + e];
+                const float r0 = lo * cs.x - hi * cs.y;
+                const float r1 = hi * cs.x + lo * cs.y;
                 if (head < p.Hq) {
                     float* dst = p.q + ((size_t)m * p.Hq + head) * hd;
                     dst[e] = r0;

@@ -360,29 +360,19 @@ __global__ void __launch_bounds__(256) resid_reduce_kernel(float* __restrict__ x
 }
 
 // K slices of the q, k, v rows (part[s][M][heads*128]) -> their sum in slice order, RMSNorm scale,
-// rotary embedding, cache append.  Block (row, share): the heads are dealt out over gridDim.y
-// blocks; the row's 64 rotation angles are the same for every head, so each block works them out
-// once (fp64) into LDS, and its second wave adds up the row's sums of squares.
+// rotary embedding (cos, sin from the call's table), cache append.  Block (row, share): the heads are
+// dealt out over gridDim.y blocks; the first wave adds up the row's sums of squares.
 __global__ void __launch_bounds__(256) qkv_finish_kernel(const float* __restrict__ part, int n_part, int M,
                                                          const float* __restrict__ ssq, int n_ssq,
                                                          float* __restrict__ q, bf16_t* __restrict__ kc,
                                                          bf16_t* __restrict__ vc, KvGeom g,
-                                                         const int32_t* __restrict__ len,
-                                                         const int32_t* __restrict__ depth, int k, int Hq, int d,
-                                                         float eps, float theta) {
-    __shared__ float s_cs[64], s_sn[64], s_rstd;
+                                                         const int32_t* __restrict__ len, int k, int Hq, int d,
+                                                         float eps, const float2* __restrict__ rope) {
+    __shared__ float s_rstd;
     const int m = blockIdx.x, b = m / k, t = m % k;
-    const int L = len[b];
-    const int slot = L + t;
+    const int slot = len[b] + t;
     if (threadIdx.x < 64) {
-        const double pos = (double)(L + (depth ? depth[t] : t));
-        const double inv = pow((double)theta, -2.0 * (double)threadIdx.x / 128.0);
-        double sn, cs;
-        sincos(pos * inv, &sn, &cs);
-        s_cs[threadIdx.x] = (float)cs;
-        s_sn[threadIdx.x] = (float)sn;
-    } else if (threadIdx.x < 128) {
-        const int lane = threadIdx.x - 64;
+        const int lane = threadIdx.x;
         float sq = 0.f;
         for (int j = lane; j < n_ssq; j += 64) sq += ssq[j * 128 + m];
 #pragma unroll
@@ -421,7 +411,8 @@ __global__ void __launch_bounds__(256) qkv_finish_kernel(const float* __restrict
         lo *= rstd;
         hi *= rstd;
         if (head < Hq + g.Hkv) {
-            const float cs = s_cs[e], sn = s_sn[e];
+            const float2 rot = rope[m * 64 + e];
+            const float cs = rot.x, sn = rot.y;
             const float r0 = lo * cs - hi * sn, r1 = hi * cs + lo * sn;
             if (head < Hq) {
                 q[((size_t)m * Hq + head) * 128 + e] = r0;
@@ -568,15 +559,15 @@ int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, in
 // q, k, v = finish((x*gain)[M][K] Wqkv^T): norm scale, rotary, append.  x first takes the x_pending
 // slices waiting in part; the same buffer then carries the slices of the projection.
 int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, float* part, int x_pending, int M, int N,
-                   int K, float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len, const int32_t* depth,
-                   int k, int Hq, float eps, float theta, void* panel, float* ssq) {
+                   int K, float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len,
+                   int k, int Hq, float eps, const float2* rope, void* panel, float* ssq) {
     make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     int sp = 0;
     DSD_TRY(tiled_gemm_partial(ctx, Wt, M, N, K, panel, part, &sp));
     // four heads (256 rotation pairs) per block: one pass of the block's threads, all slice loads in flight at once
     const int heads = N / 128;
-    qkv_finish_kernel<<<dim3(M, (heads + 3) / 4), 256, 0, ctx->stream>>>(part, sp, M, ssq, K / 128, q, kc, vc, g, len, depth, k, Hq, K,
-                                                          eps, theta);
+    qkv_finish_kernel<<<dim3(M, (heads + 3) / 4), 256, 0, ctx->stream>>>(part, sp, M, ssq, K / 128, q, kc, vc, g, len, k, Hq, K,
+                                                          eps, rope);
     return DSD_OK;
 }
 

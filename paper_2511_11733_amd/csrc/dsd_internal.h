@@ -181,13 +181,15 @@ int persist_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const v
                          float* logits, int64_t logits_seq_stride);
 // weight-streaming GEMMs for 17..128 rows (dsd_gemm_tiled.hip)
 int tiled_supported(const dsd_model_desc* d);
+// rope[m][e] = (cos, sin) of (len[m/k] + depth[m%k]) * theta^(-2e/128), e < 64, worked out in fp64
+void rope_table_launch(dsd_ctx* ctx, float2* rope, const int32_t* len, const int32_t* depth, int M, int k, float theta);
 #define TILED_MAX_KSPLIT 16
 int tiled_row_tiles(int M);
 int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, float* part, int* n_part, int M, int N, int K, const void* panel);
 int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, int M, int N);
 int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, float* part, int x_pending, int M, int N,
-                   int K, float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len, const int32_t* depth,
-                   int k, int Hq, float eps, float theta, void* panel, float* ssq);
+                   int K, float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len,
+                   int k, int Hq, float eps, const float2* rope, void* panel, float* ssq);
 int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, const float* part, int x_pending,
                       void* panel_h, int M, int F, int K, float eps, void* panel, float* ssq);
 int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, const float* part, int x_pending,

@@ -434,6 +434,22 @@ __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ o
 }
 
 // ============================================================================ small kernels
+// (cos, sin) of every row's 64 rotation angles, once per call: the angles are the same in every layer
+// and for every head, and working them out in fp64 (pow + sincos) inside a GEMM epilogue kept one
+// wave of every workgroup busy for microseconds after its last weight had arrived.
+__global__ void __launch_bounds__(64) rope_table_kernel(float2* __restrict__ rope, const int32_t* __restrict__ len,
+                                                        const int32_t* __restrict__ depth, int k, float theta) {
+    const int m = blockIdx.x, b = m / k, t = m % k, e = threadIdx.x;
+    const double pos = (double)(len[b] + (depth ? depth[t] : t));
+    const double inv = pow((double)theta, -2.0 * (double)e / 128.0);
+    double sn, cs;
+    sincos(pos * inv, &sn, &cs);
+    rope[m * 64 + e] = make_float2((float)cs, (float)sn);
+}
+void rope_table_launch(dsd_ctx* ctx, float2* rope, const int32_t* len, const int32_t* depth, int M, int k, float theta) {
+    rope_table_kernel<<<M, 64, 0, ctx->stream>>>(rope, len, depth, k, theta);
+}
+
 __global__ void rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__ h, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) x[i] = bf16_to_f32(h[i]);
@@ -496,7 +512,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // tiled path: K slices of one GEMM's result (up to TILED_MAX_KSPLIT of them), and per-chunk sums of squares
     const size_t n_part = tiled ? (size_t)TILED_MAX_KSPLIT * M * std::max(d, n_qkv) : 0;
     const size_t n_ssq = (size_t)128 * (d / 128 + 1);
-    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + n_part * 4 +
+    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + n_part * 4 + (size_t)M * 64 * 8 +
                   128 * kmax * 4 + n_ssq * 4 +
                   (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
@@ -507,6 +523,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     float* h = ws.take<float>((size_t)M * F);
     float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
     float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
+    float2* rope = ws.take<float2>((size_t)M * 64);
     float* part = ws.take<float>(n_part);
     float* ssq = ws.take<float>(n_ssq);              // [d/128][128]: sums of squares of the rows, per chunk of 128 columns
     void* panel = ws.take<float>(64 * kmax);          // up to 128 rows of activations as fp16 in A-operand order
@@ -518,6 +535,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         ProfScope ps(ctx, DSD_KC_OTHER);
         if (hidden_in) rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
         else embed_rows_kernel<<<M, 256, 0, s>>>(x, (const bf16_t*)w->embed, draft_tokens, d, D.vocab);
+        rope_table_launch(ctx, rope, kv->len_dev, depth, M, k, D.rope_theta);
     }
 
     for (int l = 0; l < D.n_layers; ++l) {
@@ -529,13 +547,13 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.eps = D.rms_eps;
         // q, k, v = rmsnorm(x; g1) Wqkv^T, rotary, cache append
         a.Wt = (const uint4*)W.qkv_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)W.g1;
-        a.q = q; a.kc = kc; a.vc = vc; a.g = g; a.len = kv->len_dev; a.depth = depth; a.k = k; a.Hq = Hq;
-        a.theta = D.rope_theta;
+        a.q = q; a.kc = kc; a.vc = vc; a.g = g; a.len = kv->len_dev; a.k = k; a.Hq = Hq;
+        a.rope = rope;
         {
             ProfScope ps(ctx, DSD_KC_QKV);
             if (tiled) {
                 DSD_TRY(tiled_gemm_qkv(ctx, W.qkv_t, x, (const bf16_t*)W.g1, part, x_pending, M, n_qkv, d, q, kc, vc, g,
-                                       kv->len_dev, depth, k, Hq, D.rms_eps, D.rope_theta, panel, ssq));
+                                       kv->len_dev, k, Hq, D.rms_eps, rope, panel, ssq));
                 x_pending = 0;
             } else
                 DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));

@@ -44,7 +44,8 @@ struct PLayer {
 struct PArgs {
     const PLayer* layers;
     int L, M, B, k, d, qd, F, Hq, Hkv, G;
-    float eps, theta;
+    float eps;
+    const float2* rope;   // [M][64] (cos, sin), rope_table_launch
     const bf16_t* hidden_in;
     bf16_t* hidden_out;
     float *x, *q, *att, *h;
@@ -424,8 +425,7 @@ __global__ void __launch_bounds__(PT) stage_persist_kernel(PArgs p) {
         // q, k, v = rmsnorm(x; g1) Wqkv^T, rotary, cache append
         ga = GemmArgs();
         ga.KS = p.d / 32; ga.M = p.M; ga.x = p.x; ga.gain = ly.g1; ga.eps = p.eps;
-        ga.q = p.q; ga.kc = kc; ga.vc = vc; ga.g = p.g; ga.len = p.len; ga.depth = p.depth; ga.k = p.k; ga.Hq = p.Hq;
-        ga.theta = p.theta;
+        ga.q = p.q; ga.kc = kc; ga.vc = vc; ga.g = p.g; ga.len = p.len; ga.rope = p.rope; ga.k = p.k; ga.Hq = p.Hq;
         gemm_phase<2, A_F32_GAIN, EPI_QKV>(p, ga, (p.Hq + 2 * p.Hkv) * 4, fifo, it, lds_panel, lds_red, lds_ssq, parity, wg, wave, lane);
         target += 1u;
         stamp(p, nst);
@@ -562,7 +562,7 @@ int persist_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const v
     PArgs p = PArgs();
     p.layers = (const PLayer*)w->layer_table;
     p.L = D.n_layers; p.M = B * k; p.B = B; p.k = k; p.d = D.d_model; p.Hq = D.n_q_heads; p.Hkv = D.n_kv_heads;
-    p.G = p.Hq / p.Hkv; p.qd = p.Hq * D.head_dim; p.F = D.d_ffn; p.eps = D.rms_eps; p.theta = D.rope_theta;
+    p.G = p.Hq / p.Hkv; p.qd = p.Hq * D.head_dim; p.F = D.d_ffn; p.eps = D.rms_eps;
     p.n_wg = ctx->n_cu;
 
     int max_len = 0;
@@ -582,7 +582,7 @@ int persist_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const v
 
     const size_t M = p.M;
     const size_t nunit = (size_t)B * p.Hkv * p.n_runs * p.rows_pad;
-    size_t need = M * p.d * 4 + M * p.qd * 4 * 2 + M * p.F * 4 + nunit * 130 * 4 + 8 * 256;
+    size_t need = M * p.d * 4 + M * p.qd * 4 * 2 + M * p.F * 4 + nunit * 130 * 4 + M * 64 * 8 + 9 * 256;
     DSD_TRY(dsd_ws_reserve(ctx, need));
     WsBump ws{ctx->ws, 0};
     p.x = ws.take<float>(M * p.d);
@@ -591,6 +591,9 @@ int persist_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const v
     p.h = ws.take<float>(M * p.F);
     p.part_o = ws.take<float>(nunit * 128);
     p.part_ml = ws.take<float>(nunit * 2);
+    float2* rope = ws.take<float2>(M * 64);
+    p.rope = rope;
+    rope_table_launch(ctx, rope, kv->len_dev, depth, (int)M, k, D.rope_theta);
     p.hidden_in = (const bf16_t*)hidden_in;
     p.hidden_out = (bf16_t*)hidden_out;
     p.kc0 = (bf16_t*)kv->k; p.vc0 = (bf16_t*)kv->v; p.g = g;
