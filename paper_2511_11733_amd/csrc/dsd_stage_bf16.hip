@@ -478,7 +478,32 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const KvGeom& g = kv->geom;
     const int M = B * k, d = D.d_model, Hq = D.n_q_heads, Hkv = D.n_kv_heads, hd = D.head_dim, F = D.d_ffn;
     const int G = Hq / Hkv, qd = Hq * hd;
-    if (M > 128) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: B*k = %d rows exceed 128", M);
+    if (M > 128) {
+        // More rows than the GEMM tiles take.  Sequences are independent (own cache rows, own
+        // positions), so they go through in groups of up to 128 rows; every group streams the
+        // weights once more, which at this many rows per weight byte is no longer the only cost.
+        const int per = 128 / k;
+        const size_t seq_cache_bytes = (size_t)g.Hkv * g.head_elems * sizeof(bf16_t);
+        const int64_t lstride = logits_seq_stride ? logits_seq_stride : (int64_t)k * D.vocab;
+        for (int b0 = 0; b0 < B; b0 += per) {
+            const int nb = std::min(per, B - b0);
+            dsd_kv view;
+            view.desc = kv->desc;
+            view.geom = kv->geom;
+            view.k = (char*)kv->k + b0 * seq_cache_bytes;
+            view.v = (char*)kv->v + b0 * seq_cache_bytes;
+            view.len_dev = kv->len_dev + b0;
+            view.len_bound.assign(kv->len_bound.begin() + b0, kv->len_bound.begin() + b0 + nb);
+            view.last_k = kv->last_k;
+            view.cap = kv->cap;
+            const size_t row0 = (size_t)b0 * k;
+            DSD_TRY(mfma_stage_verify(ctx, w, &view, hidden_in ? (const bf16_t*)hidden_in + row0 * d : nullptr,
+                                      draft_tokens ? draft_tokens + row0 : nullptr, tree_mask, depth, nb, k,
+                                      hidden_out ? (bf16_t*)hidden_out + row0 * d : nullptr,
+                                      logits ? logits + b0 * lstride : nullptr, logits_seq_stride));
+        }
+        return DSD_OK;
+    }
     if (hidden_in && M <= 8 && w->layer_table && !ctx->no_persist) {
         const int rc = persist_stage_verify(ctx, w, kv, hidden_in, tree_mask, depth, B, k, hidden_out, logits, logits_seq_stride);
         if (rc != DSD_EUNSUPPORTED) return rc;      // else: one kernel per step

@@ -252,3 +252,10 @@ def test_weights_beyond_the_fp16_range_are_refused():
     ok["l0.wq"][0, :4] = [bf16_bits(65280.0), bf16_bits(-65280.0), bf16_bits(2.0 ** -20), bf16_bits(0.0)]
     H.GpuStage(m, ok, 1, 16)
 
+
+def test_more_than_128_rows_go_through_in_groups_of_sequences():
+    """B*k = 168 rows: the library takes the sequences in groups of up to 128 rows (here 16 + 5 sequences
+    of 8 rows); the result is checked against the oracle like any other shape."""
+    B, k = 21, 8
+    check(mini("m168", B=B, k=k, lens=[24 + 5 * (b % 7) for b in range(B)], head=True, V=4112, L=2))
+
