@@ -358,17 +358,30 @@ __global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowg
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             float mx = -INFINITY;
+            if (j0 + 32 <= L) {
+                // a step of committed keys only (all but the last one or two of a run): every key is
+                // visible to every row, no mask arithmetic
 #pragma unroll
-            for (int tl = 0; tl < 2; ++tl)
+                for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = j0 + tl * 16 + g * 4 + i;
-                    bool ok = key < L;
-                    if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
-                    const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
-                    s[tl][rt][i] = v;
-                    mx = fmaxf(mx, v);
-                }
+                    for (int i = 0; i < 4; ++i) {
+                        const float v = s[tl][rt][i] * p.scale_log2e;
+                        s[tl][rt][i] = v;
+                        mx = fmaxf(mx, v);
+                    }
+            } else {
+#pragma unroll
+                for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int key = j0 + tl * 16 + g * 4 + i;
+                        bool ok = key < L;
+                        if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
+                        const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
+                        s[tl][rt][i] = v;
+                        mx = fmaxf(mx, v);
+                    }
+            }
             mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
             mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
             const float mnew = fmaxf(mrow[rt], mx);
