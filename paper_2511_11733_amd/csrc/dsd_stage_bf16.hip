@@ -553,21 +553,27 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // tiled path: K slices of one GEMM's result (up to TILED_MAX_KSPLIT of them), and per-chunk sums of squares
     const size_t n_part = tiled ? (size_t)TILED_MAX_KSPLIT * M * std::max(d, n_qkv) : 0;
     const size_t n_ssq = (size_t)128 * (d / 128 + 1);
-    size_t need = (size_t)M * d * 4 + (size_t)M * qd * 4 * 2 + (size_t)M * F * 4 + n_part * 4 + (size_t)M * 64 * 8 +
-                  128 * kmax * 4 + n_ssq * 4 +
-                  (size_t)units * n_runs * rows_pad * (128 + 2) * 4 + 8 * 256;
-    DSD_TRY(dsd_ws_reserve(ctx, need));
+    // the workspace is carved twice with the same code: once to add up the sizes, once for the pointers
+    float *x, *q, *att, *h, *part_o, *part_ml, *part, *ssq;
+    float2* rope;
+    void* panel;
+    auto carve = [&](WsBump& ws) {
+        x = ws.take<float>((size_t)M * d);
+        q = ws.take<float>((size_t)M * qd);
+        att = ws.take<float>(tiled ? 0 : (size_t)M * qd);          // from 17 rows on the combine writes the O panel
+        h = ws.take<float>((size_t)M * F);                         // from 17 rows on: the down projection's panel
+        part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
+        part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
+        rope = ws.take<float2>((size_t)M * 64);
+        part = ws.take<float>(n_part);
+        ssq = ws.take<float>(n_ssq);                               // [d/128][128]: sums of squares of the rows, per chunk of 128 columns
+        panel = ws.take<float>(tiled ? 64 * kmax : 0);             // up to 128 rows of activations as fp16 in A-operand order
+    };
+    WsBump sizing{nullptr, 0};
+    carve(sizing);
+    DSD_TRY(dsd_ws_reserve(ctx, sizing.off));
     WsBump ws{ctx->ws, 0};
-    float* x = ws.take<float>((size_t)M * d);
-    float* q = ws.take<float>((size_t)M * qd);
-    float* att = ws.take<float>((size_t)M * qd);
-    float* h = ws.take<float>((size_t)M * F);
-    float* part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
-    float* part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
-    float2* rope = ws.take<float2>((size_t)M * 64);
-    float* part = ws.take<float>(n_part);
-    float* ssq = ws.take<float>(n_ssq);              // [d/128][128]: sums of squares of the rows, per chunk of 128 columns
-    void* panel = ws.take<float>(64 * kmax);          // up to 128 rows of activations as fp16 in A-operand order
+    carve(ws);
     void* panel_h = h;                                // SiLU*up goes straight into the operand panel of the down projection
     hipStream_t s = ctx->stream;
     int x_pending = 0;                                // K slices in `part` that the residual stream has not taken yet
