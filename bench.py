@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--tree-mode", default="longest", choices=["longest", "first", "lossless"],
                     help="dsd_accept's tree rule (final-stage workloads); lossless = recursive rejection over siblings")
     ap.add_argument("--temperature", type=float, default=1.0, help="dsd_accept's temperature; 0 = greedy verification")
+    ap.add_argument("--batch", type=int, default=0, help="row-count sweeps: the named workload with another batch size")
+    ap.add_argument("--draft-len", type=int, default=0, help="row-count sweeps: another number of drafted rows (chains only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a known-size reference for HBM byte counters)")
@@ -102,6 +104,11 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.config]
+    if args.batch or args.draft_len:
+        # not a benchmark line of its own: the same model, context and recipe at another row count
+        assert not (cfg.tree and args.draft_len), "a tree workload keeps its own number of nodes"
+        nb, nk = args.batch or cfg.B, args.draft_len or cfg.k
+        cfg = W.scaled(cfg, name=f"{cfg.name} at B={nb} k={nk}", B=nb, k=nk)
     m = cfg.model
     assert m.dtype == "bf16", "bench workloads are the bf16 configurations"
     dev = "cuda:0"
@@ -211,21 +218,21 @@ def main():
     total_bytes, per_layer, head_bytes, accept_bytes = algorithmic_bytes(cfg)
     kern = {kc: (t / n if n else 0.0) for kc, (t, n) in prof.items()}
     if kern.get("stage", 0.0) > 0.0:
-        # at most 16 rows: the whole block of layers is one persistent kernel
+        # the opt-in persistent form (at most 8 rows): the whole block of layers is one kernel
         dominant, dom_bytes = "stage", total_bytes
         dom_name = "stage_persist_kernel (all layers of the block: QKV, attention, O-proj, gate/up, down)"
         dom_match = "stage_persist_kernel"
     else:
         dominant, dom_bytes = "gateup", per_layer["gateup"]
         M = B * k
-        if M <= 16:
-            dom_name = "gemm_skinny_kernel<1, 2, A_F32_GAIN, EPI_SWIGLU, 16> (RMSNorm + gate/up GEMM + SiLU*up, one launch)"
+        if M <= 10:      # the library's switch-over between its two GEMM paths
+            dom_name = "gemm_skinny_kernel<1, 2, A_F32_GAIN, EPI_SWIGLU, 4> (RMSNorm + gate/up GEMM + SiLU*up, one launch)"
             dom_match = "gemm_skinny_kernel<1, 2, 0, 1"
         else:
             # the step is the activation pre-pass (a few us) plus the weight-streaming GEMM; the
             # library picks the GEMM's geometry from the row count and the matrix width
             mt = (M + 15) // 16
-            mt = 6 if mt == 5 else (8 if mt == 7 else mt)
+            mt = {1: 2, 5: 6, 7: 8}.get(mt, mt)
             twc = 8 if (mt <= 4 and -(-(2 * (m.F // 16)) // 16) * 5 >= 256 * 4) else 4
             dom_name = (f"act_panel_kernel + gemm_tiled_kernel<{mt}, {twc}, TE_SWIGLU> (RMSNorm + gate/up GEMM + SiLU*up; "
                         "the time is that of both launches)")

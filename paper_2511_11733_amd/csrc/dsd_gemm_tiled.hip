@@ -1,8 +1,8 @@
-// Weight-streaming GEMM for 17..128 rows (B*k of the batched verification pass, section 2.1).
+// Weight-streaming GEMM for 11..128 rows (B*k of the batched verification pass, section 2.1).
 //
 // With this many rows the pass is still bound by streaming the weights once, but the activation
 // operand is no longer negligible: every weight fragment meets MT activation fragments (one fp16
-// plane of MT 16-row tiles; two planes, as the kernels for up to 16 rows use, would make the matrix
+// plane of MT 16-row tiles; two planes, as the kernels for up to 10 rows use, would make the matrix
 // cores the bound at 128 rows).  So the activations are shared through LDS and only the weights
 // come straight from HBM into registers:
 //   * a workgroup of 4 (or 8) computing waves owns 128 (256) output columns, each wave two
@@ -450,14 +450,14 @@ static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, 
     const int mt = (p.M + 15) / 16;
     if (twc == 8) {
         switch (mt) {
-            case 2: return tiled_launch<2, 8, EPI>(s, p, n_blocks, ksplit);
+            case 1: case 2: return tiled_launch<2, 8, EPI>(s, p, n_blocks, ksplit);
             case 3: return tiled_launch<3, 8, EPI>(s, p, n_blocks, ksplit);
             case 4: return tiled_launch<4, 8, EPI>(s, p, n_blocks, ksplit);
             default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: 8 computing waves with %d rows", p.M);
         }
     }
     switch (mt) {
-        case 2: return tiled_launch<2, 4, EPI>(s, p, n_blocks, ksplit);
+        case 1: case 2: return tiled_launch<2, 4, EPI>(s, p, n_blocks, ksplit);
         case 3: return tiled_launch<3, 4, EPI>(s, p, n_blocks, ksplit);
         case 4: return tiled_launch<4, 4, EPI>(s, p, n_blocks, ksplit);
         case 5: case 6: return tiled_launch<6, 4, EPI>(s, p, n_blocks, ksplit);
@@ -517,7 +517,7 @@ int tiled_supported(const dsd_model_desc* d) {
 
 static int mt_of(int M) {
     const int mt = (M + 15) / 16;
-    return mt == 5 ? 6 : (mt == 7 ? 8 : mt);      // tile counts the kernel is built for
+    return mt == 1 ? 2 : (mt == 5 ? 6 : (mt == 7 ? 8 : mt));      // tile counts the kernel is built for
 }
 int tiled_row_tiles(int M) { return mt_of(M); }
 

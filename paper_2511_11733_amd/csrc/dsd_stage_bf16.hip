@@ -11,9 +11,9 @@
 //     KV-cache append, SiLU*up, residual add, or fp32 logits;
 //   * RMSNorm never makes a pass of its own: x*g is applied while the A operand is loaded, the
 //     sum of squares is accumulated from those same loads, and 1/rms scales the output rows;
-//   * up to 16 rows, activations enter the matrix cores as a sum of two fp16 terms (hi + lo, two
+//   * up to 10 rows, activations enter the matrix cores as a sum of two fp16 terms (hi + lo, two
 //     MFMAs per weight fragment, ~22 significant bits; the extra MFMA work is free while the pass is
-//     bandwidth bound); from 17 rows on as one fp16 term (11 bits, see dsd_gemm_tiled.hip).  Queries
+//     bandwidth bound); from 11 rows on as one fp16 term (11 bits, see dsd_gemm_tiled.hip).  Queries
 //     and attention weights meet the bf16 cache as hi + lo bf16;
 //   * attention computes S^T = K Q^T so that the scores a lane holds are exactly the P^T operand
 //     of O^T = V^T P^T; V is cached transposed for that product (see KvGeom).
@@ -529,7 +529,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // a wave takes at most 4 row tiles (registers); more rows are split into row groups
     const int n_rg = (n_rt + 3) / 4;
     const int RT = (n_rt + n_rg - 1) / n_rg;
-    const bool tiled = M > 16 && tiled_supported(&D) && !getenv("DSD_NO_TILED");
+    // Measured at the 8B shape, context 2048: one workgroup per column tile converting the activations
+    // itself (gemm_skinny_kernel) wins up to 10 rows (0.87 ms at 5 rows against 0.92), the panel path
+    // from 11 rows on (0.95 against 0.99 ms at 12 rows, 0.97 against 1.12 at 16).
+    const bool tiled = M >= TILED_MIN_ROWS && tiled_supported(&D) && !getenv("DSD_NO_TILED");
 
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
@@ -560,8 +563,9 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     auto carve = [&](WsBump& ws) {
         x = ws.take<float>((size_t)M * d);
         q = ws.take<float>((size_t)M * qd);
-        att = ws.take<float>(tiled ? 0 : (size_t)M * qd);          // from 17 rows on the combine writes the O panel
-        h = ws.take<float>((size_t)M * F);                         // from 17 rows on: the down projection's panel
+        att = ws.take<float>(tiled ? 0 : (size_t)M * qd);          // on the tiled path the combine writes the O panel
+        // on the tiled path: the down projection's panel, 16 * row tiles rows of fp16
+        h = ws.take<float>(tiled ? std::max((size_t)M * F, (size_t)8 * tiled_row_tiles(M) * F) : (size_t)M * F);
         part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
         part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
         rope = ws.take<float2>((size_t)M * 64);
@@ -621,7 +625,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         }
         {
         ProfScope ps(ctx, DSD_KC_ATTN_COMBINE);
-        // more than 16 rows: straight into the operand panel of the output projection
+        // tiled path: straight into the operand panel of the output projection
         attn_combine_kernel<<<dim3(rows, Hkv, B), 128, 0, s>>>(att, part_o, part_ml, n_runs, t.rows_pad, k, G, Hq, Hkv,
                                                                tiled ? (unsigned short*)panel : nullptr,
                                                                tiled ? tiled_row_tiles(M) : 0);

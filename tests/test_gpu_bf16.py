@@ -175,7 +175,7 @@ def test_stage_replays_from_a_hip_graph():
     """Once the workspace has its size the call issues only kernels on the context's stream, so a caller
     may capture it; every replay (with eager work and synchronisations in between) must reproduce the
     eager result bit for bit: every sum on the path is taken in a fixed order (K slices of the GEMMs
-    for more than 16 rows land in buffers of their own and are added up slice by slice), so two runs
+    from 11 rows on land in buffers of their own and are added up slice by slice), so two runs
     on the same inputs may not differ at all."""
     for name, B, k in (("graph_m5", 1, 5), ("graph_m40", 5, 8)):
         cfg, m, w, K, V, hid, parent, lens = mini(name, B=B, k=k, lens=[70 + 9 * b for b in range(B)], head=True,
