@@ -259,3 +259,19 @@ def test_more_than_128_rows_go_through_in_groups_of_sequences():
     B, k = 21, 8
     check(mini("m168", B=B, k=k, lens=[24 + 5 * (b % 7) for b in range(B)], head=True, V=4112, L=2))
 
+
+@pytest.mark.parametrize("B,k", [(1, 5), (6, 8)])
+def test_outlier_channels_in_the_residual_stream(B, k):
+    """Hidden states with a few channels hundreds of times larger than the rest (the massive activations
+    of trained decoders): the fp32 residual stream carries them, the fp16 GEMM operands keep their
+    relative precision whatever the magnitude, and nothing comes near the fp16 range.  Both GEMM paths
+    (5 rows, 48 rows)."""
+    cfg, m, w, K, V, hid, parent, lens = mini(f"outliers_{B}x{k}", B=B, k=k, lens=[60 + 11 * b for b in range(B)],
+                                              head=True, V=4112, L=2)
+    f = O.widen(hid).astype(np.float64)
+    f[..., 7] *= 300.0
+    f[..., 301] *= -150.0
+    f[:, 0, 100] = 800.0
+    hid = (f.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)      # truncation to bf16 is good enough for an input
+    check((cfg, m, w, K, V, hid, parent, lens))
+
