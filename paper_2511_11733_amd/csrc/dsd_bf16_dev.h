@@ -98,6 +98,7 @@ struct GemmArgs {
     // epilogues
     float* xout;          // EPI_RESID: [M][N] fp32, updated in place
     int N;
+    bf16_t* hidden_out;   // EPI_RESID, optional: the updated rows also go out in the model dtype (last layer of a block)
     float* hout;          // EPI_SWIGLU: [M][F]
     int up_tile_off;      // EPI_SWIGLU: F/16
     float* logits;        // EPI_LOGITS
@@ -141,8 +142,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, const int (&til
         if (EPI == EPI_RESID) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                float* dst = p.xout + (size_t)m * p.N + tile[nt] * 16 + c;
-                *dst += o[nt][i];
+                const size_t at = (size_t)m * p.N + tile[nt] * 16 + c;
+                const float r = p.xout[at] + o[nt][i];
+                p.xout[at] = r;
+                if (p.hidden_out) p.hidden_out[at] = f32_to_bf16(r);
             }
         } else if (EPI == EPI_LOGITS) {
 #pragma unroll

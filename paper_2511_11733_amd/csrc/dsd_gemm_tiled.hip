@@ -346,9 +346,10 @@ __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ pane
     panel[((size_t)ks * MT + mt) * 64 + lane] = __builtin_bit_cast(uint4, pack8h(v));
 }
 
-// x[M][K] += sum of n_part K slices, in order (the residual update when no panel kernel follows)
+// x[M][K] += sum of n_part K slices, in order (the residual update when no panel kernel follows);
+// the block's output rows in the model dtype go out from here too
 __global__ void __launch_bounds__(256) resid_reduce_kernel(float* __restrict__ x, const float* __restrict__ part,
-                                                           int n_part, size_t n) {
+                                                           int n_part, size_t n, bf16_t* __restrict__ out) {
     const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= n) return;
     float4 v = *(const float4*)(x + i);
@@ -357,6 +358,12 @@ __global__ void __launch_bounds__(256) resid_reduce_kernel(float* __restrict__ x
         v.x += p4.x; v.y += p4.y; v.z += p4.z; v.w += p4.w;
     }
     *(float4*)(x + i) = v;
+    if (out) {
+        out[i] = f32_to_bf16(v.x);
+        out[i + 1] = f32_to_bf16(v.y);
+        out[i + 2] = f32_to_bf16(v.z);
+        out[i + 3] = f32_to_bf16(v.w);
+    }
 }
 
 // K slices of the q, k, v rows (part[s][M][heads*128]) -> their sum in slice order, RMSNorm scale,
@@ -550,9 +557,9 @@ int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, float* part, int* n_part, int
 }
 
 // x += the slices waiting in part
-int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, int M, int N) {
+int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, int M, int N, void* hidden_out) {
     const size_t n = (size_t)M * N;
-    resid_reduce_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, ctx->stream>>>(x, part, n_part, n);
+    resid_reduce_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, ctx->stream>>>(x, part, n_part, n, (bf16_t*)hidden_out);
     return DSD_OK;
 }
 

@@ -187,7 +187,7 @@ void rope_table_launch(dsd_ctx* ctx, float2* rope, const int32_t* len, const int
 #define TILED_MAX_KSPLIT 16
 int tiled_row_tiles(int M);
 int tiled_gemm_resid(dsd_ctx* ctx, const void* Wt, float* part, int* n_part, int M, int N, int K, const void* panel);
-int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, int M, int N);
+int tiled_resid_reduce(dsd_ctx* ctx, float* x, const float* part, int n_part, int M, int N, void* hidden_out);
 int tiled_gemm_qkv(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain, float* part, int x_pending, int M, int N,
                    int K, float* q, bf16_t* kc, bf16_t* vc, const KvGeom& g, const int32_t* len,
                    int k, int Hq, float eps, const float2* rope, void* panel, float* ssq);

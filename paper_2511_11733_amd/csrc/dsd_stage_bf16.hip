@@ -452,35 +452,51 @@ __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ o
 // ============================================================================ small kernels
 // (cos, sin) of every row's 64 rotation angles, once per call: the angles are the same in every layer
 // and for every head, and working them out in fp64 (pow + sincos) inside a GEMM epilogue kept one
-// wave of every workgroup busy for microseconds after its last weight had arrived.
-__global__ void __launch_bounds__(64) rope_table_kernel(float2* __restrict__ rope, const int32_t* __restrict__ len,
-                                                        const int32_t* __restrict__ depth, int k, float theta) {
-    const int m = blockIdx.x, b = m / k, t = m % k, e = threadIdx.x;
-    const double pos = (double)(len[b] + (depth ? depth[t] : t));
-    const double inv = pow((double)theta, -2.0 * (double)e / 128.0);
+// wave of every workgroup busy for microseconds after its last weight had arrived.  64 threads per row.
+struct RopeArgs {
+    float2* rope;            // [M][64]
+    const int32_t* len;
+    const int32_t* depth;    // NULL = chain
+    int k, M;
+    float theta;
+};
+__device__ __forceinline__ void rope_rows(const RopeArgs& r, int m, int e) {
+    if (m >= r.M) return;
+    const int b = m / r.k, t = m % r.k;
+    const double pos = (double)(r.len[b] + (r.depth ? r.depth[t] : t));
+    const double inv = pow((double)r.theta, -2.0 * (double)e / 128.0);
     double sn, cs;
     sincos(pos * inv, &sn, &cs);
-    rope[m * 64 + e] = make_float2((float)cs, (float)sn);
+    r.rope[m * 64 + e] = make_float2((float)cs, (float)sn);
 }
+__global__ void __launch_bounds__(64) rope_table_kernel(RopeArgs r) { rope_rows(r, blockIdx.x, threadIdx.x); }
 void rope_table_launch(dsd_ctx* ctx, float2* rope, const int32_t* len, const int32_t* depth, int M, int k, float theta) {
-    rope_table_kernel<<<M, 64, 0, ctx->stream>>>(rope, len, depth, k, theta);
+    const RopeArgs r = {rope, len, depth, k, M, theta};
+    rope_table_kernel<<<M, 64, 0, ctx->stream>>>(r);
 }
 
-__global__ void rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__ h, size_t n) {
+// The call's first launch: the input rows into the fp32 residual stream (blocks below n_row_blocks) and
+// the rotation table (the blocks after them, 4 rows each).
+__global__ void __launch_bounds__(256) rows_in_kernel(float* __restrict__ x, const bf16_t* __restrict__ h, size_t n,
+                                                      int n_row_blocks, RopeArgs r) {
+    if ((int)blockIdx.x >= n_row_blocks) {
+        rope_rows(r, ((int)blockIdx.x - n_row_blocks) * 4 + (threadIdx.x >> 6), threadIdx.x & 63);
+        return;
+    }
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) x[i] = bf16_to_f32(h[i]);
 }
-// first node of the pipeline: x[m,:] = E[token[m],:]  (ids clamped into the table)
-__global__ void embed_rows_kernel(float* __restrict__ x, const bf16_t* __restrict__ embed, const int32_t* __restrict__ tokens,
-                                  int d, int vocab) {
+// first node of the pipeline: x[m,:] = E[token[m],:]  (ids clamped into the table); blocks M .. do the table
+__global__ void __launch_bounds__(256) embed_rows_kernel(float* __restrict__ x, const bf16_t* __restrict__ embed,
+                                                         const int32_t* __restrict__ tokens, int d, int vocab, RopeArgs r) {
     const int m = blockIdx.x;
+    if (m >= r.M) {
+        rope_rows(r, (m - r.M) * 4 + (threadIdx.x >> 6), threadIdx.x & 63);
+        return;
+    }
     int t = tokens[m];
     t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
     for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = bf16_to_f32(embed[(size_t)t * d + i]);
-}
-__global__ void rows_out_kernel(bf16_t* __restrict__ h, const float* __restrict__ x, size_t n) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) h[i] = f32_to_bf16(x[i]);
 }
 
 // ============================================================================ orchestration
@@ -584,9 +600,12 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const size_t nx = (size_t)M * d;
     {
         ProfScope ps(ctx, DSD_KC_OTHER);
-        if (hidden_in) rows_in_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx);
-        else embed_rows_kernel<<<M, 256, 0, s>>>(x, (const bf16_t*)w->embed, draft_tokens, d, D.vocab);
-        rope_table_launch(ctx, rope, kv->len_dev, depth, M, k, D.rope_theta);
+        const RopeArgs ra = {rope, kv->len_dev, depth, k, M, D.rope_theta};
+        const int n_row_blocks = (int)((nx + 255) / 256), n_rope_blocks = (M + 3) / 4;
+        if (hidden_in)
+            rows_in_kernel<<<n_row_blocks + n_rope_blocks, 256, 0, s>>>(x, (const bf16_t*)hidden_in, nx, n_row_blocks, ra);
+        else
+            embed_rows_kernel<<<M + n_rope_blocks, 256, 0, s>>>(x, (const bf16_t*)w->embed, draft_tokens, d, D.vocab, ra);
     }
 
     for (int l = 0; l < D.n_layers; ++l) {
@@ -653,19 +672,19 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         // x += h Wd^T
         a = GemmArgs();
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
+        if (l == D.n_layers - 1) a.hidden_out = (bf16_t*)hidden_out;     // the block's output leaves with the last residual update
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
             if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, part, &x_pending, M, d, F, panel_h));
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
         }
     }
-    if (hidden_out) {
+    // the block's output rows: up to 10 rows the last down projection's epilogue has written them; on the
+    // panel path they leave with the sum of that projection's K slices
+    if (hidden_out && tiled) {
         ProfScope ps(ctx, DSD_KC_OTHER);
-        if (x_pending) {
-            DSD_TRY(tiled_resid_reduce(ctx, x, part, x_pending, M, d));
-            x_pending = 0;
-        }
-        rows_out_kernel<<<(unsigned)((nx + 255) / 256), 256, 0, s>>>((bf16_t*)hidden_out, x, nx);
+        DSD_TRY(tiled_resid_reduce(ctx, x, part, x_pending, M, d, hidden_out));
+        x_pending = 0;
     }
     if (logits) {
         GemmArgs a = GemmArgs();
