@@ -259,7 +259,12 @@ static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
 // to hide memory latency and no barrier.  The caches are stored in that operand order, so a step is
 // two contiguous 8 KiB pieces.  Stage layout: 16 fragments of 1 KiB (lane l at 16*l): K tile 0
 // features 0..31, 32..63, 64..95, 96..127, K tile 1 likewise, then V features 16h..16h+15.
-// blockIdx.x = (group of blockDim.x/64 runs) * n_rowgroups + rowgroup.
+// With several row groups (more than RT*16 query rows per kv head, e.g. a 32-node tree) the waves
+// that walk the same run for different row groups sit in the same workgroup whenever the workgroup
+// size allows, so that the run's K and V come from HBM once and from the compute unit's caches the
+// second time (spread over workgroups they land on different XCDs, each with an L2 of its own):
+// wave w = (run in the workgroup) * n_rowgroups + rowgroup.  Otherwise blockIdx.x = (group of
+// blockDim.x/64 runs) * n_rowgroups + rowgroup.
 #define ATT_STAGE_BYTES 16384
 
 __device__ __forceinline__ void attn_fetch(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int j0,
@@ -277,8 +282,10 @@ __global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowg
     extern __shared__ uint4 att_lds[];                // per wave: 2 stages of ATT_STAGE_BYTES
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int rg = blockIdx.x % n_rowgroups;
-    const int run = (blockIdx.x / n_rowgroups) * (blockDim.x >> 6) + wave, hk = blockIdx.y, b = blockIdx.z;
+    const int wpw = blockDim.x >> 6, hk = blockIdx.y, b = blockIdx.z;
+    const bool together = wpw % n_rowgroups == 0;
+    const int rg = together ? wave % n_rowgroups : blockIdx.x % n_rowgroups;
+    const int run = together ? blockIdx.x * (wpw / n_rowgroups) + wave / n_rowgroups : (blockIdx.x / n_rowgroups) * wpw + wave;
     if (run >= p.n_runs) return;
     const int row0 = rg * RT * 16;
     const int L = p.len[b];
@@ -435,7 +442,11 @@ static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int waves_per
         DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         raised = true;
     }
-    kern<<<dim3(((t.n_runs + waves_per_wg - 1) / waves_per_wg) * n_rg, Hkv, B), waves_per_wg * 64, lds, s>>>(t, n_rg);
+    // same test as in the kernel: row groups of a run share a workgroup when they fit evenly
+    const int runs_per_wg = waves_per_wg % n_rg == 0 ? waves_per_wg / n_rg : waves_per_wg;
+    const int n_wg = waves_per_wg % n_rg == 0 ? (t.n_runs + runs_per_wg - 1) / runs_per_wg
+                                              : ((t.n_runs + waves_per_wg - 1) / waves_per_wg) * n_rg;
+    kern<<<dim3(n_wg, Hkv, B), waves_per_wg * 64, lds, s>>>(t, n_rg);
     return DSD_OK;
 }
 
