@@ -350,6 +350,10 @@ __device__ __forceinline__ void attn_run(const AttnArgs& p, int b, int hk, int r
 // With `panel` the result goes out as fp16 in the A-operand order of the tiled GEMM for panel_mt
 // row tiles instead (element (row m, column kk) of entry ((kk/32)*MT + m/16)*64 + m%16 + 16*((kk/8)%4),
 // halfword kk%8), ready for the output projection.
+// NORM16: the runs' partial outputs come normalised (O_run / l_run) and as fp16 (attn_stream_kernel
+// writes them so: half the bytes of the largest intermediate of the attention, and a bounded range);
+// the weight of a run is then 2^(m_run - M) * l_run.
+template <bool NORM16 = false>
 __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const float* __restrict__ part_o,
                                                  const float* __restrict__ part_ml, int n_runs, int rows_pad, int k,
                                                  int G, int Hq, int Hkv, int r, int hk, int b, float* wgt, float* red,
@@ -373,9 +377,11 @@ __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const 
     if (on)
         for (int s = e; s < n_runs; s += 128) {
             const float m = wgt[s];
-            const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);
+            float w = (m == -INFINITY) ? 0.f : exp2f(m - M);
+            const float wl = w * part_ml[((u0 + s) * rows_pad + r) * 2 + 1];
+            if (NORM16) w = wl;
             wgt[s] = w;
-            den += w * part_ml[((u0 + s) * rows_pad + r) * 2 + 1];
+            den += wl;
         }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o, WAVE);
@@ -384,10 +390,16 @@ __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const 
     if (on) {
         den = red[2] + red[3];
         float num = 0.f;
-        const float* po = part_o + (u0 * rows_pad + r) * 128 + e;
         const size_t stride = (size_t)rows_pad * 128;
+        if (NORM16) {
+            const _Float16* po = (const _Float16*)part_o + (u0 * rows_pad + r) * 128 + e;
 #pragma unroll 8
-        for (int s = 0; s < n_runs; ++s) num += wgt[s] * po[s * stride];
+            for (int s = 0; s < n_runs; ++s) num += wgt[s] * (float)po[s * stride];
+        } else {
+            const float* po = part_o + (u0 * rows_pad + r) * 128 + e;
+#pragma unroll 8
+            for (int s = 0; s < n_runs; ++s) num += wgt[s] * po[s * stride];
+        }
         const int t = r / G, hq = hk * G + r % G;
         if (panel) {
             const int m = b * k + t, kk = hq * 128 + e;

@@ -426,8 +426,15 @@ __global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowg
             p.part_ml[(unit + r) * 2] = mrow[rt];
             p.part_ml[(unit + r) * 2 + 1] = l;
         }
+        // the run's output goes out normalised (a weighted mean of value rows: bounded by the values
+        // themselves) and as fp16; (max, sum) stay fp32 and carry the run's weight
+        const float inv_l = l > 0.f ? 1.0f / l : 0.f;
+        unsigned short* po = (unsigned short*)p.part_o + (unit + r) * 128 + g * 4;
 #pragma unroll
-        for (int h = 0; h < 8; ++h) *(f32x4*)(p.part_o + (unit + r) * 128 + h * 16 + g * 4) = o[h][rt];
+        for (int h = 0; h < 8; ++h) {
+            const f32x4 v = o[h][rt] * inv_l;
+            *(uint2*)(po + h * 16) = make_uint2(pack_f16(v[0], v[1]), pack_f16(v[2], v[3]));
+        }
     }
 }
 
@@ -456,8 +463,8 @@ __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ o
                                                           unsigned short* __restrict__ panel, int panel_mt) {
     __shared__ float wgt[MAX_RUNS];
     __shared__ float red[4];
-    attn_combine_row(out, part_o, part_ml, n_runs, rows_pad, k, G, Hq, Hkv, blockIdx.x, blockIdx.y, blockIdx.z, wgt, red,
-                     panel, panel_mt);
+    attn_combine_row<true>(out, part_o, part_ml, n_runs, rows_pad, k, G, Hq, Hkv, blockIdx.x, blockIdx.y, blockIdx.z, wgt,
+                           red, panel, panel_mt);
 }
 
 // ============================================================================ small kernels
@@ -593,7 +600,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         att = ws.take<float>(tiled ? 0 : (size_t)M * qd);          // on the tiled path the combine writes the O panel
         // on the tiled path: the down projection's panel, 16 * row tiles rows of fp16
         h = ws.take<float>(tiled ? std::max((size_t)M * F, (size_t)8 * tiled_row_tiles(M) * F) : (size_t)M * F);
-        part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 128);
+        part_o = ws.take<float>((size_t)units * n_runs * rows_pad * 64);     // fp16 [unit][run][row][128]
         part_ml = ws.take<float>((size_t)units * n_runs * rows_pad * 2);
         rope = ws.take<float2>((size_t)M * 64);
         part = ws.take<float>(n_part);
