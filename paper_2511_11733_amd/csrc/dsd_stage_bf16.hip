@@ -559,7 +559,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         DSD_FAIL(DSD_EINVAL, "bf16 path: neither hidden_in nor (embedding table, draft_tokens)");
     const int rows = k * G;
     const int n_rt = (rows + 15) / 16;       // 16-row tiles of query rows per kv head
-    if (n_rt > 8) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 128", rows);
+    if (n_rt > 32) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 512", rows);
     // a wave takes at most 4 row tiles (registers); more rows are split into row groups
     const int n_rg = (n_rt + 3) / 4;
     const int RT = (n_rt + n_rg - 1) / n_rg;

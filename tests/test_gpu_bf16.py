@@ -83,6 +83,13 @@ def test_max_rows_tree_32_nodes():
     check(mini("mini_m128", B=4, k=32, lens=[150, 90, 33, 64], tree=((4, 3, 2, 2, 1, 1), 32), head=True, L=1))
 
 
+def test_long_chains_three_and_four_row_groups():
+    """40 and 64 drafted rows per sequence: 160 and 256 query rows per kv head, i.e. three and four row
+    groups of 64 in the attention (three do not divide a workgroup's waves, four do), and k at its limit."""
+    check(mini("mini_k40", B=2, k=40, lens=[70, 129], head=True, V=4112, L=1))
+    check(mini("mini_k64", B=2, k=64, lens=[33, 64], L=1))
+
+
 def test_two_and_three_row_tiles():
     check(mini("mini_m24", B=4, k=6, lens=[100, 5, 64, 33]))
     check(mini("mini_m40", B=5, k=8, lens=[17, 200, 63, 1, 128], head=True, V=4112, L=1))
@@ -95,7 +102,7 @@ def test_six_row_tiles():
 
 
 def test_wide_ffn_picks_eight_computing_waves():
-    # with this many gate/up columns the 17..64-row GEMM runs 8 computing waves per workgroup
+    # with this many gate/up columns the GEMM for up to 64 rows runs 8 computing waves per workgroup
     check(mini("mini_wide24", B=4, k=6, lens=[50, 20, 64, 9], F=26624, L=1))
     check(mini("mini_wide64", B=8, k=8, lens=[50, 20, 64, 9, 1, 100, 33, 80], F=26624, L=1))
 
