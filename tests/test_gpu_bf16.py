@@ -90,6 +90,16 @@ def test_long_chains_three_and_four_row_groups():
     check(mini("mini_k64", B=2, k=64, lens=[33, 64], L=1))
 
 
+def test_shapes_the_panel_path_does_not_take():
+    """An FFN width that is no multiple of 512 keeps the panel GEMMs out: the one-workgroup-per-tile
+    kernels then carry any row count themselves (2, 4 and 8 row tiles here), as they did before the
+    panel path existed.  Also: one query head per kv head, and a vocabulary of two column tiles."""
+    check(mini("mini_f1792_m24", B=3, k=8, lens=[40, 9, 64], F=1792, L=1))
+    check(mini("mini_f1792_m64", B=8, k=8, lens=[40, 9, 64, 1, 100, 33, 80, 17], F=1792, head=True, V=4112, L=1))
+    check(mini("mini_f1792_m128", B=16, k=8, lens=[30 + 5 * b for b in range(16)], F=1792, L=1))
+    check(mini("mini_mha", B=2, k=5, lens=[70, 33], Hq=4, Hkv=4, head=True, V=32, L=1))
+
+
 def test_two_and_three_row_tiles():
     check(mini("mini_m24", B=4, k=6, lens=[100, 5, 64, 33]))
     check(mini("mini_m40", B=5, k=8, lens=[17, 200, 63, 1, 128], head=True, V=4112, L=1))
