@@ -100,6 +100,14 @@ def test_shapes_the_panel_path_does_not_take():
     check(mini("mini_mha", B=2, k=5, lens=[70, 33], Hq=4, Hkv=4, head=True, V=32, L=1))
 
 
+def test_head_dim_64_in_bf16_takes_the_generic_kernels():
+    lens = [50, 17]
+    cfg = W.scaled(W.CONFIGS["c3"], name="mini_hd64", B=2, k=5, C=max(lens), seed=3, L=2, d=256, Hq=4, Hkv=2, hd=64,
+                   F=512, V=1000, has_head=True, has_embed=False)
+    m = cfg.model
+    check((cfg, m, W.make_weights(m, cfg.seed), *W.make_kv(cfg), W.make_hidden(cfg), None, lens))
+
+
 def test_two_and_three_row_tiles():
     check(mini("mini_m24", B=4, k=6, lens=[100, 5, 64, 33]))
     check(mini("mini_m40", B=5, k=8, lens=[17, 200, 63, 1, 128], head=True, V=4112, L=1))
