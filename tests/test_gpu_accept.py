@@ -56,7 +56,7 @@ def ctx():
     return H.D.Context(0)
 
 
-@pytest.mark.parametrize("V", [17, 2048, 2049, 5000, 128256])
+@pytest.mark.parametrize("V", [17, 2048, 2049, 5000, 128256, 262147])
 def test_chain_strict_and_adaptive(ctx, V):
     B, k = (6, 5) if V > 10000 else (24, 5)
     lg, q, toks, u = make_rows(V, B, k, V)
