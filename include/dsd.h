@@ -104,7 +104,10 @@ const char* dsd_last_error(void);
 
 /* Context for HIP device `device`; hip_stream is a hipStream_t (NULL = the default stream).
  * The context owns a workspace that grows on demand (allocation happens inside the first
- * call that needs more, which then synchronises).  dsd_destroy frees it. */
+ * call that needs more, which then synchronises).  dsd_destroy frees it.
+ * Read from the environment here, for testing: DSD_PATH=simple (generic kernels also for bf16
+ * models), DSD_PERSIST=1 (single-kernel form of the pass for up to 8 rows), DSD_NO_TILED
+ * (no activation panels: one workgroup per column tile at every row count). */
 int dsd_create(int device, void* hip_stream, dsd_ctx** out);
 int dsd_destroy(dsd_ctx* ctx);
 int dsd_set_stream(dsd_ctx* ctx, void* hip_stream);

@@ -48,6 +48,7 @@ extern "C" int dsd_create(int device, void* hip_stream, dsd_ctx** out) {
     // more than the kernel boundaries they replace.
     const char* pp = getenv("DSD_PERSIST");
     c->no_persist = !(pp && strcmp(pp, "1") == 0);
+    c->no_tiled = getenv("DSD_NO_TILED") != nullptr;
     c->n_cu = prop.multiProcessorCount;
     c->bar_dev = nullptr;
     c->bar_base = 0;

@@ -94,6 +94,7 @@ struct dsd_ctx {
     std::vector<ProfRec> prof;
     // persistent stage kernel: grid-barrier words and their bookkeeping
     bool no_persist;               // true unless DSD_PERSIST=1: run one kernel per step
+    bool no_tiled;                 // DSD_NO_TILED set: the one-workgroup-per-tile GEMMs at every row count (testing)
     int n_cu;
     unsigned* bar_dev;             // [256] per-workgroup barrier flags, [256] abort word
     unsigned bar_base;             // barriers passed so far

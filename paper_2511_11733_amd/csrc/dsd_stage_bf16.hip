@@ -566,7 +566,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // Measured at the 8B shape, context 2048: one workgroup per column tile converting the activations
     // itself (gemm_skinny_kernel) wins up to 10 rows (0.87 ms at 5 rows against 0.92), the panel path
     // from 11 rows on (0.95 against 0.99 ms at 12 rows, 0.97 against 1.12 at 16).
-    const bool tiled = M >= TILED_MIN_ROWS && tiled_supported(&D) && !getenv("DSD_NO_TILED");
+    const bool tiled = M >= TILED_MIN_ROWS && tiled_supported(&D) && !ctx->no_tiled;
 
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);

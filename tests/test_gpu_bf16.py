@@ -30,18 +30,21 @@ def mini(name, B, k, lens, tree=None, head=False, L=2, d=512, Hq=8, Hkv=2, F=153
     return cfg, m, w, K, Vv, hid, parent, list(lens)
 
 
-def check(case, simple=False, persist=False):
+def check(case, simple=False, persist=False, no_tiled=False):
     cfg, m, w, K, V, hid, parent, lens = case
     ref = O.stage_forward(m, w.__getitem__, K, V, lens, hid, None, parent=parent)
     if simple:
         os.environ["DSD_PATH"] = "simple"
     if persist:
         os.environ["DSD_PERSIST"] = "1"
+    if no_tiled:
+        os.environ["DSD_NO_TILED"] = "1"
     try:
         st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
     finally:
         os.environ.pop("DSD_PATH", None)
         os.environ.pop("DSD_PERSIST", None)
+        os.environ.pop("DSD_NO_TILED", None)
     st.import_kv(K, V, lens)
     out, lg = st.verify(hidden=hid, parent=parent)
     tol = H.TOL["bf16"]
@@ -106,6 +109,15 @@ def test_head_dim_64_in_bf16_takes_the_generic_kernels():
                    F=512, V=1000, has_head=True, has_embed=False)
     m = cfg.model
     check((cfg, m, W.make_weights(m, cfg.seed), *W.make_kv(cfg), W.make_hidden(cfg), None, lens))
+
+
+def test_both_gemm_paths_on_the_same_case():
+    """15 and 40 rows through the panel GEMMs (the default from 11 rows on) and, with DSD_NO_TILED, through
+    the one-workgroup-per-tile kernels: each against the oracle."""
+    for name, B, k in (("both_m15", 3, 5), ("both_m40", 5, 8)):
+        case = mini(name, B=B, k=k, lens=[90 + 13 * b for b in range(B)], head=True, V=4112, L=2)
+        check(case)
+        check(case, no_tiled=True)
 
 
 def test_two_and_three_row_tiles():
