@@ -120,6 +120,13 @@ def test_both_gemm_paths_on_the_same_case():
         check(case, no_tiled=True)
 
 
+def test_large_vocabulary_head_with_many_rows():
+    """From 65 rows on a vocabulary of at least 256 column blocks of 256 ids runs the LM head with 8
+    computing waves per workgroup (6 and 8 row tiles): 80 and 128 rows, V = 66000."""
+    check(mini("mini_v66k_m80", B=10, k=8, lens=[20 + 3 * b for b in range(10)], head=True, V=66000, L=1))
+    check(mini("mini_v66k_m128", B=16, k=8, lens=[20 + 3 * b for b in range(16)], head=True, V=66000, L=1))
+
+
 def test_two_and_three_row_tiles():
     check(mini("mini_m24", B=4, k=6, lens=[100, 5, 64, 33]))
     check(mini("mini_m40", B=5, k=8, lens=[17, 200, 63, 1, 128], head=True, V=4112, L=1))
