@@ -199,9 +199,10 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
         w[i] = p.Wt + ((size_t)(live[i] ? tile[i] : 0) * p.KS + ks0) * 64 + lane;
     }
 
-    // fragments in flight per wave: 32 (16 k-steps), or 16 where 128 rows of accumulators and
-    // activation fragments leave no more registers at two waves per SIMD
-    constexpr int NF = (MT <= 3 || (TWC == 8 && MT > 4)) ? 8 : 16;      // 8 computing waves with 6 or 8 row tiles: 170 registers each
+    // weight fragments in flight per wave: 16 (8 k-steps); 8 where the registers are the limit: up to 3
+    // row tiles run four waves per SIMD (128 registers each), 8 computing waves with 6 or 8 row
+    // tiles three (170 each).  A FIFO of 32 was measured at 8 row tiles: no faster (the fill takes longer).
+    constexpr int NF = (MT <= 3 || (TWC == 8 && MT > 4)) ? 8 : 16;
     u32x4 fifo[NF];
     int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
 #pragma unroll
