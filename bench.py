@@ -233,7 +233,7 @@ def main():
             # library picks the GEMM's geometry from the row count and the matrix width
             mt = (M + 15) // 16
             mt = {1: 2, 5: 6, 7: 8}.get(mt, mt)
-            twc = 8 if (mt <= 4 and -(-(2 * (m.F // 16)) // 16) * 5 >= 256 * 4) else 4
+            twc = 8 if -(-(2 * (m.F // 16)) // 16) * 5 >= 256 * 4 else 4
             dom_name = (f"act_panel_kernel + gemm_tiled_kernel<{mt}, {twc}, TE_SWIGLU> (RMSNorm + gate/up GEMM + SiLU*up; "
                         "the time is that of both launches)")
             dom_match = f"gemm_tiled_kernel<{mt}, {twc}, 1>"

@@ -461,11 +461,11 @@ static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, 
             case 1: case 2: return tiled_launch<2, 8, EPI>(s, p, n_blocks, ksplit);
             case 3: return tiled_launch<3, 8, EPI>(s, p, n_blocks, ksplit);
             case 4: return tiled_launch<4, 8, EPI>(s, p, n_blocks, ksplit);
-            // more row tiles with 8 computing waves: the LM head only (see tiled_gemm_logits)
+            // more row tiles with 8 computing waves: only the kernels that do not cut K (see choose_twc)
             case 5: case 6:
-                if constexpr (EPI == TE_LOGITS) return tiled_launch<6, 8, EPI>(s, p, n_blocks, ksplit);
+                if constexpr (EPI != TE_PARTIAL) return tiled_launch<6, 8, EPI>(s, p, n_blocks, ksplit);
             case 7: case 8:
-                if constexpr (EPI == TE_LOGITS) return tiled_launch<8, 8, EPI>(s, p, n_blocks, ksplit);
+                if constexpr (EPI != TE_PARTIAL) return tiled_launch<8, 8, EPI>(s, p, n_blocks, ksplit);
             default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: 8 computing waves with %d rows", p.M);
         }
     }
@@ -481,10 +481,12 @@ static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, 
 
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Column tiles (16 wide) per workgroup: 16 (8 computing waves) when the rows allow it and the matrix
-// is wide enough to give about a workgroup per compute unit without cutting K, else 8.
-static int choose_twc(int M, int n_tiles16, int n_cu) {
-    if ((M + 15) / 16 > 4) return 4;
+// Column tiles (16 wide) per workgroup: 16 (8 computing waves) when the matrix is wide enough to give
+// about a workgroup per compute unit without cutting K, else 8.  More than 4 row tiles run 8
+// computing waves only in the kernels that do not cut K (gate/up, LM head): those are the ones with
+// several rounds of workgroups to halve.
+static int choose_twc(int M, int n_tiles16, int n_cu, bool k_sliced) {
+    if ((M + 15) / 16 > 4 && k_sliced) return 4;
     return (long)ceil_div(n_tiles16, 8 * NTW) * 5 >= (long)n_cu * 4 ? 8 : 4;
 }
 
@@ -547,7 +549,7 @@ static int tiled_gemm_partial(dsd_ctx* ctx, const void* Wt, int M, int N, int K,
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = part; p.N = N;
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    const int twc = choose_twc(M, N / 16, ctx->n_cu);
+    const int twc = choose_twc(M, N / 16, ctx->n_cu, true);
     const int nb = ceil_div(N / 16, twc * NTW);
     const int sp = choose_ksplit(p.KS, nb, tiled_slots(M, twc, ctx->n_cu), ctx->n_cu, twc * NTW * 16, M, N);
     p.ks_per_split = p.KS / sp;
@@ -593,7 +595,7 @@ int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.n_ssq = K / 128; p.eps = eps; p.panel_out = (unsigned short*)panel_h; p.N = F; p.up_tile_off = F / 16;
     // fused SiLU*up needs the whole K in one workgroup: no K split
-    const int twc = choose_twc(M, 2 * (F / 16), ctx->n_cu);
+    const int twc = choose_twc(M, 2 * (F / 16), ctx->n_cu, false);
     return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, twc, ceil_div(F / 16, twc * NTW / 2), 1);
 }
 
@@ -609,7 +611,6 @@ int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     // A vocabulary gives several rounds of workgroups, each paying its pipeline fill and its epilogue with
     // the compute unit idle; 256-column workgroups (8 computing waves, a shorter weight FIFO to fit
     // the registers) halve the number of rounds.  Measured at 128 rows, V = 128256: 254 -> 238 us.
-    int twc = choose_twc(M, V / 16, ctx->n_cu);
-    if (mt_of(M) > 4 && ceil_div(V / 16, 8 * NTW) >= ctx->n_cu) twc = 8;
+    const int twc = choose_twc(M, V / 16, ctx->n_cu, false);
     return tiled_dispatch<TE_LOGITS>(ctx->stream, p, twc, ceil_div(V / 16, twc * NTW), 1);
 }

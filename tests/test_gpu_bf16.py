@@ -120,6 +120,13 @@ def test_both_gemm_paths_on_the_same_case():
         check(case, no_tiled=True)
 
 
+def test_wide_ffn_with_many_rows():
+    """A 70B-wide FFN at 80 and 128 rows: gate/up has a workgroup of 256 columns per compute unit, so it
+    runs 8 computing waves with 6 and 8 row tiles."""
+    check(mini("mini_wide80", B=10, k=8, lens=[20 + 3 * b for b in range(10)], F=28672, L=1))
+    check(mini("mini_wide128", B=16, k=8, lens=[20 + 3 * b for b in range(16)], F=28672, L=1))
+
+
 def test_large_vocabulary_head_with_many_rows():
     """From 65 rows on a vocabulary of at least 256 column blocks of 256 ids runs the LM head with 8
     computing waves per workgroup (6 and 8 row tiles): 80 and 128 rows, V = 66000."""
