@@ -43,7 +43,13 @@ def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None):
                      tau_override)
     excused, near = H.compare_accept(g, ora, what)
     fin = np.isfinite(ora.ratio)
-    np.testing.assert_allclose(g["ratio"][fin], ora.ratio[fin], rtol=1e-6, err_msg=what)
+    # The reported ratios are fp64 over fp32 per-id terms: 1e-6 relative for the per-node rules.  In the
+    # lossless walk a later sibling's p is a residual max(0, p - q) / Z; Z sums fp32 terms whose absolute
+    # error is ~1e-7 of p, so its relative error is 1e-7 / Z, and Z (the mass on which target and draft
+    # disagree) is 1e-3 or less when peaked rows nearly coincide.  Decisions are protected by the
+    # oracle's near-tie margin of 1e-3 on the same ratio.
+    np.testing.assert_allclose(g["ratio"][fin], ora.ratio[fin], rtol=1e-4 if prm.get("tree_mode", 0) == 2 else 1e-6,
+                               err_msg=what)
     if prm.get("norm_match_kind", 0) == 1:      # a vocabulary-wide sum: fp32 terms on the GPU
         np.testing.assert_allclose(g["norm_match"], ora.norm_match, rtol=1e-6, err_msg=what)
     else:
@@ -73,6 +79,22 @@ def test_chain_strict_and_adaptive(ctx, V):
     ora, g, ex, near = run_case(ctx, lg, q, toks, None, u, prm, f"adaptive V={V}")
     assert 0.1 < ora.key.mean() < 0.9
     print(f"V={V}: key fraction {ora.key.mean():.2f}, mean accepted {ora.accepted_len.mean():.2f}, near ties {near}, excused {ex}")
+
+
+@pytest.mark.parametrize("spread,noise", [(4.0, 0.5), (8.0, 2.0)])
+def test_peaked_rows(ctx, spread, noise):
+    """Rows like a trained model's: a few ids carry most of the mass (logit spread 4 and 8 standard
+    deviations: top probability 0.1 .. 0.9), most probabilities underflow towards zero, accepted lengths are
+    long.  Strict, adaptive and lossless-tree rules."""
+    B, k, V = 6, 6, 50257
+    lg, q, toks, u = make_rows(int(spread * 10), B, k, V, spread=spread, noise=noise)
+    ora, *_ = run_case(ctx, lg, q, toks, None, u, dict(tau=0.0), f"peaked {spread} strict")
+    run_case(ctx, lg, q, toks, None, u, dict(tau=0.3, lambda1=1.2, lambda2=1e-2, lambda3=0.5), f"peaked {spread} adaptive")
+    parent = W.ranked_tree_parents((3, 2), 6)
+    lg2, q2, toks2, u2 = make_rows(int(spread * 10) + 1, B, k, V, parent=parent, spread=spread, noise=noise)
+    run_case(ctx, lg2, q2, toks2, parent, u2, dict(tau=0.0, tree_mode=2), f"peaked {spread} lossless tree")
+    print(f"spread {spread}: top probability {np.exp(lg[0, 0] - lg[0, 0].max()).max() / np.exp(lg[0, 0] - lg[0, 0].max()).sum():.2f}, "
+          f"mean accepted {ora.accepted_len.mean():.2f} of {k}")
 
 
 def test_top_m_limits_and_temperature(ctx):
