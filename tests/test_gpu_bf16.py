@@ -326,3 +326,49 @@ def test_outlier_channels_in_the_residual_stream(B, k):
     hid = (f.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)      # truncation to bf16 is good enough for an input
     check((cfg, m, w, K, V, hid, parent, lens))
 
+
+def test_commit_of_tree_paths_in_the_operand_order_cache():
+    """After a tree verify, dsd_kv_commit moves the accepted path's rows (scattered among the k drafted
+    slots) to the slots right behind the committed ones.  The bf16 cache keeps K and V in MFMA operand
+    order, V with a permutation inside blocks of 32 slots, so the move is checked on exported rows:
+    rows exported after the commit equal, bit for bit, the path's rows exported before it; lengths that
+    straddle 16- and 32-slot boundaries; one sequence accepts nothing."""
+    B, k = 4, 10
+    lens = [31, 64, 13, 95]
+    cfg, m, w, K, V, hid, parent, _ = mini("commit_tree", B=B, k=k, lens=lens, tree=((3, 2, 2), 10))
+    st = H.GpuStage(m, w, B, max(lens) + k + 3)
+    st.import_kv(K, V, lens)
+    st.verify(hidden=hid, parent=parent)
+    par = [int(p) for p in parent]
+
+    def path_to(node):                      # root-to-node path of 1-based node ids
+        out = []
+        while node:
+            out.append(node)
+            node = par[node - 1]
+        return out[::-1]
+
+    leaves = [n for n in range(1, k + 1) if n not in par]
+    paths = [path_to(leaves[0]), path_to(leaves[-1]), [], path_to(par[leaves[-1] - 1])]
+    before = [[st.new_rows(l, lens[b], k, B) for b in range(B)] for l in range(m.L)]
+    alen = torch.tensor([len(p) for p in paths], dtype=torch.int32, device="cuda:0")
+    padded = np.full((B, k), -1, dtype=np.int32)
+    for b, p in enumerate(paths):
+        padded[b, :len(p)] = p
+    H.D.dsd_kv_commit(st.ctx, st.kv, alen, torch.from_numpy(padded).to("cuda:0"), B, k)
+    torch.cuda.synchronize()
+    assert st.kv.get_len(B) == [lens[b] + len(paths[b]) for b in range(B)]
+    for l in range(m.L):
+        for b, p in enumerate(paths):
+            if not p:
+                continue
+            gk, gv = st.new_rows(l, lens[b], len(p), B)
+            bk, bv = before[l][b]
+            idx = [n - 1 for n in p]
+            np.testing.assert_array_equal(gk[b], bk[b][:, idx], err_msg=f"K layer {l} sequence {b}")
+            np.testing.assert_array_equal(gv[b], bv[b][:, idx], err_msg=f"V layer {l} sequence {b}")
+        # committed context untouched
+        gk, gv = st.new_rows(l, 0, min(lens), B)
+        np.testing.assert_array_equal(gk, O.widen(K[l][:, :, :min(lens)]))
+        np.testing.assert_array_equal(gv, O.widen(V[l][:, :, :min(lens)]))
+
