@@ -567,6 +567,9 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // itself (gemm_skinny_kernel) wins up to 10 rows (0.87 ms at 5 rows against 0.92), the panel path
     // from 11 rows on (0.95 against 0.99 ms at 12 rows, 0.97 against 1.12 at 16).
     const bool tiled = M >= TILED_MIN_ROWS && tiled_supported(&D) && !ctx->no_tiled;
+    // The LM head takes the panel path at every row count: a vocabulary is a gigabyte of weights, and 256-column
+    // workgroups stream it faster than one workgroup per 16 columns (207 against 228 us at 5 rows, V = 128256).
+    const bool tiled_head = logits && tiled_supported(&D) && !ctx->no_tiled;
 
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
@@ -605,7 +608,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         rope = ws.take<float2>((size_t)M * 64);
         part = ws.take<float>(n_part);
         ssq = ws.take<float>(n_ssq);                               // [d/128][128]: sums of squares of the rows, per chunk of 128 columns
-        panel = ws.take<float>(tiled ? 64 * kmax : 0);             // up to 128 rows of activations as fp16 in A-operand order
+        panel = ws.take<float>(tiled || tiled_head ? 64 * kmax : 0);             // up to 128 rows of activations as fp16 in A-operand order
     };
     WsBump sizing{nullptr, 0};
     carve(sizing);
@@ -709,7 +712,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)w->lm_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)w->gf;
         a.logits = logits; a.N = D.vocab; a.rows_per_seq = k; a.seq_stride = logits_seq_stride;
         ProfScope ps(ctx, DSD_KC_HEAD);
-        if (tiled)
+        if (tiled_head)
             DSD_TRY(tiled_gemm_logits(ctx, w->lm_t, x, (const bf16_t*)w->gf, part, x_pending, logits, M, D.vocab, d,
                                       D.rms_eps, k, logits_seq_stride, panel, ssq));
         else
