@@ -84,6 +84,7 @@ def main():
     ap.add_argument("--temperature", type=float, default=1.0, help="dsd_accept's temperature; 0 = greedy verification")
     ap.add_argument("--batch", type=int, default=0, help="row-count sweeps: the named workload with another batch size")
     ap.add_argument("--draft-len", type=int, default=0, help="row-count sweeps: another number of drafted rows (chains only)")
+    ap.add_argument("--context", type=int, default=0, help="context sweeps: another committed length per sequence")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a known-size reference for HBM byte counters)")
@@ -104,11 +105,11 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.config]
-    if args.batch or args.draft_len:
-        # not a benchmark line of its own: the same model, context and recipe at another row count
+    if args.batch or args.draft_len or args.context:
+        # not a benchmark line of its own: the same model and recipe at another row count or context
         assert not (cfg.tree and args.draft_len), "a tree workload keeps its own number of nodes"
-        nb, nk = args.batch or cfg.B, args.draft_len or cfg.k
-        cfg = W.scaled(cfg, name=f"{cfg.name} at B={nb} k={nk}", B=nb, k=nk)
+        nb, nk, nc = args.batch or cfg.B, args.draft_len or cfg.k, args.context or cfg.C
+        cfg = W.scaled(cfg, name=f"{cfg.name} at B={nb} k={nk} C={nc}", B=nb, k=nk, C=nc)
     m = cfg.model
     assert m.dtype == "bf16", "bench workloads are the bf16 configurations"
     dev = "cuda:0"
