@@ -232,15 +232,20 @@ static int launch_gemm(hipStream_t s, const GemmArgs& p, int n_blocks) {
 }
 
 template <int NT, int AMODE, int EPI>
-static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks) {
+static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks, int n_cu) {
     const int mt = (p.M + 15) / 16;
     switch (mt) {
         case 1:
-            // 16 waves split K when a matrix has few column tiles; a matrix with at least two tiles per
-            // compute unit (gate/up, LM head) streams better from small workgroups, several of which fit a
-            // compute unit and overlap each other's start-up and reduction phases (measured: 46.5 vs 49.6 us)
-            if (n_blocks >= 512) return launch_gemm<1, NT, AMODE, EPI, 4>(s, p, n_blocks);
-            return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
+            // The waves of a workgroup split K.  As many of them as keep the whole grid resident at once
+            // (32 waves per compute unit): every wave has one k-step of loads in flight, so it is the
+            // number of resident waves that feeds the memory system, and a grid that does not fit runs
+            // in rounds.  16 for the narrow matrices (QKV, O, down; down at d_model 8192 with 4 waves:
+            // 147 us, with 16: 105), 4 for gate/up (8 was measured at d_model 4096: 47.0 against 45.3 us).
+            {
+                const long resident = 32L * n_cu;
+                if ((long)n_blocks * 16 <= resident) return launch_gemm<1, NT, AMODE, EPI, 16>(s, p, n_blocks);
+                return launch_gemm<1, NT, AMODE, EPI, 4>(s, p, n_blocks);
+            }
         case 2: return launch_gemm<2, NT, AMODE, EPI, 16>(s, p, n_blocks);
         case 3: return launch_gemm<3, NT, AMODE, EPI, 8>(s, p, n_blocks);
         case 4: return launch_gemm<4, NT, AMODE, EPI, 8>(s, p, n_blocks);
@@ -563,10 +568,15 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // a wave takes at most 4 row tiles (registers); more rows are split into row groups
     const int n_rg = (n_rt + 3) / 4;
     const int RT = (n_rt + n_rg - 1) / n_rg;
-    // Measured at the 8B shape, context 2048: one workgroup per column tile converting the activations
-    // itself (gemm_skinny_kernel) wins up to 10 rows (0.87 ms at 5 rows against 0.92), the panel path
-    // from 11 rows on (0.95 against 0.99 ms at 12 rows, 0.97 against 1.12 at 16).
-    const bool tiled = M >= TILED_MIN_ROWS && tiled_supported(&D) && !ctx->no_tiled;
+    // Which GEMM path.  One workgroup per column tile converting the activations itself
+    // (gemm_skinny_kernel) wins for up to 10 rows when the residual GEMMs (d_model / 16 tiles) are exactly
+    // one round of one workgroup per compute unit: d_model 4096 on 256 CUs, 107.6 against 114.4 us per
+    // layer at 5 rows; from 11 rows on the panel path wins there too (0.95 against 0.99 ms at 12 rows,
+    // 0.97 against 1.12 at 16).  Wider models leave that kernel a ragged second round, and the panel
+    // path wins at every row count: per layer at 5 rows 136.9 against 149.0 us (d_model 5120), 166.8
+    // against 182.4 (6144), 333.7 against 353.2 (8192).
+    const int tiled_min_rows = d / 16 <= ctx->n_cu ? TILED_MIN_ROWS : 1;
+    const bool tiled = M >= tiled_min_rows && tiled_supported(&D) && !ctx->no_tiled;
     // The LM head takes the panel path at every row count: a vocabulary is a gigabyte of weights, and 256-column
     // workgroups stream it faster than one workgroup per 16 columns (207 against 228 us at 5 rows, V = 128256).
     const bool tiled_head = logits && tiled_supported(&D) && !ctx->no_tiled;
@@ -647,7 +657,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
                                        kv->len_dev, k, Hq, D.rms_eps, rope, panel, ssq));
                 x_pending = 0;
             } else
-                DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4)));
+                DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_QKV>(s, a, (Hq + 2 * Hkv) * 4, ctx->n_cu)));
         }
         // attention
         AttnArgs t;
@@ -676,7 +686,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
             if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wo_t, part, &x_pending, M, d, qd, panel));
-            else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
+            else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16, ctx->n_cu)));
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
         a = GemmArgs();
@@ -688,7 +698,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
                 DSD_TRY(tiled_gemm_swiglu(ctx, W.gu_t, x, (const bf16_t*)W.g2, part, x_pending, panel_h, M, F, d, D.rms_eps,
                                           panel, ssq));
                 x_pending = 0;
-            } else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16)));
+            } else DSD_TRY((gemm_dispatch<2, A_F32_GAIN, EPI_SWIGLU>(s, a, F / 16, ctx->n_cu)));
         }
         // x += h Wd^T
         a = GemmArgs();
@@ -697,7 +707,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         {
             ProfScope ps(ctx, DSD_KC_DOWN);
             if (tiled) DSD_TRY(tiled_gemm_resid(ctx, W.wd_t, part, &x_pending, M, d, F, panel_h));
-            else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16)));
+            else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16, ctx->n_cu)));
         }
     }
     // the block's output rows: up to 10 rows the last down projection's epilogue has written them; on the
@@ -716,7 +726,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
             DSD_TRY(tiled_gemm_logits(ctx, w->lm_t, x, (const bf16_t*)w->gf, part, x_pending, logits, M, D.vocab, d,
                                       D.rms_eps, k, logits_seq_stride, panel, ssq));
         else
-            DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16)));
+            DSD_TRY((gemm_dispatch<1, A_F32_GAIN, EPI_LOGITS>(s, a, D.vocab / 16, ctx->n_cu)));
     }
     DSD_HIP(hipGetLastError());
     return DSD_OK;

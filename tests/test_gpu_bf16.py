@@ -134,6 +134,13 @@ def test_large_vocabulary_head_with_many_rows():
     check(mini("mini_v66k_m128", B=16, k=8, lens=[20 + 3 * b for b in range(16)], head=True, V=66000, L=1))
 
 
+def test_few_rows_on_the_panel_path_for_wide_models():
+    """A d_model of more than 16 tiles per compute unit (here 4608: 288 tiles on 256 CUs) takes the panel
+    GEMMs at every row count: 1, 5 and 10 rows."""
+    for B, k in ((1, 1), (1, 5), (2, 5)):
+        check(mini(f"mini_d4608_m{B * k}", B=B, k=k, lens=[70, 33][:B], d=4608, Hq=36, Hkv=4, F=2048, L=1))
+
+
 def test_two_and_three_row_tiles():
     check(mini("mini_m24", B=4, k=6, lens=[100, 5, 64, 33]))
     check(mini("mini_m40", B=5, k=8, lens=[17, 200, 63, 1, 128], head=True, V=4112, L=1))
