@@ -211,7 +211,11 @@ int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, cons
 /* Advances every sequence by its accepted tokens (section 2.1: x_{1:i+k} = x_{1:i} (+) y_{i+1:i+k}):
  * in every layer the K/V rows that the last dsd_stage_verify wrote for the path's nodes become
  * slots len[b] .. len[b]+a-1, and len[b] += a.  accepted_len / accepted_path are device arrays
- * as written by dsd_accept ([B], [B,k]); accepted_path NULL = chain (first a rows, nothing moves). */
+ * as written by dsd_accept ([B], [B,k]); accepted_path NULL = chain (first a rows, nothing moves).
+ * Does not synchronise: the lengths live on the device, and the host only keeps an upper bound
+ * (+k per commit) for validation and grid sizes.  dsd_kv_get_len reads the true lengths back and
+ * tightens that bound; a caller that never does loses k - a slots of usable capacity per round.
+ * Errors: DSD_ESHAPE if k differs from the last dsd_stage_verify on this cache. */
 int dsd_kv_commit(dsd_ctx* ctx, dsd_kv* kv, const int32_t* accepted_len, const int32_t* accepted_path,
                   int B, int k);
 
