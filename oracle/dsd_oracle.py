@@ -243,7 +243,66 @@ class AcceptOut:
     tau_used: np.ndarray          # [B, k]
     ratio: np.ndarray             # [B, k]  P~(y)/q(y)  (inf when q(y) = 0 < P~(y))
     norm_match: np.ndarray        # [B, k]
-    near_tie: np.ndarray          # [B] bit 0: accept test, bit 1: key rule, bit 2: resample draw
+    near_tie: np.ndarray          # [B] bit 0: accept test, bit 1: key rule, bit 2: resample draw (any node)
+    tie_accept: np.ndarray        # [B, k] bool: node i's ratio P~(y)/q(y) lies within TIE_RATIO of its uniform
+    tie_key: np.ndarray           # [B, k] bool: one of node i's key comparisons lies within its band (see accept)
+    tie_draw: np.ndarray          # [B] bool: u_0 * S lies within TIE_CDF * S of a boundary of the cumulative sum
+
+
+# Near-tie bands.  A decision is a comparison of two real numbers; an implementation that evaluates
+# them in another precision or order may legitimately land on the other side when they are this
+# close.  The oracle only REPORTS where that is the case (per node and per kind of decision); what a
+# comparison of two implementations does with the flags is the test's business.
+TIE_RATIO = 1e-3      # |P~(y)/q(y) - u_i|: the exception the acceptance test is allowed
+TIE_LAMBDA = 1e-3     # relative distance of H_d from lambda1*H_t, of |P_t(y)-q(y)| from lambda2
+TIE_TOP_M = 1e-5      # relative gap between the M-th and (M+1)-th largest entry of a row (top-M NormMatch)
+TIE_OVERLAP = 1e-6    # absolute distance of the overlap NormMatch from lambda3
+TIE_CDF = 1e-6        # distance of u_0*S from a cumulative-sum boundary, relative to S
+
+
+def _new_out(B: int, k: int) -> AcceptOut:
+    return AcceptOut(
+        accepted_len=np.zeros(B, dtype=np.int32), next_token=np.zeros(B, dtype=np.int32),
+        accepted_path=-np.ones((B, max(k, 1)), dtype=np.int32), key=np.zeros((B, k), dtype=bool),
+        node_accept=np.zeros((B, k), dtype=bool), tau_used=np.zeros((B, k)), ratio=np.zeros((B, k)),
+        norm_match=np.zeros((B, k)), near_tie=np.zeros(B, dtype=np.int32),
+        tie_accept=np.zeros((B, k), dtype=bool), tie_key=np.zeros((B, k), dtype=bool),
+        tie_draw=np.zeros(B, dtype=bool))
+
+
+def _forced(force: Optional[np.ndarray], b: int, i: int, computed: bool) -> bool:
+    """A decision as computed, unless the caller pins it (force[b, i-1] in {0, 1}; -1 = not pinned).
+    Used by tests to ask what follows from a near-tie decision falling the other way."""
+    if force is not None and int(force[b, i - 1]) >= 0:
+        return bool(int(force[b, i - 1]))
+    return computed
+
+
+def _row_nm_and_tie(pt: np.ndarray, q: np.ndarray, prm: "AcceptParams"):
+    """NormMatch of a row pair and whether it sits within its band of changing."""
+    nm = row_norm_match(pt, q, prm)
+    tie = False
+    V = pt.shape[0]
+    if prm.norm_match_kind == NM_TOP_M:
+        for row in (pt, q):
+            srt = np.sort(row)[::-1]
+            if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < TIE_TOP_M * srt[prm.top_m - 1]:
+                tie = True
+    elif np.isfinite(prm.lambda3) and abs(nm - prm.lambda3) < TIE_OVERLAP:
+        tie = True
+    return nm, tie
+
+
+def _key_tie(pt_y: float, q_y: float, h_t: float, h_d: float, prm: "AcceptParams") -> bool:
+    """Whether the first or the second key criterion of a node lies within TIE_LAMBDA of its threshold."""
+    tie = False
+    with np.errstate(divide="ignore", invalid="ignore"):
+        if np.isfinite(prm.lambda1) and np.isfinite(h_t) and np.isfinite(h_d) and \
+                abs(h_d - prm.lambda1 * h_t) < TIE_LAMBDA * abs(prm.lambda1 * h_t):
+            tie = True
+    if np.isfinite(prm.lambda2) and abs(abs(pt_y - q_y) - prm.lambda2) < TIE_LAMBDA * prm.lambda2:
+        tie = True
+    return tie
 
 
 def softmax_row(logits_row: np.ndarray, temperature: float) -> np.ndarray:
@@ -328,7 +387,8 @@ def inverse_cdf(weights: np.ndarray, u: float):
 
 def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray,
            parent: Optional[Sequence[int]], uniforms: np.ndarray, prm: AcceptParams,
-           tau_override: Optional[np.ndarray] = None) -> AcceptOut:
+           tau_override: Optional[np.ndarray] = None, force_key: Optional[np.ndarray] = None,
+           force_accept: Optional[np.ndarray] = None) -> AcceptOut:
     """Algorithm 1, lines 2-16, for B sequences.
 
     logits       [B, k+1, V]  row 0 follows the committed context, row i follows node i
@@ -337,6 +397,8 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
     parent       [k] in 0..k  (None = chain); parent[i-1] < i
     uniforms     [B, k+1]     u_i decides node i, u_0 draws the additional token
     tau_override [B, k]       if given, tau of node i regardless of the key rule
+    force_key, force_accept [B, k] in {-1, 0, 1}: tests only -- pins the key flag / the outcome of
+                 node i's own test (-1 = as computed), to follow a near-tie decision the other way
     """
     B, k1, V = logits.shape
     k = k1 - 1
@@ -346,7 +408,8 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
     if prm.temperature == 0.0:
         return accept_greedy(logits, draft_tokens, parent, prm)
     if prm.tree_mode == TREE_LOSSLESS:
-        return accept_lossless(logits, draft_probs, draft_tokens, parent, uniforms, prm)
+        return accept_lossless(logits, draft_probs, draft_tokens, parent, uniforms, prm, force_key=force_key,
+                               force_accept=force_accept)
     children: Dict[int, List[int]] = {}
     for i in range(1, k + 1):
         children.setdefault(parent[i - 1], []).append(i)
@@ -354,15 +417,11 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
     for i in range(1, k + 1):
         depth[i] = depth[parent[i - 1]] + 1
 
-    out = AcceptOut(
-        accepted_len=np.zeros(B, dtype=np.int32), next_token=np.zeros(B, dtype=np.int32),
-        accepted_path=-np.ones((B, max(k, 1)), dtype=np.int32), key=np.zeros((B, k), dtype=bool),
-        node_accept=np.zeros((B, k), dtype=bool), tau_used=np.zeros((B, k)), ratio=np.zeros((B, k)),
-        norm_match=np.zeros((B, k)), near_tie=np.zeros(B, dtype=np.int32))
+    out = _new_out(B, k)
 
     for b in range(B):
         pt_rows: Dict[int, np.ndarray] = {}
-        nm_rows: Dict[int, float] = {}
+        nm_rows: Dict[int, tuple] = {}
 
         def target_row(p):
             if p not in pt_rows:
@@ -376,35 +435,21 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
             pt = target_row(p)
             q = draft_probs[b, p].astype(F64)
             if p not in nm_rows:
-                nm_rows[p] = row_norm_match(pt, q, prm)
-                # top-M boundary gaps (a swap across the boundary could change NormMatch)
-                if prm.norm_match_kind == NM_TOP_M:
-                    for row in (pt, q):
-                        srt = np.sort(row)[::-1]
-                        if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
-                            out.near_tie[b] |= 2
-                elif np.isfinite(prm.lambda3) and abs(nm_rows[p] - prm.lambda3) < 1e-6:
-                    out.near_tie[b] |= 2
-            nm = nm_rows[p]
+                nm_rows[p] = _row_nm_and_tie(pt, q, prm)
+            nm, nm_tie = nm_rows[p]
             h_t, h_d = key_entropies(pt, q, y, prm)
-            key = is_key(pt[y], q[y], nm, prm, (h_t, h_d))
-            with np.errstate(divide="ignore", invalid="ignore"):
-                if np.isfinite(prm.lambda1) and np.isfinite(h_t) and np.isfinite(h_d) and \
-                        abs(h_d - prm.lambda1 * h_t) < 1e-3 * abs(prm.lambda1 * h_t):
-                    out.near_tie[b] |= 2
-            if np.isfinite(prm.lambda2) and abs(abs(pt[y] - q[y]) - prm.lambda2) < 1e-3 * prm.lambda2:
-                out.near_tie[b] |= 2
+            key = _forced(force_key, b, i, is_key(pt[y], q[y], nm, prm, (h_t, h_d)))
+            out.tie_key[b, i - 1] = nm_tie or _key_tie(pt[y], q[y], h_t, h_d, prm)
             tau_i = 0.0 if key else prm.tau
             if tau_override is not None:
                 tau_i = float(tau_override[b, i - 1])
             ptil = softened_target(pt, q, tau_i)
             ptilde_of[i] = ptil
             u = F64(uniforms[b, i])
-            acc = bool(u * q[y] < ptil[y])
+            acc = _forced(force_accept, b, i, bool(u * q[y] < ptil[y]))
             with np.errstate(divide="ignore", invalid="ignore"):
                 ratio = ptil[y] / q[y] if q[y] > 0 else (np.inf if ptil[y] > 0 else 0.0)
-            if abs(ratio - u) < 1e-3:
-                out.near_tie[b] |= 1
+            out.tie_accept[b, i - 1] = abs(ratio - u) < TIE_RATIO
             out.key[b, i - 1] = key
             out.node_accept[b, i - 1] = acc
             out.tau_used[b, i - 1] = tau_i
@@ -451,14 +496,16 @@ def accept(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray
             if w.sum() == 0.0:
                 w = ptil
         tok, gap = inverse_cdf(w, u0)
-        if gap < 1e-6:
-            out.near_tie[b] |= 4
+        out.tie_draw[b] = gap < TIE_CDF
         out.next_token[b] = tok
+        out.near_tie[b] = (1 if out.tie_accept[b].any() else 0) | (2 if out.tie_key[b].any() else 0) | \
+                          (4 if out.tie_draw[b] else 0)
     return out
 
 
 def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: np.ndarray, parent: Sequence[int],
-                    uniforms: np.ndarray, prm: AcceptParams) -> AcceptOut:
+                    uniforms: np.ndarray, prm: AcceptParams, force_key: Optional[np.ndarray] = None,
+                    force_accept: Optional[np.ndarray] = None) -> AcceptOut:
     """Tree verification that keeps the target distribution when a node has several children.
 
     The paper verifies chains (section 2.1, Algorithm 1); for the token trees of the line of work
@@ -482,11 +529,7 @@ def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: n
     children: Dict[int, List[int]] = {}
     for i in range(1, k + 1):
         children.setdefault(parent[i - 1], []).append(i)
-    out = AcceptOut(
-        accepted_len=np.zeros(B, dtype=np.int32), next_token=np.zeros(B, dtype=np.int32),
-        accepted_path=-np.ones((B, max(k, 1)), dtype=np.int32), key=np.zeros((B, k), dtype=bool),
-        node_accept=np.zeros((B, k), dtype=bool), tau_used=np.zeros((B, k)), ratio=np.zeros((B, k)),
-        norm_match=np.zeros((B, k)), near_tie=np.zeros(B, dtype=np.int32))
+    out = _new_out(B, k)
     for b in range(B):
         # key flags and NormMatch as in the other modes (reported only)
         for i in range(1, k + 1):
@@ -494,22 +537,11 @@ def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: n
             y = int(draft_tokens[b, i - 1])
             pt = softmax_row(logits[b, p_row], prm.temperature)
             q = draft_probs[b, p_row].astype(F64)
-            nm = row_norm_match(pt, q, prm)
+            nm, nm_tie = _row_nm_and_tie(pt, q, prm)
             h_t, h_d = key_entropies(pt, q, y, prm)
-            out.key[b, i - 1] = is_key(pt[y], q[y], nm, prm, (h_t, h_d))
+            out.key[b, i - 1] = _forced(force_key, b, i, is_key(pt[y], q[y], nm, prm, (h_t, h_d)))
             out.norm_match[b, i - 1] = nm
-            if prm.norm_match_kind == NM_TOP_M:
-                for srt in (np.sort(pt)[::-1], np.sort(q)[::-1]):
-                    if prm.top_m < V and srt[prm.top_m - 1] - srt[prm.top_m] < 1e-5 * srt[prm.top_m - 1]:
-                        out.near_tie[b] |= 2
-            elif np.isfinite(prm.lambda3) and abs(nm - prm.lambda3) < 1e-6:
-                out.near_tie[b] |= 2
-            with np.errstate(divide="ignore", invalid="ignore"):
-                if np.isfinite(prm.lambda1) and np.isfinite(h_t) and np.isfinite(h_d) and \
-                        abs(h_d - prm.lambda1 * h_t) < 1e-3 * abs(prm.lambda1 * h_t):
-                    out.near_tie[b] |= 2
-            if np.isfinite(prm.lambda2) and abs(abs(pt[y] - q[y]) - prm.lambda2) < 1e-3 * prm.lambda2:
-                out.near_tie[b] |= 2
+            out.tie_key[b, i - 1] = nm_tie or _key_tie(pt[y], q[y], h_t, h_d, prm)
         v = 0
         path: List[int] = []
         while True:
@@ -519,11 +551,10 @@ def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: n
             for c in children.get(v, []):
                 y = int(draft_tokens[b, c - 1])
                 u = F64(uniforms[b, c])
-                acc = bool(u * q[y] < p[y])
+                acc = _forced(force_accept, b, c, bool(u * q[y] < p[y]))
                 with np.errstate(divide="ignore", invalid="ignore"):
                     ratio = p[y] / q[y] if q[y] > 0 else (np.inf if p[y] > 0 else 0.0)
-                if abs(ratio - u) < 1e-3:
-                    out.near_tie[b] |= 1
+                out.tie_accept[b, c - 1] = abs(ratio - u) < TIE_RATIO
                 out.node_accept[b, c - 1] = acc
                 out.ratio[b, c - 1] = ratio
                 if acc:
@@ -545,9 +576,10 @@ def accept_lossless(logits: np.ndarray, draft_probs: np.ndarray, draft_tokens: n
         out.accepted_len[b] = a
         out.accepted_path[b, :a] = path
         tok, gap = inverse_cdf(p, F64(uniforms[b, 0]))
-        if gap < 1e-6:
-            out.near_tie[b] |= 4
+        out.tie_draw[b] = gap < TIE_CDF
         out.next_token[b] = tok
+        out.near_tie[b] = (1 if out.tie_accept[b].any() else 0) | (2 if out.tie_key[b].any() else 0) | \
+                          (4 if out.tie_draw[b] else 0)
     return out
 
 
@@ -566,11 +598,7 @@ def accept_greedy(logits: np.ndarray, draft_tokens: np.ndarray, parent: Sequence
     for i in range(1, k + 1):
         children.setdefault(parent[i - 1], []).append(i)
         depth[i] = depth[parent[i - 1]] + 1
-    out = AcceptOut(
-        accepted_len=np.zeros(B, dtype=np.int32), next_token=np.zeros(B, dtype=np.int32),
-        accepted_path=-np.ones((B, max(k, 1)), dtype=np.int32), key=np.zeros((B, k), dtype=bool),
-        node_accept=np.zeros((B, k), dtype=bool), tau_used=np.zeros((B, k)), ratio=np.zeros((B, k)),
-        norm_match=np.zeros((B, k)), near_tie=np.zeros(B, dtype=np.int32))
+    out = _new_out(B, k)
     for b in range(B):
         best = [int(np.argmax(logits[b, r])) for r in range(k + 1)]      # numpy: first of equal maxima
         acc = np.zeros(k + 1, dtype=bool)

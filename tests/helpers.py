@@ -125,23 +125,101 @@ def gpu_accept(ctx, logits: torch.Tensor, probs: torch.Tensor, tokens: np.ndarra
                 ratio=ratio.cpu().numpy(), norm_match=nm.cpu().numpy(), dev=(alen, nxt, path))
 
 
-def compare_accept(gpu: dict, ora, what: str):
-    """Integer outputs must be identical, except for sequences the oracle flags as near ties
-    (a decision within the stated distance of its threshold).  Returns (mismatching sequences that
-    were near ties, number of near-tie sequences)."""
-    B = len(ora.accepted_len)
-    excused = 0
+class AcceptInputs:
+    """What the oracle was called with, so that compare_accept can ask it what follows from a near-tie
+    decision falling the other way."""
+
+    def __init__(self, O, logits, probs, tokens, parent, uniforms, prm, tau_override=None):
+        self.O, self.logits, self.probs, self.tokens, self.parent = O, logits, probs, tokens, parent
+        self.uniforms, self.prm, self.tau_override = uniforms, prm, tau_override
+
+    def rerun(self, b, force_key, force_accept):
+        to = None if self.tau_override is None else np.asarray(self.tau_override, dtype=np.float64)[b:b + 1]
+        return self.O.accept(np.asarray(self.logits[b:b + 1], dtype=np.float64),
+                             np.asarray(self.probs[b:b + 1], dtype=np.float64), self.tokens[b:b + 1], self.parent,
+                             self.uniforms[b:b + 1], oracle_prm(self.O, self.prm), to, force_key=force_key,
+                             force_accept=force_accept)
+
+
+MAX_FLAGGED_NODE_FRACTION = 0.10      # of the B*k node decisions of a case with at least 50 of them
+
+
+def compare_accept(gpu: dict, ora, what: str, inputs: "AcceptInputs" = None, max_excused=None):
+    """Integer outputs against the oracle, decision by decision.
+
+    The rule.  Key flags, each node's own test, accepted length, path and the extra token must be
+    identical, except that ONE kind of difference is tolerated: a decision the oracle itself marks
+    as a near tie for exactly that node and that kind of decision --
+      key flag of node i      only if ora.tie_key[b, i]     (a key comparison within 1e-3 relative of
+                              its lambda, or the row's top-M boundary gap below 1e-5 relative);
+      node i's own test       only if ora.tie_accept[b, i]  (|P~(y)/q(y) - u_i| < 1e-3), or if node i's
+                              key flag differs under the rule above (its tau, hence its ratio, changed);
+      the extra token         only if ora.tie_draw[b]       (u_0 S within 1e-6 S of a CDF boundary).
+    Everything downstream of a tolerated difference (later decisions, path, length, which row the
+    token is drawn from) must then equal what the ORACLE computes when exactly those decisions are
+    pinned to the GPU's values (`inputs` re-runs it); nothing else about the sequence is excused.
+    Returns a dict of counts; asserts that the share of flagged node decisions stays below
+    MAX_FLAGGED_NODE_FRACTION (an over-eager flag would hollow the comparison out) and, if
+    max_excused is given, that no more than that many sequences needed the exception."""
+    B, k = ora.key.shape
+    width = gpu["accepted_path"].shape[1]
+    stats = dict(nodes=B * k, flagged_accept=int(ora.tie_accept.sum()), flagged_key=int(ora.tie_key.sum()),
+                 flagged_draw=int(ora.tie_draw.sum()), excused_sequences=0, excused=[])
+
+    def outputs_equal(g_b, o, ob, allow_draw_tie):
+        same = (g_b["accepted_len"] == o.accepted_len[ob] and
+                (g_b["accepted_path"] == o.accepted_path[ob][:width]).all() and
+                (g_b["key"] == o.key[ob]).all() and (g_b["node_accept"] == o.node_accept[ob]).all())
+        if same and g_b["next_token"] != o.next_token[ob]:
+            same = bool(allow_draw_tie and o.tie_draw[ob])
+        return bool(same)
+
     for b in range(B):
-        same = (gpu["accepted_len"][b] == ora.accepted_len[b] and gpu["next_token"][b] == ora.next_token[b]
-                and (gpu["accepted_path"][b] == ora.accepted_path[b][:gpu["accepted_path"].shape[1]]).all()
-                and (gpu["key"][b] == ora.key[b]).all() and (gpu["node_accept"][b] == ora.node_accept[b]).all())
-        if not same:
-            assert ora.near_tie[b] != 0, (
-                f"{what}: sequence {b} differs with no near tie: gpu len {gpu['accepted_len'][b]} tok "
-                f"{gpu['next_token'][b]} path {gpu['accepted_path'][b]} vs oracle len {ora.accepted_len[b]} tok "
-                f"{ora.next_token[b]} path {ora.accepted_path[b]}")
-            excused += 1
-    return excused, int((ora.near_tie != 0).sum())
+        g_b = {n: gpu[n][b] for n in ("accepted_len", "next_token", "accepted_path", "key", "node_accept")}
+        if outputs_equal(g_b, ora, b, False):
+            continue
+        msg = (f"{what}: sequence {b}: gpu len {g_b['accepted_len']} tok {g_b['next_token']} path "
+               f"{g_b['accepted_path'].tolist()} key {g_b['key'].astype(int).tolist()} acc "
+               f"{g_b['node_accept'].astype(int).tolist()} vs oracle len {ora.accepted_len[b]} tok {ora.next_token[b]} "
+               f"path {ora.accepted_path[b].tolist()} key {ora.key[b].astype(int).tolist()} acc "
+               f"{ora.node_accept[b].astype(int).tolist()}")
+        if outputs_equal(g_b, ora, b, True):
+            stats["excused_sequences"] += 1
+            stats["excused"].append((b, "draw"))
+            continue
+        # which decisions differ, and is each of them flagged for its own kind
+        dkey = g_b["key"] != ora.key[b]
+        assert not (dkey & ~ora.tie_key[b]).any(), f"{msg}: key flag differs at a node without a key near tie"
+        assert inputs is not None, f"{msg}: decisions differ and the case gave no inputs to follow them up"
+        fk = np.where(dkey, g_b["key"].astype(np.int64), -1)[None, :]
+        # node tests: pin only nodes flagged as accept near ties whose outcome differs, one at a time (a
+        # node whose key flag flipped gets its new tau from the re-run by itself; in the lossless walk a
+        # pinned test changes which nodes are tried next)
+        fa = np.full((1, k), -1, dtype=np.int64)
+        re = inputs.rerun(b, fk, fa)
+        for _ in range(k + 1):
+            dacc = (g_b["node_accept"] != re.node_accept[0]) & (fa[0] < 0)
+            if not dacc.any():
+                break
+            i = int(np.nonzero(dacc)[0][0])
+            assert re.tie_accept[0, i], (f"{msg}: node {i + 1}'s test differs and its ratio {re.ratio[0, i]:.6g} is "
+                                          f"not within 1e-3 of its uniform")
+            fa[0, i] = int(g_b["node_accept"][i])
+            re = inputs.rerun(b, fk, fa)
+        assert outputs_equal(g_b, re, 0, True), (f"{msg}: differs from the oracle also with the near-tie decisions "
+                                                 f"(key {np.nonzero(dkey)[0].tolist()}, test {np.nonzero(fa[0] >= 0)[0].tolist()}) "
+                                                 f"pinned to the GPU's: oracle then gives len {re.accepted_len[0]} tok "
+                                                 f"{re.next_token[0]} path {re.accepted_path[0].tolist()}")
+        stats["excused_sequences"] += 1
+        stats["excused"].append((b, "key" if dkey.any() else "accept", np.nonzero(dkey)[0].tolist(),
+                                 np.nonzero(fa[0] >= 0)[0].tolist()))
+    flagged = stats["flagged_accept"] + stats["flagged_key"]
+    if B * k >= 50:
+        assert flagged <= MAX_FLAGGED_NODE_FRACTION * 2 * B * k, (
+            f"{what}: {flagged} of {2 * B * k} node decisions are flagged as near ties: the excuse is too wide")
+    if max_excused is not None:
+        assert stats["excused_sequences"] <= max_excused, f"{what}: excused {stats['excused']}"
+    return stats
 
 
 def oracle_prm(O, prm: dict):

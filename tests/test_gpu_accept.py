@@ -41,7 +41,8 @@ def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None):
                    None if tau_override is None else tau_override.astype(np.float64))
     g = H.gpu_accept(ctx, torch.from_numpy(lg).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm,
                      tau_override)
-    excused, near = H.compare_accept(g, ora, what)
+    st = H.compare_accept(g, ora, what, H.AcceptInputs(O, lg, q, toks, parent, u, prm, tau_override))
+    excused, near = st["excused_sequences"], st["flagged_accept"] + st["flagged_key"] + st["flagged_draw"]
     fin = np.isfinite(ora.ratio)
     # The reported ratios are fp64 over fp32 per-id terms: 1e-6 relative for the per-node rules.  In the
     # lossless walk a later sibling's p is a residual max(0, p - q) / Z; Z sums fp32 terms whose absolute

@@ -92,7 +92,8 @@ def test_c1_accept_matches_oracle_both_ways(c1):
             ora = O.accept(lg.astype(np.float64), c1["q"].astype(np.float64), c1["draft"], None, uu,
                            H.oracle_prm(O, prm))
             g = H.gpu_accept(ctx, torch.from_numpy(lg).to("cuda:0"), probs, c1["draft"], None, uu, prm)
-            H.compare_accept(g, ora, f"c1 accept ({name}, trial {trial})")
+            H.compare_accept(g, ora, f"c1 accept ({name}, trial {trial})",
+                             H.AcceptInputs(O, lg, c1["q"], c1["draft"], None, uu, prm))
             if trial == 1:
                 assert ora.accepted_len[0] == k
 

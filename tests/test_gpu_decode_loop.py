@@ -60,7 +60,7 @@ def test_decode_loop_rounds(tau, noise):
         lg_np = lg.cpu().numpy()
         ora = O.accept(lg_np.astype(np.float64), q.astype(np.float64), toks, None, u, H.oracle_prm(O, prm))
         g = H.gpu_accept(st.ctx, lg, torch.from_numpy(q).to("cuda:0"), toks, None, u, prm)
-        H.compare_accept(g, ora, f"round {r}")
+        H.compare_accept(g, ora, f"round {r}", H.AcceptInputs(O, lg_np, q, toks, None, u, prm))
         a = ora.accepted_len.astype(np.int64)     # go on from the oracle's decisions (identical unless a near tie)
         # --- commit the pending token's row and the accepted ones (a chain: the first a+1 rows)
         n_rows = torch.from_numpy((a + 1).astype(np.int32)).to("cuda:0")
