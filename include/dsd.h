@@ -23,6 +23,7 @@
 #ifndef DSD_H
 #define DSD_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -239,6 +240,14 @@ enum dsd_kernel_class {
 };
 int dsd_profile_enable(dsd_ctx* ctx, int on);
 int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launches);
+
+/* Diagnostics: what a bare stream over device memory reaches on this device, the yardstick for a pass that
+ * the paper's own argument (section 2.1, Fig. 1) makes memory bound.  buf: device, `bytes` long (a multiple
+ * of 32, at least 1 MiB, 16-byte aligned), contents irrelevant.  mode 0: one kernel reads all of it;
+ * mode 1: one kernel copies its first half onto its second half (bytes/2 read + bytes/2 written).
+ * Runs 2 untimed + `iters` timed launches on the context's stream, synchronises, and returns the
+ * average time of a launch in *ms_avg (host). */
+int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode, int iters, double* ms_avg);
 
 #ifdef __cplusplus
 }

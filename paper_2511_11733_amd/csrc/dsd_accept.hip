@@ -1,22 +1,27 @@
 // Acceptance loop of Algorithm 1 (lines 2-16) with the key-token rule and the softened target
 // of section 2.3, for B sequences at once.
 //
-// The vocabulary is cut into slices of SLICE ids; every vocabulary-wide quantity is reduced per
-// slice by one workgroup (wavefront shuffles + one LDS hop), the few per-slice partials are
-// merged by a small second kernel, and only those partials ever reach memory: no probability
-// row is materialised.  Every quantity that decides something by itself (a drafted token's own
-// probabilities, the accept test, all sums and cumulative sums) is fp64; the per-id terms of the
-// vocabulary-wide sums are evaluated in fp32 (relative error below 1e-6, independent between ids,
-// so that a sum over thousands of ids is good to about 1e-9) and accumulated in fp64.  The
-// integer outputs therefore follow an fp64 reference except within the near-tie bands the tests
-// state.
+// The logits rows and the draft rows are read ONCE, by slice_pass_kernel: one wavefront per slice of
+// SLICE ids of one row reduces everything the rule needs from the vocabulary to a few numbers --
+// the slice's share of the log-sum-exp, of Z~ = sum_v P_t(v)^(1-tau) q(v)^tau (the call has one tau;
+// a key token only chooses between Z~ and 1), and the slice's top-M candidates of both rows (NormMatch).
+// Only those partials reach memory: no probability row is materialised.  seq_kernel (one workgroup
+// per sequence) merges them per row, applies the key rule and the test u*q(y) < P(y) to every node,
+// walks the tree for the accepted path and says what the extra token is drawn from; that row is
+// then read a second time by draw_parts / draw_pick (inverse CDF in token-id order).
 //
-//   row_stats   per (sequence, row, slice): max and sum-exp of logits/T, top-M candidates of the
-//               logits row and of the draft row
-//   row_merge   per (sequence, row): log-sum-exp, NormMatch
-//   node_soft   per (sequence, node, slice): key test -> tau_i; partial of
-//               Z~ = sum_v P_t(v)^(1-tau_i) q(v)^tau_i   (skipped when tau_i = 0)
-//   decide      per sequence: every node's test u*q(y) < P(y), accepted path, what to draw from
+// Precision.  Every quantity that decides something by itself (a drafted token's own probabilities,
+// the accept test, all sums over slices and cumulative sums) is fp64.  The per-id terms of the
+// vocabulary-wide sums are fp32: the exponent (l/T - reference) log2(e) is formed with a two-float
+// constant so that its error is one rounding of the exponent itself (about 6e-8 of its magnitude,
+// independent between ids), the terms of a lane are added in four short fp32 chains and everything
+// above that in fp64; a sum over thousands of ids is then good to about 1e-8.  The integer outputs
+// therefore follow an fp64 reference except within the near-tie bands the tests state.
+//
+//   slice_pass  per (sequence, row, slice): max, sum-exp and Z~ share, top-M candidates of both rows
+//   seq         per sequence: rows' log-sum-exp, Z~, NormMatch; key test and accept test of every
+//               node; accepted path; what to draw from
+//   node_z      only with tau_override (a tau per node): per (sequence, node, slice) share of that node's Z~
 //   draw_parts  per (sequence, slice): partial mass of the distribution the extra token comes from
 //   draw_pick   per sequence: inverse CDF in token-id order
 #include "dsd_internal.h"
@@ -113,55 +118,64 @@ __device__ inline unsigned order_u32(float v) {
     const unsigned u = __float_as_uint(v);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
-// One selection round of a wave over o[j] = order_u32 of id base + threadIdx.x + j*TPB (0 = not a
-// candidate): finds the largest value, the lowest id among its holders, clears it there and returns
-// its rank_key to every lane (0 when nothing is left).
-__device__ inline u64 select_round(unsigned (&o)[EPT], int base, int lane) {
-    unsigned best = 0;
+
+// ---------------------------------------------------------------------------- wave-level tools
+// 64 values, one per lane, sorted across the lanes (bitonic network, 21 exchange steps): descending,
+// lane 0 ends up with the largest.  NaNs behave as fminf / fmaxf treat them.
+__device__ inline float wave_sort_desc_f(float v, int lane) {
 #pragma unroll
-    for (int j = 0; j < EPT; ++j) best = o[j] > best ? o[j] : best;
-    unsigned top = best;
+    for (int k = 2; k <= WAVE; k <<= 1)
 #pragma unroll
-    for (int s = 32; s > 0; s >>= 1) {
-        const unsigned t = __shfl_xor(top, s, WAVE);
-        top = t > top ? t : top;
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const float o = __shfl_xor(v, j, WAVE);
+            const bool desc = (lane & k) == 0, lower = (lane & j) == 0;
+            v = (lower == desc) ? fmaxf(v, o) : fminf(v, o);
+        }
+    return v;
+}
+__device__ inline u64 wave_sort_desc_u(u64 v, int lane) {
+#pragma unroll
+    for (int k = 2; k <= WAVE; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const u64 o = __shfl_xor(v, j, WAVE);
+            const bool desc = (lane & k) == 0, lower = (lane & j) == 0;
+            const u64 hi = v > o ? v : o, lo = v > o ? o : v;
+            v = (lower == desc) ? hi : lo;
+        }
+    return v;
+}
+__device__ inline float wave_max_f(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+// exclusive prefix sum of a small count over the lanes, and the wave's total
+__device__ inline int wave_excl_scan(int v, int lane, int* total) {
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        const int t = __shfl_up(inc, o, WAVE);
+        if (lane >= o) inc += t;
     }
-    if (top == 0) return 0ull;                        // wave-uniform
-    int my_j = EPT;
-#pragma unroll
-    for (int j = EPT - 1; j >= 0; --j) my_j = o[j] == top ? j : my_j;
-    const unsigned long long holders = __ballot(my_j < EPT);
-    int win = __ffsll((long long)holders) - 1;
-    if (__popcll(holders) > 1) {                      // rare: equal values in several lanes
-        int key = my_j < EPT ? (my_j << 6) | lane : 0x7FFFFFFF;
-#pragma unroll
-        for (int s = 32; s > 0; s >>= 1) key = min(key, __shfl_xor(key, s, WAVE));
-        win = key & 63;
-    }
-    const int win_j = __shfl(my_j, win, WAVE);
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) o[j] = (lane == win && j == win_j) ? 0u : o[j];
-    const int id = base + (int)(threadIdx.x - lane) + win + win_j * TPB;
-    return ((u64)top << 32) | (u64)(0xFFFFFFFFu - (unsigned)id);
+    *total = __shfl(inc, WAVE - 1, WAVE);
+    return inc - v;
 }
 
 struct AcceptWs {
-    double* part_m;     // [B][R][S]
-    double* part_s;     // [B][R][S]
-    u64* part_top_t;    // [B][R][S][MAXM]
-    u64* part_top_q;    // [B][R][S][MAXM]
-    double* row_lse;    // [B][R]
+    float* part_m;      // [B][R][S]   reference exponent of the slice: (max logit / T) log2 e, as one float
+    double* part_s;     // [B][R][S]   sum_v 2^(x_v - part_m),  x_v = (l_v / T) log2 e
+    double* part_zs;    // [B][R][S]   sum_v 2^((1-tau)(x_v - part_m)) q_v^tau   (rows with children, call-wide tau > 0)
+    u64* part_top_t;    // [B][R][S][top_m]   slice's top_m (value, id) keys of the logits row, best first, 0 = none
+    u64* part_top_q;    // [B][R][S][top_m]   the same of the draft row
+    double* row_lse;    // [B][R]  natural-log log-sum-exp of logits / T
+    double* row_z;      // [B][R]  Z~ of the row under the call-wide tau
     double* row_nm;     // [B][R]
     double* row_ht;     // [B][R]  Shannon entropy of the target row   (DSD_H_ROW)
     double* row_hd;     // [B][R]  Shannon entropy of the draft row    (DSD_H_ROW)
     double* part_x;     // [B][R][S][3] per-slice sum min(P_t, q), -sum P_t ln P_t, -sum q ln q
-    double* node_tau;   // [B][k]
-    double* node_lnpt;  // [B][k]  ln P_t(y)
-    double* node_q;     // [B][k]  q(y)
     int32_t* node_key;  // [B][k]
-    int32_t* node_acc;  // [B][k]  the node's own test
-    double* node_z;     // [B][k]  Z~ of the node's softened target
-    double* part_z;     // [B][k][S]
+    double* part_z;     // [B][k][S]  per-node Z~ shares (tau_override only)
     int32_t* draw_row;  // [B]
     int32_t* draw_mode; // [B] 0 = target row (bonus), 1 = positive part of P - q
     double* draw_tau;   // [B]
@@ -170,207 +184,157 @@ struct AcceptWs {
     double* part_fb;    // [B][S]  mass of P itself (used when the positive part is all zero)
 };
 
-__global__ void __launch_bounds__(TPB)
-row_stats_kernel(const float* __restrict__ logits, const float* __restrict__ qp, AcceptWs ws, int R, int V, int S,
-                 double inv_temp, int top_m) {
-    __shared__ double shd[TPB / WAVE];
-    __shared__ u64 sh_top[2][TPB / WAVE][MAXM];
-    const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
-    const size_t row = ((size_t)b * R + r) * V;
-    const int base = s * SLICE;
-    float lv[EPT], qv[EPT];
-    double mx = -INFINITY;
+// What one pass over the rows has to know about the call.
+struct SliceArgs {
+    const float* logits;
+    const float* qp;
+    const int32_t* parent;   // [k] or NULL
+    int k, V, S, top_m;
+    float c_hi, c_lo;        // log2(e) / T as a two-float sum
+    float a_hi, a_lo;        // 1 - tau as a two-float sum
+    float t_hi, t_lo;        // tau as a two-float sum
+    int soft;                // 1: accumulate the Z~ share (call-wide tau in (0, 1], no per-node override)
+    int tau_is_one;          // the Z~ share is sum q
+    int want_top;            // 1: top_m candidates wanted (the top-M reading of NormMatch)
+};
+
+#define EPL (SLICE / WAVE)       // ids per lane of a slice
+// id of element j of a lane: with 16-byte loads a lane takes 4 consecutive ids of each 256-id piece
+template <bool VEC>
+__device__ __forceinline__ int slice_id(int base, int lane, int j) {
+    return VEC ? base + (j >> 2) * (4 * WAVE) + lane * 4 + (j & 3) : base + j * WAVE + lane;
+}
+template <bool VEC>
+__device__ __forceinline__ void slice_load(const float* __restrict__ row, int base, int V, int lane, float (&v)[EPL], float fill) {
+    if (VEC) {      // row start and V are multiples of 4 ids: a 16-byte piece lies inside the row or outside
 #pragma unroll
-    for (int j = 0; j < EPT; ++j) {
-        const int i = base + threadIdx.x + j * TPB;
-        const bool in = i < V;
-        lv[j] = in ? logits[row + i] : -INFINITY;
-        qv[j] = in ? qp[row + i] : -INFINITY;
-        if (in) mx = fmax(mx, (double)lv[j] * inv_temp);
-    }
-    mx = block_max_d(mx, shd);
-    float fsum = 0.f;
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) {
-        const int i = base + threadIdx.x + j * TPB;
-        if (i < V) fsum += expf((float)((double)lv[j] * inv_temp - mx));
-    }
-    double sum = block_sum_d((double)fsum, shd);
-    const size_t pidx = ((size_t)b * R + r) * S + s;
-    if (threadIdx.x == 0) {
-        ws.part_m[pidx] = mx;
-        ws.part_s[pidx] = sum;
-    }
-    // top_m candidates of this slice, for the logits row (a = 0) and for the draft row (a = 1), on
-    // the 32-bit order-preserving image of the values (0 = out of range), ties to the lowest id.
-    // A threshold first: the slice is 16 groups of 16 lanes x 8 ids, and the top_m-th largest of
-    // the 16 group maxima cannot exceed the slice's top_m-th largest value (the maxima are top_m
-    // different ids at least that large), so everything that can be among the top_m lies at or
-    // above it.  Usually a dozen ids pass; they go to a list in LDS and one wave per row kind picks
-    // the top_m of them.  If more than 64 pass (many equal values), the slice falls back to
-    // selection rounds over all ids.
-    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
-    __shared__ unsigned sh_gm[2][16];
-    __shared__ int sh_n[2];
-    __shared__ u64 sh_cand[2][64];
-    unsigned ot[EPT], oq[EPT];
-    unsigned gt = 0u, gq = 0u;
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) {
-        const int i = base + threadIdx.x + j * TPB;
-        ot[j] = i < V ? order_u32(lv[j]) : 0u;
-        oq[j] = i < V ? order_u32(qv[j]) : 0u;
-        gt = ot[j] > gt ? ot[j] : gt;
-        gq = oq[j] > gq ? oq[j] : gq;
-    }
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) {
-        const unsigned t = __shfl_xor(gt, o, WAVE), q = __shfl_xor(gq, o, WAVE);
-        gt = t > gt ? t : gt;
-        gq = q > gq ? q : gq;
-    }
-    if ((lane & 15) == 0) {
-        sh_gm[0][wave * 4 + (lane >> 4)] = gt;
-        sh_gm[1][wave * 4 + (lane >> 4)] = gq;
-    }
-    if (threadIdx.x < 2) sh_n[threadIdx.x] = 0;
-    __syncthreads();
-    unsigned thr[2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        // rank of group maximum (lane & 15) among the 16, equal values in index order
-        const unsigned mine = sh_gm[a][lane & 15];
-        int rank = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const unsigned other = sh_gm[a][i];
-            rank += (other > mine || (other == mine && i < (lane & 15))) ? 1 : 0;
+        for (int jj = 0; jj < EPL / 4; ++jj) {
+            const int id0 = base + jj * (4 * WAVE) + lane * 4;
+            float4 x = make_float4(fill, fill, fill, fill);
+            if (id0 < V) x = *(const float4*)(row + id0);
+            v[jj * 4] = x.x; v[jj * 4 + 1] = x.y; v[jj * 4 + 2] = x.z; v[jj * 4 + 3] = x.w;
         }
-        const unsigned long long holder = __ballot(rank == top_m - 1);      // one lane in each group of 16
-        thr[a] = __shfl(mine, __ffsll((long long)holder) - 1, WAVE);
-    }
+    } else {
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        const unsigned (&o)[EPT] = a ? oq : ot;
-        unsigned long long mask[EPT];
-        int cnt = 0;
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-            mask[j] = __ballot(o[j] != 0u && o[j] >= thr[a]);
-            cnt += __popcll(mask[j]);
-        }
-        int at = 0;
-        if (lane == 0) at = atomicAdd(&sh_n[a], cnt);
-        at = __shfl(at, 0, WAVE);
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-            const int pos = at + __popcll(mask[j] & ((1ull << lane) - 1ull));
-            if (((mask[j] >> lane) & 1ull) && pos < 64) {
-                const int id = base + threadIdx.x + j * TPB;
-                sh_cand[a][pos] = ((u64)o[j] << 32) | (u64)(0xFFFFFFFFu - (unsigned)id);
-            }
-            at += __popcll(mask[j]);
-        }
-    }
-    __syncthreads();
-    const int n_t = sh_n[0], n_q = sh_n[1];
-    u64* out_t = ws.part_top_t + pidx * MAXM;
-    u64* out_q = ws.part_top_q + pidx * MAXM;
-    if (wave < 2) {
-        const int n = wave ? n_q : n_t;
-        if (n <= 64) {
-            u64 c = lane < n ? sh_cand[wave][lane] : 0ull;
-            u64* out = wave ? out_q : out_t;
-            for (int round = 0; round < top_m; ++round) {
-                const u64 w = wave_max_u(c);                  // 0 when the slice ran out of ids
-                c = c == w ? 0ull : c;
-                if (lane == 0) out[round] = w;
-            }
-        }
-    }
-    if (n_t <= 64 && n_q <= 64) return;                        // block-uniform
-    // Fallback.  Every wave selects among its own 512 ids, without barriers: top_m rounds of a
-    // wave-wide maximum; among equal values the lowest id wins, which inside a wave is the lowest j,
-    // then the lowest lane.  Wave 0 then merges the 4 lists (at most 64 candidates: one per lane) on
-    // the full (value, id) keys.
-    const bool redo_t = n_t > 64, redo_q = n_q > 64;
-    for (int round = 0; round < top_m; ++round) {
-        const u64 wt = redo_t ? select_round(ot, base, lane) : 0ull, wq = redo_q ? select_round(oq, base, lane) : 0ull;
-        if (lane == 0) {
-            sh_top[0][wave][round] = wt;
-            sh_top[1][wave][round] = wq;
-        }
-    }
-    __syncthreads();
-    if (wave == 0) {
-        const int w = lane / MAXM, r = lane % MAXM;          // TPB/WAVE * MAXM = 64 candidates
-        u64 ct = r < top_m ? sh_top[0][w][r] : 0ull, cq = r < top_m ? sh_top[1][w][r] : 0ull;
-        for (int round = 0; round < top_m; ++round) {
-            const u64 wt = wave_max_u(ct), wq = wave_max_u(cq);   // 0 when the slice ran out of ids
-            ct = ct == wt ? 0ull : ct;
-            cq = cq == wq ? 0ull : cq;
-            if (lane == 0) {
-                if (redo_t) out_t[round] = wt;
-                if (redo_q) out_q[round] = wq;
-            }
+        for (int j = 0; j < EPL; ++j) {
+            const int id = base + j * WAVE + lane;
+            v[j] = id < V ? row[id] : fill;
         }
     }
 }
 
-// cand_lds = 1: the 2 * S * top_m candidates of the row fit the dynamic LDS and are read from memory once
-__global__ void __launch_bounds__(WAVE)
-row_merge_kernel(AcceptWs ws, int R, int S, int top_m, int cand_lds) {
-    extern __shared__ u64 sh_cand[];                  // [2][S*top_m] when cand_lds
-    const int r = blockIdx.x, b = blockIdx.y;
-    const int lane = threadIdx.x;
-    const size_t ridx = (size_t)b * R + r;
-    double m = -INFINITY;
-    for (int s = lane; s < S; s += WAVE) m = fmax(m, ws.part_m[ridx * S + s]);
-    m = wave_max_d(m);
-    double sum = 0.0;
-    for (int s = lane; s < S; s += WAVE) sum += ws.part_s[ridx * S + s] * exp(ws.part_m[ridx * S + s] - m);
-    sum = wave_sum_d(sum);
-    // merge the per-slice candidate lists: top_m rounds of a wave-wide maximum; keys are distinct, so
-    // each round selects strictly below the previous winner
-    const u64* gt = ws.part_top_t + ridx * S * MAXM;
-    const u64* gq = ws.part_top_q + ridx * S * MAXM;
-    const int n = S * top_m;
-    if (cand_lds) {
-        for (int i = lane; i < n; i += WAVE) {
-            const int src = (i / top_m) * MAXM + i % top_m;
-            sh_cand[i] = gt[src];
-            sh_cand[n + i] = gq[src];
+// The slice's top_m of one row, best first, to out[0..top_m) (0 = the slice ran out of ids).
+// Threshold first: the top_m-th largest of the 64 lane maxima cannot exceed the slice's top_m-th
+// largest value (the maxima are top_m different ids at least that large), so everything that can be
+// among the top_m lies at or above it; usually a dozen ids pass.  They go to a list in LDS, one per
+// lane, and a sort across the lanes on the full (value, id) keys puts the winners into lanes
+// 0..top_m-1; equal values go to the lower id.  If more than 64 ids pass (many equal values), top_m
+// rounds of a wave-wide maximum over all ids of the slice instead.
+template <bool VEC>
+__device__ inline void slice_top_m(const float (&v)[EPL], int base, int V, int lane, int top_m, u64* __restrict__ cand,
+                                   u64* __restrict__ out) {
+    float lm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < EPL; ++j)
+        if (slice_id<VEC>(base, lane, j) < V) lm = fmaxf(lm, v[j]);
+    const float sorted = wave_sort_desc_f(lm, lane);
+    const float thr = __shfl(sorted, top_m - 1, WAVE);
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) cnt += (slice_id<VEC>(base, lane, j) < V && v[j] >= thr) ? 1 : 0;
+    int total;
+    int pos = wave_excl_scan(cnt, lane, &total);
+    if (total <= WAVE) {                                  // wave-uniform
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int id = slice_id<VEC>(base, lane, j);
+            if (id < V && v[j] >= thr) cand[pos++] = rank_key(v[j], id);
         }
-        __syncthreads();
+        __syncthreads();                                  // the workgroup is this one wave; branch is wave-uniform
+        u64 c = lane < total ? cand[lane] : 0ull;
+        c = wave_sort_desc_u(c, lane);
+        if (lane < top_m) out[lane] = c;
+        __syncthreads();                                  // the list is rewritten by the next call
+        return;
     }
-    int idt[MAXM], idq[MAXM];
-    u64 last_t = ~0ull, last_q = ~0ull;
+    u64 last = ~0ull;
     for (int round = 0; round < top_m; ++round) {
-        u64 bt = 0, bq = 0;
-        for (int i = lane; i < n; i += WAVE) {
-            u64 a, c;
-            if (cand_lds) {
-                a = sh_cand[i];
-                c = sh_cand[n + i];
-            } else {
-                const int src = (i / top_m) * MAXM + i % top_m;
-                a = gt[src];
-                c = gq[src];
-            }
-            if (a < last_t && a > bt) bt = a;
-            if (c < last_q && c > bq) bq = c;
+        u64 best = 0ull;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int id = slice_id<VEC>(base, lane, j);
+            const u64 key = id < V ? rank_key(v[j], id) : 0ull;
+            best = (key < last && key > best) ? key : best;
         }
-        last_t = wave_max_u(bt);
-        last_q = wave_max_u(bq);
-        idt[round] = key_id(last_t);
-        idq[round] = key_id(last_q);
+        last = wave_max_u(best);
+        if (lane == 0) out[round] = last;
+        if (last == 0ull) last = 1ull;                    // nothing left: the remaining rounds store 0
     }
+}
+
+// One wavefront per (slice, row, sequence).
+template <bool VEC>
+__global__ void __launch_bounds__(WAVE) slice_pass_kernel(SliceArgs p, AcceptWs ws) {
+    __shared__ u64 cand[WAVE];
+    const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+    const int R = p.k + 1;
+    // does any node hang under this row?  (parents precede children: only nodes r+1.. can)
+    bool has_child = false;
+    for (int c = r + 1; c <= p.k; ++c) {
+        int par = p.parent ? p.parent[c - 1] : c - 1;
+        par = par < 0 ? 0 : (par > c - 1 ? c - 1 : par);
+        has_child = has_child || par == r;
+    }
+    const size_t row = ((size_t)b * R + r) * p.V;
+    const int base = s * SLICE;
+    const size_t pidx = ((size_t)b * R + r) * p.S + s;
+    float lv[EPL];
+    slice_load<VEC>(p.logits + row, base, p.V, lane, lv, -INFINITY);
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) lmax = fmaxf(lmax, lv[j]);
+    lmax = wave_max_f(lmax);
+    const float mref = lmax * p.c_hi;                     // one rounding; the merge uses this very float
+    const bool live = lmax > -INFINITY && lmax < INFINITY;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f}, zacc[4] = {0.f, 0.f, 0.f, 0.f};
+    float x[EPL];                                         // x_v - mref
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+        // -inf logits (masked ids, ids past V) give weight 0; keep them out of the two-float product
+        const float l = fmaxf(lv[j], -3.0e38f);
+        const float d = fmaf(l, p.c_hi, -mref);
+        x[j] = live ? fmaf(l, p.c_lo, d) : -INFINITY;
+        acc[j & 3] += __builtin_amdgcn_exp2f(x[j]);
+    }
+    double sum = ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);
+    sum = wave_sum_d(sum);
     if (lane == 0) {
-        int common = 0;
-        for (int i = 0; i < top_m; ++i)
-            for (int j = 0; j < top_m; ++j) common += (idt[i] == idq[j]) ? 1 : 0;
-        ws.row_lse[ridx] = m + log(sum);
-        ws.row_nm[ridx] = (double)common / (double)top_m;
+        ws.part_m[pidx] = live ? mref : -INFINITY;
+        ws.part_s[pidx] = sum;
+    }
+    if (!has_child) return;                               // a leaf's draft row is never read
+    float qv[EPL];
+    slice_load<VEC>(p.qp + row, base, p.V, lane, qv, 0.f);
+    if (p.soft) {
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            float t;
+            if (p.tau_is_one) {
+                t = slice_id<VEC>(base, lane, j) < p.V ? fmaxf(qv[j], 0.f) : 0.f;     // P_t^0 = 1 for every id
+            } else {
+                const float lq = log2f(qv[j]);            // -inf for q = 0: weight 0
+                const float e = fmaf(p.a_hi, x[j], fmaf(p.t_hi, lq, fmaf(p.a_lo, x[j], p.t_lo * lq)));
+                t = (qv[j] > 0.f && x[j] > -INFINITY) ? __builtin_amdgcn_exp2f(e) : 0.f;
+            }
+            zacc[j & 3] += t;
+        }
+        double z = ((double)zacc[0] + (double)zacc[1]) + ((double)zacc[2] + (double)zacc[3]);
+        z = wave_sum_d(z);
+        if (lane == 0) ws.part_zs[pidx] = z;
+    }
+    if (p.want_top) {
+        slice_top_m<VEC>(lv, base, p.V, lane, p.top_m, cand, ws.part_top_t + pidx * p.top_m);
+        slice_top_m<VEC>(qv, base, p.V, lane, p.top_m, cand, ws.part_top_q + pidx * p.top_m);
     }
 }
 
@@ -425,41 +389,21 @@ row_extra_merge_kernel(AcceptWs ws, int R, int S, int overlap_is_norm_match) {
     }
 }
 
+// Only with tau_override: node i's own Z~ = sum_v P_t(v)^(1-tau_i) q(v)^tau_i, per slice (skipped for tau_i = 0).
 __global__ void __launch_bounds__(TPB)
-node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const int32_t* __restrict__ tokens,
-                 const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params prm, int k, int V, int S,
-                 double inv_temp) {
+node_z_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const int32_t* __restrict__ parent,
+              const float* __restrict__ tau_override, AcceptWs ws, int k, int V, int S, double inv_temp) {
     __shared__ double shd[TPB / WAVE];
     const int s = blockIdx.x, node = blockIdx.y + 1, b = blockIdx.z;
     const int R = k + 1;
     int p = parent ? parent[node - 1] : node - 1;
     p = p < 0 ? 0 : (p > node - 1 ? node - 1 : p);
-    int y = tokens[(size_t)b * k + node - 1];
-    y = y < 0 ? 0 : (y >= V ? V - 1 : y);
+    const size_t nidx = (size_t)b * k + node - 1;
+    double tau = (double)tau_override[nidx];
+    tau = tau < 0.0 ? 0.0 : (tau > 1.0 ? 1.0 : tau);
+    if (tau == 0.0) return;     // P~ = P_t, Z~ = 1
     const size_t row = ((size_t)b * R + p) * V;
     const double lse = ws.row_lse[(size_t)b * R + p];
-    const double ln_pt = (double)logits[row + y] * inv_temp - lse;
-    const double pt_y = exp(ln_pt);
-    const double q_y = (double)qp[row + y];
-    // key-token rule: any of the three criteria
-    double h_t = -ln_pt, h_d = -log(q_y);
-    if (prm.entropy_kind == DSD_H_ROW) {
-        h_t = ws.row_ht[(size_t)b * R + p];
-        h_d = ws.row_hd[(size_t)b * R + p];
-    }
-    const bool key = (h_d > prm.lambda1 * h_t) || (fabs(pt_y - q_y) > prm.lambda2) ||
-                     (ws.row_nm[(size_t)b * R + p] < prm.lambda3);
-    double tau = key ? 0.0 : prm.tau;
-    if (prm.tau_override) tau = (double)prm.tau_override[(size_t)b * k + node - 1];
-    tau = tau < 0.0 ? 0.0 : (tau > 1.0 ? 1.0 : tau);
-    const size_t nidx = (size_t)b * k + node - 1;
-    if (s == 0 && threadIdx.x == 0) {
-        ws.node_tau[nidx] = tau;
-        ws.node_lnpt[nidx] = ln_pt;
-        ws.node_q[nidx] = q_y;
-        ws.node_key[nidx] = key ? 1 : 0;
-    }
-    if (tau == 0.0) return;     // P~ = P_t, Z~ = 1
     float fz = 0.f;
     const int base = s * SLICE;
     const float ftau = (float)tau;
@@ -472,72 +416,186 @@ node_soft_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     if (threadIdx.x == 0) ws.part_z[nidx * S + s] = z;
 }
 
-// One wavefront per (sequence, node): Z~ of the node's softened target from the slice partials, the
-// node's test u * q(y) < P~(y), and the optional statistics.
-__global__ void __launch_bounds__(WAVE)
-node_accept_kernel(const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws, int k, int S,
-                   dsd_accept_stats st) {
-    const int i = blockIdx.x + 1, b = blockIdx.y;
-    const int lane = threadIdx.x;
-    const int R = k + 1;
-    int p = parent ? parent[i - 1] : i - 1;
-    p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
-    const size_t nidx = (size_t)b * k + i - 1;
-    const double tau = ws.node_tau[nidx];
-    double z = 1.0;
-    if (tau != 0.0) {
-        z = 0.0;
-        for (int s = lane; s < S; s += WAVE) z += ws.part_z[nidx * S + s];
-        z = wave_sum_d(z);
+// The top_m best of n_lists lists of top_m keys each (every list best first, 0 = none), by one wave.
+// Lane l holds list l in registers; a round takes the wave-wide maximum of the heads and the winner
+// shifts its list (keys are distinct: they carry the id).  More than 63 lists go through in groups,
+// lane 63 carrying the best of the groups before.  ids[0..top_m) to every lane (-1 = none).
+__device__ inline void merge_top_lists(const u64* __restrict__ lists, int n_lists, int top_m, int lane, int (&ids)[MAXM]) {
+    u64 best[MAXM];
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) best[i] = 0ull;
+    for (int g0 = 0; g0 < n_lists; g0 += WAVE - 1) {
+        u64 c[MAXM];
+#pragma unroll
+        for (int i = 0; i < MAXM; ++i) {
+            u64 v = 0ull;
+            if (lane < WAVE - 1 && g0 + lane < n_lists && i < top_m) v = lists[(size_t)(g0 + lane) * top_m + i];
+            c[i] = lane == WAVE - 1 ? best[i] : v;
+        }
+#pragma unroll
+        for (int round = 0; round < MAXM; ++round) {
+            if (round < top_m) {
+                const u64 w = wave_max_u(c[0]);
+                best[round] = w;
+                const bool mine = w != 0ull && c[0] == w;
+#pragma unroll
+                for (int i = 0; i < MAXM - 1; ++i) c[i] = mine ? c[i + 1] : c[i];
+                c[MAXM - 1] = mine ? 0ull : c[MAXM - 1];
+            }
+        }
     }
-    if (lane != 0) return;
-    const double q_y = ws.node_q[nidx];
-    const double p_y = soft_weight(ws.node_lnpt[nidx], q_y, tau) / z;
-    const double u = (double)uniforms[(size_t)b * R + i];
-    const bool acc = u * q_y < p_y;
-    ws.node_z[nidx] = z;
-    ws.node_acc[nidx] = acc ? 1 : 0;
-    if (st.key_flags) st.key_flags[nidx] = ws.node_key[nidx];
-    if (st.node_accept) st.node_accept[nidx] = acc ? 1 : 0;
-    if (st.ratio) st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
-    if (st.norm_match) st.norm_match[nidx] = ws.row_nm[(size_t)b * R + p];
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) ids[i] = best[i] != 0ull ? key_id(best[i]) : -1;
 }
 
-// One workgroup per sequence: thread i = node i (0 = the root) walks up to the root for its depth and
-// for whether it and all its ancestors passed their tests; thread 0 then picks the accepted path and
-// what the extra token is drawn from.  The tree lives in LDS.
+struct SeqArgs {
+    const float* logits;
+    const float* qp;
+    const int32_t* tokens;
+    const int32_t* parent;
+    const float* uniforms;
+    dsd_accept_params prm;
+    int k, V, S;
+    double c;                // log2(e) / T exactly as slice_pass used it: (double)c_hi + (double)c_lo
+    int soft;                // slice_pass accumulated Z~ shares for the call-wide tau
+    int want_top;
+    int do_rows, do_nodes;   // phases (both in one launch unless another kernel has to run in between)
+    int walk;                // 0: lossless mode -- key flags only; the walk kernel does the rest
+    int32_t* accepted_len;
+    int32_t* accepted_path;
+    dsd_accept_stats st;
+};
+
+// One workgroup per sequence.
+//   rows:  wave w takes rows w, w+16, ...: log-sum-exp from the slice partials, Z~ of the row under
+//          the call-wide tau, NormMatch from the slices' candidate lists;
+//   nodes: thread i-1 takes node i: key rule, tau_i, P(y), the test u q(y) < P(y), statistics;
+//          then the tree walk for the accepted path and what the extra token is drawn from.
+#define SEQ_TPB 512
 #define DECIDE_TPB 128
-__global__ void __launch_bounds__(DECIDE_TPB)
-decide_kernel(const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params prm, int k,
-              int32_t* __restrict__ accepted_len, int32_t* __restrict__ accepted_path) {
+__global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
     __shared__ int par[DSD_MAX_K + 1], acc[DSD_MAX_K + 1], dep[DSD_MAX_K + 1], ok[DSD_MAX_K + 1];
-    const int b = blockIdx.x;
-    const int i = threadIdx.x;
-    if (i <= k) {
-        int p = 0, a = 1;
-        if (i > 0) {
-            p = parent ? parent[i - 1] : i - 1;
-            p = p < 0 ? 0 : (p > i - 1 ? i - 1 : p);
-            a = ws.node_acc[(size_t)b * k + i - 1] != 0;
+    __shared__ double s_tau[DSD_MAX_K + 1], s_z[DSD_MAX_K + 1];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int k = p.k, R = k + 1, S = p.S;
+    if (tid <= k) {
+        int pr = 0;
+        if (tid > 0) {
+            pr = p.parent ? p.parent[tid - 1] : tid - 1;
+            pr = pr < 0 ? 0 : (pr > tid - 1 ? tid - 1 : pr);
         }
-        par[i] = p;
-        acc[i] = a;
+        par[tid] = pr;
     }
-    if (accepted_path && i < k) accepted_path[(size_t)b * k + i] = -1;
     __syncthreads();
-    if (i <= k) {
-        int d = 0, good = acc[i];
-        for (int n = i; n != 0; n = par[n]) {        // parents precede children: at most k steps
+    if (p.do_rows) {
+        for (int r = wave; r < R; r += SEQ_TPB / WAVE) {
+            const size_t ridx = (size_t)b * R + r;
+            float mf = -INFINITY;
+            for (int s = lane; s < S; s += WAVE) mf = fmaxf(mf, ws.part_m[ridx * S + s]);
+            mf = wave_max_f(mf);
+            const double m = (double)mf;
+            double sum = 0.0;
+            for (int s = lane; s < S; s += WAVE) {
+                const float ms = ws.part_m[ridx * S + s];
+                if (ms > -INFINITY) sum += ws.part_s[ridx * S + s] * exp2((double)ms - m);
+            }
+            sum = wave_sum_d(sum);
+            const double lse2 = m + log2(sum);            // log2 of sum_v 2^(x_v)
+            bool has_child = false;
+            for (int c = r + 1; c <= k; ++c) has_child = has_child || par[c] == r;
+            double z = 1.0, nm = 0.0;
+            if (has_child && p.soft) {
+                const double a = 1.0 - p.prm.tau;
+                z = 0.0;
+                for (int s = lane; s < S; s += WAVE) {
+                    const float ms = ws.part_m[ridx * S + s];
+                    if (ms > -INFINITY) z += ws.part_zs[ridx * S + s] * (a == 0.0 ? 1.0 : exp2(a * ((double)ms - lse2)));
+                }
+                z = wave_sum_d(z);
+            }
+            if (has_child && p.want_top) {
+                int idt[MAXM], idq[MAXM];
+                merge_top_lists(ws.part_top_t + ridx * S * p.prm.top_m, S, p.prm.top_m, lane, idt);
+                merge_top_lists(ws.part_top_q + ridx * S * p.prm.top_m, S, p.prm.top_m, lane, idq);
+                int mine = -2;
+#pragma unroll
+                for (int i = 0; i < MAXM; ++i) mine = (lane == i && i < p.prm.top_m) ? idt[i] : mine;
+                bool hit = false;
+#pragma unroll
+                for (int j = 0; j < MAXM; ++j) hit = hit || (j < p.prm.top_m && idq[j] >= 0 && idq[j] == mine);
+                nm = (double)__popcll(__ballot(hit)) / (double)p.prm.top_m;
+            }
+            if (lane == 0) {
+                ws.row_lse[ridx] = lse2 * 0.6931471805599453094;      // natural log
+                ws.row_z[ridx] = z;
+                if (p.want_top) ws.row_nm[ridx] = nm;
+            }
+        }
+    }
+    if (!p.do_nodes) return;
+    // rows written above are read below by other threads of this workgroup
+    __threadfence_block();
+    __syncthreads();
+    if (tid >= 1 && tid <= k) {
+        const int i = tid, pr = par[i];
+        const size_t nidx = (size_t)b * k + i - 1, ridx = (size_t)b * R + pr;
+        int y = p.tokens[nidx];
+        y = y < 0 ? 0 : (y >= p.V ? p.V - 1 : y);
+        const size_t row = ridx * p.V;
+        const double lse = ws.row_lse[ridx];
+        const double ln_pt = (double)p.logits[row + y] * p.c * 0.6931471805599453094 - lse;
+        const double pt_y = exp(ln_pt);
+        const double q_y = (double)p.qp[row + y];
+        const double nm = ws.row_nm[ridx];
+        // key-token rule: any of the three criteria
+        double h_t = -ln_pt, h_d = -log(q_y);
+        if (p.prm.entropy_kind == DSD_H_ROW) {
+            h_t = ws.row_ht[ridx];
+            h_d = ws.row_hd[ridx];
+        }
+        const bool key = (h_d > p.prm.lambda1 * h_t) || (fabs(pt_y - q_y) > p.prm.lambda2) || (nm < p.prm.lambda3);
+        double tau = key ? 0.0 : p.prm.tau;
+        double z = (tau == 0.0) ? 1.0 : ws.row_z[ridx];
+        if (p.prm.tau_override) {
+            tau = (double)p.prm.tau_override[nidx];
+            tau = tau < 0.0 ? 0.0 : (tau > 1.0 ? 1.0 : tau);
+            z = 1.0;
+            if (tau != 0.0) {
+                z = 0.0;
+                for (int s = 0; s < S; ++s) z += ws.part_z[nidx * S + s];
+            }
+        }
+        ws.node_key[nidx] = key ? 1 : 0;
+        if (p.walk) {
+            const double p_y = soft_weight(ln_pt, q_y, tau) / z;
+            const double u = (double)p.uniforms[(size_t)b * R + i];
+            const bool a = u * q_y < p_y;
+            acc[i] = a ? 1 : 0;
+            s_tau[i] = tau;
+            s_z[i] = z;
+            if (p.st.key_flags) p.st.key_flags[nidx] = key ? 1 : 0;
+            if (p.st.node_accept) p.st.node_accept[nidx] = a ? 1 : 0;
+            if (p.st.ratio) p.st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
+            if (p.st.norm_match) p.st.norm_match[nidx] = nm;
+        }
+    }
+    if (!p.walk) return;
+    if (tid == 0) acc[0] = 1;
+    if (p.accepted_path && tid < k) p.accepted_path[(size_t)b * k + tid] = -1;
+    __syncthreads();
+    if (tid <= k) {
+        int d = 0, good = acc[tid];
+        for (int n = tid; n != 0; n = par[n]) {        // parents precede children: at most k steps
             ++d;
             good &= acc[par[n]];
         }
-        dep[i] = d;
-        ok[i] = good;
+        dep[tid] = d;
+        ok[tid] = good;
     }
     __syncthreads();
-    if (i != 0) return;
+    if (tid != 0) return;
     int vstar = 0;
-    if (prm.tree_mode == DSD_TREE_FIRST_ACCEPTED) {
+    if (p.prm.tree_mode == DSD_TREE_FIRST_ACCEPTED) {
         for (;;) {
             int nxt = 0;
             for (int c = vstar + 1; c <= k; ++c)
@@ -550,9 +608,9 @@ decide_kernel(const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params
             if (ok[c] && dep[c] > dep[vstar]) vstar = c;
     }
     const int a = dep[vstar];
-    accepted_len[b] = a;
-    if (accepted_path)
-        for (int n = vstar, j = a - 1; n != 0; n = par[n], --j) accepted_path[(size_t)b * k + j] = n;
+    p.accepted_len[b] = a;
+    if (p.accepted_path)
+        for (int n = vstar, j = a - 1; n != 0; n = par[n], --j) p.accepted_path[(size_t)b * k + j] = n;
     int child = 0;
     for (int c = vstar + 1; c <= k; ++c)
         if (par[c] == vstar) { child = c; break; }
@@ -563,8 +621,8 @@ decide_kernel(const int32_t* __restrict__ parent, AcceptWs ws, dsd_accept_params
         ws.draw_z[b] = 1.0;
     } else {
         ws.draw_mode[b] = 1;
-        ws.draw_tau[b] = ws.node_tau[(size_t)b * k + child - 1];
-        ws.draw_z[b] = ws.node_z[(size_t)b * k + child - 1];
+        ws.draw_tau[b] = s_tau[child];
+        ws.draw_z[b] = s_z[child];
     }
 }
 
@@ -1033,81 +1091,115 @@ greedy_decide_kernel(const int32_t* __restrict__ tokens, const int32_t* __restri
     next_token[b] = amax[vstar];
 }
 
-int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
-                  const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k, int V,
-                  int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path, const dsd_accept_stats* stats) {
-    const int R = k + 1;
-    const int S = (V + SLICE - 1) / SLICE;
-    const size_t BR = (size_t)B * R, BK = (size_t)B * k;
-    if (prm->temperature == 0.0) {
-        DSD_TRY(dsd_ws_reserve(ctx, BR * S * 8 + 256));
-        u64* part = (u64*)ctx->ws;
-        dsd_accept_stats st0 = {nullptr, nullptr, nullptr, nullptr};
-        if (stats) st0 = *stats;
-        if (B > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
-        ProfScope ps(ctx, DSD_KC_ACCEPT);
-        row_argmax_kernel<<<dim3(S, R, B), TPB, 0, ctx->stream>>>(logits, part, R, V, S);
-        greedy_decide_kernel<<<B, DECIDE_TPB, 0, ctx->stream>>>(draft_tokens, parent, part, prm->tree_mode, k, S, accepted_len,
-                                                                 next_token, accepted_path, st0);
-        DSD_HIP(hipGetLastError());
-        return DSD_OK;
-    }
-    size_t need = (BR * S * 5 + BR * 4 + BK * 4 + BK * S + (size_t)B * 2 + (size_t)B * S * 2) * 8 +
-                  BR * S * MAXM * 8 * 2 + (2 * BK + 2 * (size_t)B) * 4 + 32 * 256;
-    DSD_TRY(dsd_ws_reserve(ctx, need));
-    WsBump bump{ctx->ws, 0};
-    AcceptWs ws;
-    ws.part_m = bump.take<double>(BR * S);
+// Carves the scratch memory of one call out of [base, ...); returns the bytes used (base may be NULL to size it).
+static size_t accept_carve(AcceptWs& ws, char* base, size_t B, size_t k, size_t S, size_t top_m) {
+    const size_t BR = B * (k + 1), BK = B * k;
+    WsBump bump{base, 0};
+    ws.part_m = bump.take<float>(BR * S);
     ws.part_s = bump.take<double>(BR * S);
-    ws.part_top_t = bump.take<u64>(BR * S * MAXM);
-    ws.part_top_q = bump.take<u64>(BR * S * MAXM);
+    ws.part_zs = bump.take<double>(BR * S);
+    ws.part_top_t = bump.take<u64>(BR * S * top_m);
+    ws.part_top_q = bump.take<u64>(BR * S * top_m);
     ws.row_lse = bump.take<double>(BR);
+    ws.row_z = bump.take<double>(BR);
     ws.row_nm = bump.take<double>(BR);
     ws.row_ht = bump.take<double>(BR);
     ws.row_hd = bump.take<double>(BR);
     ws.part_x = bump.take<double>(BR * S * 3);
-    ws.node_tau = bump.take<double>(BK);
-    ws.node_lnpt = bump.take<double>(BK);
-    ws.node_q = bump.take<double>(BK);
     ws.node_key = bump.take<int32_t>(BK);
-    ws.node_acc = bump.take<int32_t>(BK);
-    ws.node_z = bump.take<double>(BK);
     ws.part_z = bump.take<double>(BK * S);
     ws.draw_row = bump.take<int32_t>(B);
     ws.draw_mode = bump.take<int32_t>(B);
     ws.draw_tau = bump.take<double>(B);
     ws.draw_z = bump.take<double>(B);
-    ws.part_res = bump.take<double>((size_t)B * S);
-    ws.part_fb = bump.take<double>((size_t)B * S);
-    if (bump.off > ctx->ws_bytes) DSD_FAIL(DSD_ENOMEM, "accept workspace estimate too small");
+    ws.part_res = bump.take<double>(B * S);
+    ws.part_fb = bump.take<double>(B * S);
+    return bump.off;
+}
+
+size_t accept_scratch_bytes(int B, int k, int V, int top_m) {
+    AcceptWs ws;
+    const size_t S = ((size_t)V + SLICE - 1) / SLICE;
+    const size_t greedy = (size_t)B * (k + 1) * S * 8 + 256;
+    const size_t full = accept_carve(ws, nullptr, B, k, S, top_m);
+    return full > greedy ? full : greedy;
+}
+
+// scratch: device memory of at least accept_scratch_bytes(B, k, V, top_m) bytes, 256-byte aligned; its contents
+// need not be cleared (every word read by a kernel was written by an earlier kernel of the same call)
+int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+                  const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k, int V,
+                  int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path, const dsd_accept_stats* stats,
+                  char* scratch) {
+    const int R = k + 1;
+    const int S = (V + SLICE - 1) / SLICE;
     hipStream_t s = ctx->stream;
-    const double inv_temp = 1.0 / prm->temperature;
     dsd_accept_stats st = {nullptr, nullptr, nullptr, nullptr};
     if (stats) st = *stats;
-    if (B > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
-    ProfScope ps(ctx, DSD_KC_ACCEPT);
-    row_stats_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp, prm->top_m);
-    const size_t cand_bytes = (size_t)2 * S * prm->top_m * sizeof(u64);
-    const int cand_lds = cand_bytes <= 48 * 1024;
-    row_merge_kernel<<<dim3(R, B), WAVE, cand_lds ? cand_bytes : 0, s>>>(ws, R, S, prm->top_m, cand_lds);
-    if (prm->norm_match_kind == DSD_NM_OVERLAP || prm->entropy_kind == DSD_H_ROW) {
-        row_extra_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
-        row_extra_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->norm_match_kind == DSD_NM_OVERLAP ? 1 : 0);
+    if (B > 65535 || R > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
+    if (prm->temperature == 0.0) {
+        u64* part = (u64*)scratch;
+        ProfScope ps(ctx, DSD_KC_ACCEPT);
+        row_argmax_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, part, R, V, S);
+        greedy_decide_kernel<<<B, DECIDE_TPB, 0, s>>>(draft_tokens, parent, part, prm->tree_mode, k, S, accepted_len,
+                                                     next_token, accepted_path, st);
+        DSD_HIP(hipGetLastError());
+        return DSD_OK;
     }
-    if (prm->tree_mode == DSD_TREE_LOSSLESS) {
-        // no relaxation in this mode: node_soft only evaluates the key rule (reported), then the walk
-        dsd_accept_params strict = *prm;
-        strict.tau = 0.0;
-        strict.tau_override = nullptr;
-        node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, strict, k, V, S, inv_temp);
+    AcceptWs ws;
+    accept_carve(ws, scratch, B, k, S, prm->top_m);
+    const double inv_temp = 1.0 / prm->temperature;
+    const bool lossless = prm->tree_mode == DSD_TREE_LOSSLESS;
+    const bool variants = prm->norm_match_kind == DSD_NM_OVERLAP || prm->entropy_kind == DSD_H_ROW;
+    const bool per_node_tau = prm->tau_override != nullptr && !lossless;
+
+    SliceArgs sa;
+    sa.logits = logits; sa.qp = draft_probs; sa.parent = parent; sa.k = k; sa.V = V; sa.S = S; sa.top_m = prm->top_m;
+    const double c = 1.4426950408889634074 * inv_temp;
+    sa.c_hi = (float)c; sa.c_lo = (float)(c - (double)sa.c_hi);
+    const double tau = lossless ? 0.0 : prm->tau;         // no relaxation under the lossless tree rule
+    const double a = 1.0 - tau;
+    sa.a_hi = (float)a; sa.a_lo = (float)(a - (double)sa.a_hi);
+    sa.t_hi = (float)tau; sa.t_lo = (float)(tau - (double)sa.t_hi);
+    sa.soft = (tau > 0.0 && !per_node_tau) ? 1 : 0;
+    sa.tau_is_one = tau == 1.0 ? 1 : 0;
+    sa.want_top = prm->norm_match_kind == DSD_NM_TOP_M ? 1 : 0;
+
+    SeqArgs q;
+    q.logits = logits; q.qp = draft_probs; q.tokens = draft_tokens; q.parent = parent; q.uniforms = uniforms;
+    q.prm = *prm;
+    q.prm.tau = tau;
+    if (lossless) q.prm.tau_override = nullptr;
+    q.k = k; q.V = V; q.S = S; q.c = (double)sa.c_hi + (double)sa.c_lo; q.soft = sa.soft; q.want_top = sa.want_top;
+    q.walk = lossless ? 0 : 1;
+    q.accepted_len = accepted_len; q.accepted_path = accepted_path; q.st = st;
+
+    const bool vec = (V & 3) == 0 && (((size_t)logits | (size_t)draft_probs) & 15) == 0;
+    ProfScope ps(ctx, DSD_KC_ACCEPT);
+    if (vec) slice_pass_kernel<true><<<dim3(S, R, B), WAVE, 0, s>>>(sa, ws);
+    else slice_pass_kernel<false><<<dim3(S, R, B), WAVE, 0, s>>>(sa, ws);
+    if (variants || per_node_tau) {
+        // something else has to look at the rows between their log-sum-exp and the nodes' tests
+        q.do_rows = 1; q.do_nodes = 0;
+        seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
+        if (variants) {
+            row_extra_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
+            row_extra_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->norm_match_kind == DSD_NM_OVERLAP ? 1 : 0);
+        }
+        if (per_node_tau)
+            node_z_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, parent, prm->tau_override, ws, k, V, S, inv_temp);
+        q.do_rows = 0; q.do_nodes = 1;
+        seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
+    } else {
+        q.do_rows = 1; q.do_nodes = 1;
+        seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
+    }
+    if (lossless) {
         lossless_walk_kernel<<<B, WALK_TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, uniforms, ws, k, V, inv_temp,
                                                       accepted_len, next_token, accepted_path, st);
         DSD_HIP(hipGetLastError());
         return DSD_OK;
     }
-    node_soft_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, ws, *prm, k, V, S, inv_temp);
-    node_accept_kernel<<<dim3(k, B), WAVE, 0, s>>>(parent, uniforms, ws, k, S, st);
-    decide_kernel<<<B, DECIDE_TPB, 0, s>>>(parent, ws, *prm, k, accepted_len, accepted_path);
     draw_parts_kernel<<<dim3(S, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
     draw_pick_kernel<<<B, TPB, 0, s>>>(logits, draft_probs, uniforms, ws, R, V, S, inv_temp, next_token);
     DSD_HIP(hipGetLastError());

@@ -23,7 +23,7 @@ DSD_MAX_K, DSD_MAX_TOP_M = 64, 16
 EXPORTS = [
     "dsd_last_error", "dsd_create", "dsd_destroy", "dsd_set_stream", "dsd_weights_create", "dsd_weights_destroy",
     "dsd_kv_create", "dsd_kv_destroy", "dsd_kv_import", "dsd_kv_export", "dsd_kv_set_len", "dsd_kv_get_len",
-    "dsd_stage_verify", "dsd_accept", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read",
+    "dsd_stage_verify", "dsd_accept", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read", "dsd_stream_probe",
 ]
 KERNEL_CLASSES = ["qkv", "attn", "attn_combine", "oproj", "gateup", "down", "head", "accept", "other", "stage"]
 
@@ -82,6 +82,7 @@ def load() -> C.CDLL:
         "dsd_kv_commit": [vp, vp, vp, vp, i32, i32],
         "dsd_profile_enable": [vp, i32],
         "dsd_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
+        "dsd_stream_probe": [vp, vp, C.c_size_t, i32, i32, C.POINTER(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -142,6 +143,13 @@ class Context:
         cnt = (C.c_int64 * n)()
         _check(self.lib.dsd_profile_read(self.h, ms, cnt), "dsd_profile_read")
         return {KERNEL_CLASSES[i]: (ms[i], cnt[i]) for i in range(n)}
+
+    def stream_probe(self, buf: torch.Tensor, mode: int, iters: int) -> float:
+        """Average milliseconds of one launch of the bare read (mode 0) / copy (mode 1) kernel over buf."""
+        ms = C.c_double()
+        _check(self.lib.dsd_stream_probe(self.h, _ptr(buf, None, "buf"), buf.numel() * buf.element_size(), mode, iters,
+                                         C.byref(ms)), "dsd_stream_probe")
+        return ms.value
 
     def close(self) -> None:
         if self.h:

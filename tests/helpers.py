@@ -144,7 +144,8 @@ class AcceptInputs:
 MAX_FLAGGED_NODE_FRACTION = 0.10      # of the B*k node decisions of a case with at least 50 of them
 
 
-def compare_accept(gpu: dict, ora, what: str, inputs: "AcceptInputs" = None, max_excused=None):
+def compare_accept(gpu: dict, ora, what: str, inputs: "AcceptInputs" = None, max_excused=None,
+                   max_flagged_fraction=None):
     """Integer outputs against the oracle, decision by decision.
 
     The rule.  Key flags, each node's own test, accepted length, path and the extra token must be
@@ -159,8 +160,9 @@ def compare_accept(gpu: dict, ora, what: str, inputs: "AcceptInputs" = None, max
     token is drawn from) must then equal what the ORACLE computes when exactly those decisions are
     pinned to the GPU's values (`inputs` re-runs it); nothing else about the sequence is excused.
     Returns a dict of counts; asserts that the share of flagged node decisions stays below
-    MAX_FLAGGED_NODE_FRACTION (an over-eager flag would hollow the comparison out) and, if
-    max_excused is given, that no more than that many sequences needed the exception."""
+    MAX_FLAGGED_NODE_FRACTION (an over-eager flag would hollow the comparison out; a case that puts a
+    threshold into the middle of a tightly concentrated statistic on purpose states its own bound) and,
+    if max_excused is given, that no more than that many sequences needed the exception."""
     B, k = ora.key.shape
     width = gpu["accepted_path"].shape[1]
     stats = dict(nodes=B * k, flagged_accept=int(ora.tie_accept.sum()), flagged_key=int(ora.tie_key.sum()),
@@ -215,7 +217,8 @@ def compare_accept(gpu: dict, ora, what: str, inputs: "AcceptInputs" = None, max
                                  np.nonzero(fa[0] >= 0)[0].tolist()))
     flagged = stats["flagged_accept"] + stats["flagged_key"]
     if B * k >= 50:
-        assert flagged <= MAX_FLAGGED_NODE_FRACTION * 2 * B * k, (
+        frac = MAX_FLAGGED_NODE_FRACTION if max_flagged_fraction is None else max_flagged_fraction
+        assert flagged <= frac * 2 * B * k, (
             f"{what}: {flagged} of {2 * B * k} node decisions are flagged as near ties: the excuse is too wide")
     if max_excused is not None:
         assert stats["excused_sequences"] <= max_excused, f"{what}: excused {stats['excused']}"

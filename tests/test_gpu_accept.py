@@ -36,12 +36,13 @@ def make_rows(seed, B, k, V, parent=None, spread=1.28, noise=0.5, zero_frac=0.0)
     return lg, q, toks, u
 
 
-def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None):
+def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None, max_flagged_fraction=None):
     ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm),
                    None if tau_override is None else tau_override.astype(np.float64))
     g = H.gpu_accept(ctx, torch.from_numpy(lg).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm,
                      tau_override)
-    st = H.compare_accept(g, ora, what, H.AcceptInputs(O, lg, q, toks, parent, u, prm, tau_override))
+    st = H.compare_accept(g, ora, what, H.AcceptInputs(O, lg, q, toks, parent, u, prm, tau_override),
+                          max_flagged_fraction=max_flagged_fraction)
     excused, near = st["excused_sequences"], st["flagged_accept"] + st["flagged_key"] + st["flagged_draw"]
     fin = np.isfinite(ora.ratio)
     # The reported ratios are fp64 over fp32 per-id terms: 1e-6 relative for the per-node rules.  In the
@@ -240,7 +241,10 @@ def test_key_rule_variants_and_tau_sweep(ctx):
         for prm in (dict(tau=0.3, lambda3=lam3, norm_match_kind=1), dict(tau=0.3, lambda1=lam1, entropy_kind=1),
                     dict(tau=0.3, lambda1=lam1, lambda3=lam3, norm_match_kind=1, entropy_kind=1, tree_mode=1),
                     dict(lambda3=lam3, norm_match_kind=1, tree_mode=2)):
-            ora, g, ex, near = run_case(ctx, lg, q, toks, par, u, prm, f"{what} {prm}")
+            # lambda1 sits at the median of the rows' entropy ratios, which on these near-flat rows all lie within
+            # a percent of each other: a large share of the nodes is within 1e-3 of that threshold by construction
+            ora, g, ex, near = run_case(ctx, lg, q, toks, par, u, prm, f"{what} {prm}",
+                                        max_flagged_fraction=0.5 if prm.get("entropy_kind") else None)
             assert 0.1 < ora.key.mean() < 0.9, (what, prm, ora.key.mean())
     # accept rate against tau, no key tokens
     lg, q, toks, u = make_rows(73, 64, 5, 3000, noise=1.0)

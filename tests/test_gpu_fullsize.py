@@ -1,9 +1,11 @@
 """GPU parity at the full sizes of the benchmark configurations 2-5, in the launch configuration
-bench.py times.  The GPU computes every sequence; the oracle recomputes a sample of whole
-sequences (sequences are independent, so a sampled sequence is checked element by element:
-hidden rows, logits rows, appended K/V rows), the rest is checked for finiteness.  On the
-final-stage configurations dsd_accept is checked for every sequence on the GPU-produced logits,
-and for the sampled sequences on the oracle's logits."""
+bench.py times.  Every sequence of every configuration is checked element by element against ONE
+batched oracle pass (the oracle widens each layer's weights once for the whole batch, so all sequences
+cost little more than one): hidden rows, logits rows (root row included) and the appended K/V rows
+of every layer.  On the final-stage configurations dsd_accept is checked for every sequence twice:
+on the logits the GPU produced (fed bit-identically to the oracle) and on the oracle's logits; no
+sequence may need the near-tie exception there (the inputs are seeded, so this is a fixed fact of
+these workloads, not luck)."""
 import os
 
 import numpy as np
@@ -25,30 +27,22 @@ def lambdas():
     return l1, l2, l3
 
 
-def bf16_round64(a):
-    """What a bf16 cache keeps of an fp64 row."""
-    return O.widen(W.f32_to_bf16_bits(a.astype(np.float32)))
-
-
-def oracle_sequence(cfg, w, K, V, hid, root_hid, parent, b):
-    """Oracle for sequence b alone: optional root pass (1 row at C-1, committed into the bf16
-    cache), then the k-row pass."""
+def oracle_batch(cfg, w, K, V, hid, root_hid, parent):
+    """Oracle for all sequences: optional root pass (1 row at C-1, whose K/V rows are then committed
+    into the bf16 cache at slot C-1, rounded as a bf16 cache rounds them), then the k-row pass.
+    K, V stay in their stored dtype (the oracle widens what it reads) and are modified in place."""
     m = cfg.model
-    Kb = O.widen(K[:, b:b + 1])
-    Vb = O.widen(V[:, b:b + 1])
-    pad = np.zeros(Kb.shape[:3] + (cfg.k,) + Kb.shape[4:])
-    Kb = np.concatenate([Kb, pad], axis=3)
-    Vb = np.concatenate([Vb, pad], axis=3)
+    B, C = cfg.B, cfg.C
     root = None
     if root_hid is not None:
-        root = O.stage_forward(m, w.__getitem__, Kb, Vb, [cfg.C - 1], root_hid[b:b + 1], None)
-        O.kv_commit(Kb, Vb, np.array([cfg.C - 1]), bf16_round64(root.new_k), bf16_round64(root.new_v),
-                    np.array([[1]], dtype=np.int32))
-    full = O.stage_forward(m, w.__getitem__, Kb, Vb, [cfg.C], hid[b:b + 1], None, parent=parent)
+        root = O.stage_forward(m, w.__getitem__, K, V, [C - 1] * B, root_hid, None)
+        K[:, :, :, C - 1, :] = W.f32_to_bf16_bits(root.new_k[:, :, :, 0, :].astype(np.float32))
+        V[:, :, :, C - 1, :] = W.f32_to_bf16_bits(root.new_v[:, :, :, 0, :].astype(np.float32))
+    full = O.stage_forward(m, w.__getitem__, K, V, [C] * B, hid, None, parent=parent)
     return root, full
 
 
-def run_config(name, sample):
+def run_config(name):
     cfg = W.CONFIGS[name]
     m = cfg.model
     B, k, C = cfg.B, cfg.k, cfg.C
@@ -75,22 +69,30 @@ def run_config(name, sample):
     got_h = H.to_np64(out)
     assert np.isfinite(got_h).all()
     tol = H.TOL["bf16"]
-    refs = {}
-    for b in sample:
-        print(f"[{name}] oracle for sequence {b}", flush=True)
-        root, full = oracle_sequence(cfg, w, K, V, hid, root_hid, parent, b)
-        refs[b] = (root, full)
-        nrms, worst = H.assert_close(got_h[b:b + 1], full.hidden, tol, f"{name} hidden seq {b}")
-        print(f"[{name}] seq {b}: hidden normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}", flush=True)
-        if m.has_head:
-            ref_lg = np.concatenate([root.logits, full.logits], axis=1)
-            nrms, worst = H.assert_close(H.to_np64(buf[b:b + 1]), ref_lg, tol, f"{name} logits seq {b}")
-            print(f"[{name}] seq {b}: logits normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}", flush=True)
-        for l in (0, m.L - 1):
-            gk, gv = st.new_rows(l, C, k, B)
-            H.assert_close(gk[b:b + 1], full.new_k[l], tol, f"{name} appended K layer {l} seq {b}")
-            H.assert_close(gv[b:b + 1], full.new_v[l], tol, f"{name} appended V layer {l} seq {b}")
-    return cfg, st, buf, refs, parent
+    print(f"[{name}] oracle for all {B} sequences", flush=True)
+    root, full = oracle_batch(cfg, w, K, V, hid, root_hid, parent)
+    ref_lg = None
+    # every sequence, element by element (assert_close's allowance is per row, so the batch can go in one call;
+    # the worst sequence is named when it fails)
+    for b in range(B):
+        H.assert_close(got_h[b], full.hidden[b], tol, f"{name} hidden seq {b}")
+    nrms, worst = H.assert_close(got_h, full.hidden, tol, f"{name} hidden")
+    print(f"[{name}] hidden, all {B} sequences: normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}", flush=True)
+    if m.has_head:
+        ref_lg = np.concatenate([root.logits, full.logits], axis=1)
+        got_lg = H.to_np64(buf)
+        for b in range(B):
+            H.assert_close(got_lg[b], ref_lg[b], tol, f"{name} logits seq {b}")
+        nrms, worst = H.assert_close(got_lg, ref_lg, tol, f"{name} logits")
+        print(f"[{name}] logits, all {B} sequences: normalised rms error {nrms:.2e}, worst/allowance {worst:.3f}", flush=True)
+        del got_lg
+    for l in range(m.L):
+        gk, gv = st.new_rows(l, C, k, B)
+        for b in range(B):
+            H.assert_close(gk[b], full.new_k[l][b], tol, f"{name} appended K layer {l} seq {b}")
+            H.assert_close(gv[b], full.new_v[l][b], tol, f"{name} appended V layer {l} seq {b}")
+    print(f"[{name}] appended K/V rows of all {m.L} layers and {B} sequences agree", flush=True)
+    return cfg, st, buf, ref_lg, parent
 
 
 def draft_from(cfg, logits_np, parent, tag):
@@ -119,51 +121,44 @@ def draft_from(cfg, logits_np, parent, tag):
     return q, toks
 
 
-def accept_both_ways(name, cfg, st, buf, refs, parent, tree_mode=0):
+def accept_both_ways(name, cfg, st, buf, ref_lg, parent, tree_mode=0):
     l1, l2, l3 = lambdas()
     prm = dict(tau=cfg.tau, lambda1=l1, lambda2=l2, lambda3=l3, top_m=cfg.top_m, tree_mode=tree_mode)
     k = cfg.k
-    # (i) every sequence, on the logits the GPU produced (fed bit-identically to the oracle)
-    lg = buf.cpu().numpy()
-    q, toks = draft_from(cfg, lg, parent, "draft.gpu")
     u = W.make_uniforms(cfg, k + 1)
-    ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm))
-    g = H.gpu_accept(st.ctx, buf, torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm)
-    ex, near = H.compare_accept(g, ora, f"{name} accept on GPU logits")
-    print(f"[{name}] accept on GPU logits: accepted {ora.accepted_len.tolist()}, key fraction {ora.key.mean():.2f}, "
-          f"near-tie sequences {near}, excused mismatches {ex}", flush=True)
-    # (ii) the sampled sequences, on the oracle's logits
-    bs = sorted(refs)
-    lo = np.stack([np.concatenate([refs[b][0].logits, refs[b][1].logits], axis=1)[0] for b in bs]).astype(np.float32)
-    sub = W.scaled(cfg, B=len(bs))
-    q, toks = draft_from(sub, lo, parent, "draft.oracle")
-    u = W.make_uniforms(sub, k + 1, tag="u.oracle")
-    ora = O.accept(lo.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm))
-    g = H.gpu_accept(st.ctx, torch.from_numpy(lo).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm)
-    ex, near = H.compare_accept(g, ora, f"{name} accept on oracle logits")
-    print(f"[{name}] accept on oracle logits: accepted {ora.accepted_len.tolist()}, near-tie sequences {near}, "
-          f"excused mismatches {ex}", flush=True)
-    # commit what was accepted and check the cache lengths
-    alen, nxt, path = g["dev"]
+    ora = None
+    # every sequence (i) on the logits the GPU produced, fed bit-identically to the oracle, (ii) on the oracle's logits
+    for what, lg, tag in (("GPU logits", buf.cpu().numpy(), "draft.gpu"), ("oracle logits", ref_lg.astype(np.float32), "draft.oracle")):
+        q, toks = draft_from(cfg, lg, parent, tag)
+        ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm))
+        g = H.gpu_accept(st.ctx, torch.from_numpy(lg).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm)
+        stt = H.compare_accept(g, ora, f"{name} accept on {what}", H.AcceptInputs(O, lg, q, toks, parent, u, prm),
+                               max_excused=0)
+        fin = np.isfinite(ora.ratio) & (ora.ratio != 0)
+        np.testing.assert_allclose(g["ratio"][fin], ora.ratio[fin], rtol=1e-4 if tree_mode == 2 else 1e-6,
+                                   err_msg=f"{name} accept on {what}")
+        print(f"[{name}] accept on {what}: accepted {ora.accepted_len.tolist()}, key fraction {ora.key.mean():.2f}, "
+              f"near-tie decisions of {stt['nodes']} nodes: test {stt['flagged_accept']}, key {stt['flagged_key']}, "
+              f"draw {stt['flagged_draw']}; sequences that needed the exception: {stt['excused_sequences']}", flush=True)
     return ora
 
 
 def test_c2_middle_stage_full_size():
-    run_config("c2", [0])
+    run_config("c2")
 
 
 def test_c3_final_stage_full_size_with_adaptive_accept():
-    cfg, st, buf, refs, parent = run_config("c3", [0, 11])
-    accept_both_ways("c3", cfg, st, buf, refs, parent)
+    cfg, st, buf, ref_lg, parent = run_config("c3")
+    accept_both_ways("c3", cfg, st, buf, ref_lg, parent)
 
 
 def test_c4_70b_stage_full_size():
-    run_config("c4", [5])
+    run_config("c4")
 
 
 def test_c5_tree_final_stage_full_size_with_adaptive_accept():
-    cfg, st, buf, refs, parent = run_config("c5", [2])
-    ora = accept_both_ways("c5", cfg, st, buf, refs, parent)
+    cfg, st, buf, ref_lg, parent = run_config("c5")
+    ora = accept_both_ways("c5", cfg, st, buf, ref_lg, parent)
     assert ora.accepted_path.shape[1] == 32
     # the same logits under the lossless multi-sibling rule
-    accept_both_ways("c5 lossless", cfg, st, buf, refs, parent, tree_mode=2)
+    accept_both_ways("c5 lossless", cfg, st, buf, ref_lg, parent, tree_mode=2)
