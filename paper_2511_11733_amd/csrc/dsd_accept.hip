@@ -31,6 +31,7 @@
 #define TPB 256
 #define EPT (SLICE / TPB)
 #define MAXM DSD_MAX_TOP_M
+#define LCAP 32           // candidate keys a slice may hand to the row merge (top_m <= 16 of them matter)
 
 typedef unsigned long long u64;
 
@@ -120,54 +121,63 @@ __device__ inline unsigned order_u32(float v) {
 }
 
 // ---------------------------------------------------------------------------- wave-level tools
-// 64 values, one per lane, sorted across the lanes (bitonic network, 21 exchange steps): descending,
-// lane 0 ends up with the largest.  NaNs behave as fminf / fmaxf treat them.
-__device__ inline float wave_sort_desc_f(float v, int lane) {
-#pragma unroll
-    for (int k = 2; k <= WAVE; k <<= 1)
-#pragma unroll
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            const float o = __shfl_xor(v, j, WAVE);
-            const bool desc = (lane & k) == 0, lower = (lane & j) == 0;
-            v = (lower == desc) ? fmaxf(v, o) : fminf(v, o);
-        }
-    return v;
-}
-__device__ inline u64 wave_sort_desc_u(u64 v, int lane) {
-#pragma unroll
-    for (int k = 2; k <= WAVE; k <<= 1)
-#pragma unroll
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            const u64 o = __shfl_xor(v, j, WAVE);
-            const bool desc = (lane & k) == 0, lower = (lane & j) == 0;
-            const u64 hi = v > o ? v : o, lo = v > o ? o : v;
-            v = (lower == desc) ? hi : lo;
-        }
-    return v;
-}
 __device__ inline float wave_max_f(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
     return v;
 }
-// exclusive prefix sum of a small count over the lanes, and the wave's total
-__device__ inline int wave_excl_scan(int v, int lane, int* total) {
-    int inc = v;
+__device__ __forceinline__ u64 readlane_u64(u64 v, int l) {      // l wave-uniform
+    const unsigned lo = __builtin_amdgcn_readlane((int)(unsigned)v, l), hi = __builtin_amdgcn_readlane((int)(unsigned)(v >> 32), l);
+    return ((u64)hi << 32) | (u64)lo;
+}
+// The top_m-th largest of the 64 / GL group maxima of v (a group = GL neighbouring lanes), equal
+// values counted separately: a lower bound of the top_m-th largest of all the values the lanes'
+// v stand for, as long as every v is the maximum of a set of ids of its own.  top_m <= 64 / GL.
+// All lanes get the result.  T = float or u64 (anything ordered by > and ==).
+__device__ __forceinline__ float rd_lane(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
+__device__ __forceinline__ u64 rd_lane(u64 v, int l) { return readlane_u64(v, l); }
+template <int GL, typename T>
+__device__ inline T group_threshold(T v, int lane, int top_m) {
 #pragma unroll
-    for (int o = 1; o < WAVE; o <<= 1) {
-        const int t = __shfl_up(inc, o, WAVE);
-        if (lane >= o) inc += t;
+    for (int o = 1; o < GL; o <<= 1) {
+        const T t = __shfl_xor(v, o, WAVE);
+        v = t > v ? t : v;
     }
-    *total = __shfl(inc, WAVE - 1, WAVE);
-    return inc - v;
+    int rank = 0;                                         // of this lane's group among the 64 / GL groups
+    const int mine = lane / GL;
+#pragma unroll
+    for (int g = 0; g < WAVE / GL; ++g) {
+        const T o = rd_lane(v, g * GL);
+        rank += (o > v || (o == v && g < mine)) ? 1 : 0;
+    }
+    const unsigned long long holder = __ballot(rank == top_m - 1);      // the lanes of exactly one group
+    return rd_lane(v, __ffsll((long long)holder) - 1);
+}
+
+// Between a wave's LDS writes and its own lanes' reads of them: LDS operations of one wave complete in
+// order; this keeps the compiler from moving them and waits for the writes.
+__device__ __forceinline__ void wave_lds_sync() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
+
+// cnt <= 64 distinct keys sit in cand[0..cnt) (LDS of this wave): the top_m largest go to out[0..top_m),
+// best first, 0 where the keys run out.  Every lane counts the keys above its own.
+__device__ inline void rank_out(const u64* __restrict__ cand, int cnt, int top_m, int lane, u64* __restrict__ out) {
+    const u64 c = lane < cnt ? cand[lane] : 0ull;
+    int rank = 0;
+    for (int i = 0; i < cnt; ++i) rank += readlane_u64(c, i) > c ? 1 : 0;
+    if (lane < cnt) {
+        if (rank < top_m) out[rank] = c;
+    } else if (lane < top_m) {
+        out[lane] = 0ull;                                 // cnt <= lane < top_m: fewer keys than top_m
+    }
 }
 
 struct AcceptWs {
     float* part_m;      // [B][R][S]   reference exponent of the slice: (max logit / T) log2 e, as one float
     double* part_s;     // [B][R][S]   sum_v 2^(x_v - part_m),  x_v = (l_v / T) log2 e
     double* part_zs;    // [B][R][S]   sum_v 2^((1-tau)(x_v - part_m)) q_v^tau   (rows with children, call-wide tau > 0)
-    u64* part_top_t;    // [B][R][S][top_m]   slice's top_m (value, id) keys of the logits row, best first, 0 = none
-    u64* part_top_q;    // [B][R][S][top_m]   the same of the draft row
+    u64* part_top_t;    // [B][R][S][LCAP]  (value, id) keys of the slice's candidates for the row's top_m, logits row, unordered
+    u64* part_top_q;    // [B][R][S][LCAP]  the same of the draft row
+    int32_t* part_cnt;  // [B][R][S][2]     how many of them (logits row, draft row)
     double* row_lse;    // [B][R]  natural-log log-sum-exp of logits / T
     double* row_z;      // [B][R]  Z~ of the row under the call-wide tau
     double* row_nm;     // [B][R]
@@ -223,119 +233,143 @@ __device__ __forceinline__ void slice_load(const float* __restrict__ row, int ba
     }
 }
 
-// The slice's top_m of one row, best first, to out[0..top_m) (0 = the slice ran out of ids).
-// Threshold first: the top_m-th largest of the 64 lane maxima cannot exceed the slice's top_m-th
-// largest value (the maxima are top_m different ids at least that large), so everything that can be
-// among the top_m lies at or above it; usually a dozen ids pass.  They go to a list in LDS, one per
-// lane, and a sort across the lanes on the full (value, id) keys puts the winners into lanes
-// 0..top_m-1; equal values go to the lower id.  If more than 64 ids pass (many equal values), top_m
-// rounds of a wave-wide maximum over all ids of the slice instead.
-template <bool VEC>
-__device__ inline void slice_top_m(const float (&v)[EPL], int base, int V, int lane, int top_m, u64* __restrict__ cand,
-                                   u64* __restrict__ out) {
-    float lm = -INFINITY;
+// The slice's candidates for the row's top_m of one row kind: every id at or above a threshold that is
+// known not to exceed the slice's own top_m-th largest value -- the top_m-th largest of the maxima of
+// 16 (32 from top_m = 9 on) groups of lanes (those maxima are that many different ids at least that
+// large).  Usually a dozen ids pass; they go out as (value, id) keys in no particular order, the row
+// merge ranks them.  The comparisons leave wave-wide lane masks in scalar registers, so counting,
+// positions and skipping the ids nobody passes cost no vector work.  If more than LCAP ids pass (many
+// equal values), the slice's exact top_m instead, by rounds of a wave-wide maximum, equal values to
+// the lower id.  Returns the number of keys written to out[].
+template <bool VEC, bool FULL>
+__device__ __forceinline__ int slice_candidates(const float (&v)[EPL], float lm, int base, int V, int lane, int top_m,
+                                                u64* __restrict__ out) {
+    // lm: the largest of this lane's values (ids inside the row only)
+    const float thr = top_m <= 8 ? group_threshold<4, float>(lm, lane, top_m) : group_threshold<2, float>(lm, lane, top_m);
+    int cnt = 0;                                          // wave-uniform
 #pragma unroll
-    for (int j = 0; j < EPL; ++j)
-        if (slice_id<VEC>(base, lane, j) < V) lm = fmaxf(lm, v[j]);
-    const float sorted = wave_sort_desc_f(lm, lane);
-    const float thr = __shfl(sorted, top_m - 1, WAVE);
-    int cnt = 0;
-#pragma unroll
-    for (int j = 0; j < EPL; ++j) cnt += (slice_id<VEC>(base, lane, j) < V && v[j] >= thr) ? 1 : 0;
-    int total;
-    int pos = wave_excl_scan(cnt, lane, &total);
-    if (total <= WAVE) {                                  // wave-uniform
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const int id = slice_id<VEC>(base, lane, j);
-            if (id < V && v[j] >= thr) cand[pos++] = rank_key(v[j], id);
+    for (int j = 0; j < EPL; ++j) {
+        const int id = slice_id<VEC>(base, lane, j);
+        const unsigned long long m = __builtin_amdgcn_ballot_w64((FULL || id < V) && v[j] >= thr);
+        if (m) {
+            const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+            if (((m >> lane) & 1ull) && pos < LCAP) out[pos] = rank_key(v[j], id);
+            cnt += __popcll(m);
         }
-        __syncthreads();                                  // the workgroup is this one wave; branch is wave-uniform
-        u64 c = lane < total ? cand[lane] : 0ull;
-        c = wave_sort_desc_u(c, lane);
-        if (lane < top_m) out[lane] = c;
-        __syncthreads();                                  // the list is rewritten by the next call
-        return;
     }
+    if (cnt <= LCAP) return cnt;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");    // the stores above land before the ones below
     u64 last = ~0ull;
+    int n = 0;
     for (int round = 0; round < top_m; ++round) {
         u64 best = 0ull;
 #pragma unroll
         for (int j = 0; j < EPL; ++j) {
             const int id = slice_id<VEC>(base, lane, j);
-            const u64 key = id < V ? rank_key(v[j], id) : 0ull;
+            const u64 key = (FULL || id < V) ? rank_key(v[j], id) : 0ull;
             best = (key < last && key > best) ? key : best;
         }
         last = wave_max_u(best);
+        if (last == 0ull) break;                          // the slice ran out of ids
         if (lane == 0) out[round] = last;
-        if (last == 0ull) last = 1ull;                    // nothing left: the remaining rounds store 0
+        ++n;
     }
+    return n;
 }
 
-// One wavefront per (slice, row, sequence).
-template <bool VEC>
-__global__ void __launch_bounds__(WAVE) slice_pass_kernel(SliceArgs p, AcceptWs ws) {
-    __shared__ u64 cand[WAVE];
+// FULL: every id of the slice lies inside the row (all slices of a row but the last)
+template <bool VEC, bool FULL>
+__device__ __forceinline__ void slice_pass_body(const SliceArgs& p, const AcceptWs& ws, bool has_child) {
     const int s = blockIdx.x, r = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
     const int R = p.k + 1;
-    // does any node hang under this row?  (parents precede children: only nodes r+1.. can)
-    bool has_child = false;
-    for (int c = r + 1; c <= p.k; ++c) {
-        int par = p.parent ? p.parent[c - 1] : c - 1;
-        par = par < 0 ? 0 : (par > c - 1 ? c - 1 : par);
-        has_child = has_child || par == r;
-    }
     const size_t row = ((size_t)b * R + r) * p.V;
     const int base = s * SLICE;
     const size_t pidx = ((size_t)b * R + r) * p.S + s;
-    float lv[EPL];
+    float lv[EPL], qv[EPL];
     slice_load<VEC>(p.logits + row, base, p.V, lane, lv, -INFINITY);
-    float lmax = -INFINITY;
+    if (has_child) slice_load<VEC>(p.qp + row, base, p.V, lane, qv, 0.f);
+    float lane_max = -INFINITY;                           // ids past V hold -inf
 #pragma unroll
-    for (int j = 0; j < EPL; ++j) lmax = fmaxf(lmax, lv[j]);
-    lmax = wave_max_f(lmax);
-    const float mref = lmax * p.c_hi;                     // one rounding; the merge uses this very float
+    for (int j = 0; j < EPL; ++j) lane_max = fmaxf(lane_max, lv[j]);
+    const float lmax = wave_max_f(lane_max);
     const bool live = lmax > -INFINITY && lmax < INFINITY;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f}, zacc[4] = {0.f, 0.f, 0.f, 0.f};
-    float x[EPL];                                         // x_v - mref
+    const float ref = live ? lmax * p.c_hi : 0.f;         // the slice's reference exponent: one rounding; the merge uses this very float
+    // x_v - ref = l c_hi - ref + l c_lo.  c_lo > 0, so a logit of -inf (a masked id, an id past V)
+    // gives -inf, weight 0, without a test.
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    float x[EPL];
 #pragma unroll
     for (int j = 0; j < EPL; ++j) {
-        // -inf logits (masked ids, ids past V) give weight 0; keep them out of the two-float product
-        const float l = fmaxf(lv[j], -3.0e38f);
-        const float d = fmaf(l, p.c_hi, -mref);
-        x[j] = live ? fmaf(l, p.c_lo, d) : -INFINITY;
+        x[j] = fmaf(lv[j], p.c_lo, fmaf(lv[j], p.c_hi, -ref));
         acc[j & 3] += __builtin_amdgcn_exp2f(x[j]);
     }
     double sum = ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);
     sum = wave_sum_d(sum);
     if (lane == 0) {
-        ws.part_m[pidx] = live ? mref : -INFINITY;
-        ws.part_s[pidx] = sum;
+        ws.part_m[pidx] = live ? ref : -INFINITY;
+        ws.part_s[pidx] = live ? sum : 0.0;
     }
     if (!has_child) return;                               // a leaf's draft row is never read
-    float qv[EPL];
-    slice_load<VEC>(p.qp + row, base, p.V, lane, qv, 0.f);
     if (p.soft) {
+        float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p.tau_is_one) {
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            float t;
-            if (p.tau_is_one) {
-                t = slice_id<VEC>(base, lane, j) < p.V ? fmaxf(qv[j], 0.f) : 0.f;     // P_t^0 = 1 for every id
-            } else {
-                const float lq = log2f(qv[j]);            // -inf for q = 0: weight 0
-                const float e = fmaf(p.a_hi, x[j], fmaf(p.t_hi, lq, fmaf(p.a_lo, x[j], p.t_lo * lq)));
-                t = (qv[j] > 0.f && x[j] > -INFINITY) ? __builtin_amdgcn_exp2f(e) : 0.f;
+            for (int j = 0; j < EPL; ++j) zacc[j & 3] += fmaxf(qv[j], 0.f);      // P_t^0 = 1 for every id; ids past V hold 0
+        } else {
+            // (1-tau) x + tau log2 q = x + tau (log2 q - x), x short for x_v - ref.  q = 0 gives -inf, weight 0
+            // (t_lo > 0); so does a logit of -inf.  The hardware logarithm takes subnormal q for 0: if the
+            // slice holds any (next to never), the library's logarithm does the pass again.
+            bool subnormal = false;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                subnormal = subnormal || __builtin_amdgcn_ballot_w64(__builtin_amdgcn_class(qv[j], 0x010 | 0x080)) != 0ull;
+                const float lq = __builtin_amdgcn_logf(qv[j]);
+                const float d = lq - fmaxf(x[j], -1.0e30f);       // finite also for a logit of -inf: no inf - inf below
+                const float e = fmaf(p.t_hi, d, fmaf(p.t_lo, d, x[j]));
+                zacc[j & 3] += __builtin_amdgcn_exp2f(e);
             }
-            zacc[j & 3] += t;
+            if (subnormal) {                              // wave-uniform
+                zacc[0] = zacc[1] = zacc[2] = zacc[3] = 0.f;
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) {
+                    const float d = log2f(qv[j]) - fmaxf(x[j], -1.0e30f);
+                    zacc[j & 3] += __builtin_amdgcn_exp2f(fmaf(p.t_hi, d, fmaf(p.t_lo, d, x[j])));
+                }
+            }
         }
         double z = ((double)zacc[0] + (double)zacc[1]) + ((double)zacc[2] + (double)zacc[3]);
         z = wave_sum_d(z);
-        if (lane == 0) ws.part_zs[pidx] = z;
+        if (lane == 0) ws.part_zs[pidx] = live ? z : 0.0;
     }
     if (p.want_top) {
-        slice_top_m<VEC>(lv, base, p.V, lane, p.top_m, cand, ws.part_top_t + pidx * p.top_m);
-        slice_top_m<VEC>(qv, base, p.V, lane, p.top_m, cand, ws.part_top_q + pidx * p.top_m);
+        float q_max = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j)
+            if (FULL || slice_id<VEC>(base, lane, j) < p.V) q_max = fmaxf(q_max, qv[j]);
+        const int n_t = slice_candidates<VEC, FULL>(lv, lane_max, base, p.V, lane, p.top_m, ws.part_top_t + pidx * LCAP);
+        const int n_q = slice_candidates<VEC, FULL>(qv, q_max, base, p.V, lane, p.top_m, ws.part_top_q + pidx * LCAP);
+        if (lane == 0) *(int2*)(ws.part_cnt + pidx * 2) = make_int2(n_t, n_q);
     }
+}
+
+// Does any node hang under row r?  One load per lane instead of a walk over the parent array.
+__device__ __forceinline__ bool row_has_child(const int32_t* __restrict__ parent, int k, int r, int lane) {
+    if (!parent) return r < k;                            // chain
+    bool mine = false;
+    for (int c = lane + 1; c <= k; c += WAVE) {
+        int par = parent[c - 1];
+        par = par < 0 ? 0 : (par > c - 1 ? c - 1 : par);
+        mine = mine || par == r;
+    }
+    return __builtin_amdgcn_ballot_w64(mine) != 0ull;
+}
+
+// One wavefront per (slice, row, sequence).
+template <bool VEC>
+__global__ void __launch_bounds__(WAVE, 4) slice_pass_kernel(SliceArgs p, AcceptWs ws) {
+    const bool has_child = row_has_child(p.parent, p.k, blockIdx.y, threadIdx.x);
+    if ((blockIdx.x + 1) * SLICE <= p.V) slice_pass_body<VEC, true>(p, ws, has_child);
+    else slice_pass_body<VEC, false>(p, ws, has_child);
 }
 
 // Row quantities of the other readings of the key rule (only launched when one is selected; needs
@@ -416,36 +450,68 @@ node_z_kernel(const float* __restrict__ logits, const float* __restrict__ qp, co
     if (threadIdx.x == 0) ws.part_z[nidx * S + s] = z;
 }
 
-// The top_m best of n_lists lists of top_m keys each (every list best first, 0 = none), by one wave.
-// Lane l holds list l in registers; a round takes the wave-wide maximum of the heads and the winner
-// shifts its list (keys are distinct: they carry the id).  More than 63 lists go through in groups,
-// lane 63 carrying the best of the groups before.  ids[0..top_m) to every lane (-1 = none).
-__device__ inline void merge_top_lists(const u64* __restrict__ lists, int n_lists, int top_m, int lane, int (&ids)[MAXM]) {
-    u64 best[MAXM];
+// The top_m best keys of a row from its slices' candidate lists (LCAP slots each, cnt[2*l + kind] of
+// them in use), by one wave, to out[0..top_m) (LDS), best first, 0 where the keys run out.  Same
+// scheme as inside a slice: a lane's head is the best key of the lists it owns, the top_m-th largest
+// group maximum of the heads bounds the answer from below, the few keys at or above it are ranked
+// (every lane counts the keys above its own).  More than 64 such keys (few lists, many equal
+// values): rounds of a wave-wide maximum.  A lane's lists are fetched whole, all loads in flight at once.
+__device__ inline void merge_top_lists(const u64* __restrict__ lists, const int32_t* __restrict__ cnts, int kind, int n_lists,
+                                       int top_m, int lane, u64* __restrict__ cand, u64* __restrict__ out) {
+    u64 h = 0ull;
+    for (int l = lane; l < n_lists; l += WAVE) {
+        const int n = cnts[2 * l + kind];
+        const ulonglong2* src = (const ulonglong2*)(lists + (size_t)l * LCAP);
+        ulonglong2 kk[LCAP / 2];
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) best[i] = 0ull;
-    for (int g0 = 0; g0 < n_lists; g0 += WAVE - 1) {
-        u64 c[MAXM];
+        for (int i = 0; i < LCAP / 2; ++i) kk[i] = src[i];
 #pragma unroll
-        for (int i = 0; i < MAXM; ++i) {
-            u64 v = 0ull;
-            if (lane < WAVE - 1 && g0 + lane < n_lists && i < top_m) v = lists[(size_t)(g0 + lane) * top_m + i];
-            c[i] = lane == WAVE - 1 ? best[i] : v;
+        for (int i = 0; i < LCAP / 2; ++i) {
+            const u64 a = 2 * i < n ? kk[i].x : 0ull, c = 2 * i + 1 < n ? kk[i].y : 0ull;
+            h = a > h ? a : h;
+            h = c > h ? c : h;
         }
+    }
+    const u64 thr = top_m <= 8 ? group_threshold<4, u64>(h, lane, top_m) : group_threshold<2, u64>(h, lane, top_m);
+    int cnt = 0;
+    for (int l0 = 0; l0 < n_lists; l0 += WAVE) {
+        const int l = l0 + lane;
+        const int n = l < n_lists ? cnts[2 * l + kind] : 0;
+        const ulonglong2* src = (const ulonglong2*)(lists + (size_t)(l < n_lists ? l : 0) * LCAP);
+        ulonglong2 kk[LCAP / 2];
 #pragma unroll
-        for (int round = 0; round < MAXM; ++round) {
-            if (round < top_m) {
-                const u64 w = wave_max_u(c[0]);
-                best[round] = w;
-                const bool mine = w != 0ull && c[0] == w;
+        for (int i = 0; i < LCAP / 2; ++i) kk[i] = src[i];
 #pragma unroll
-                for (int i = 0; i < MAXM - 1; ++i) c[i] = mine ? c[i + 1] : c[i];
-                c[MAXM - 1] = mine ? 0ull : c[MAXM - 1];
+        for (int i = 0; i < LCAP; ++i) {
+            const u64 key = i < n ? ((i & 1) ? kk[i / 2].y : kk[i / 2].x) : 0ull;
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(key != 0ull && key >= thr);
+            if (m) {
+                const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                if (((m >> lane) & 1ull) && pos < WAVE) cand[pos] = key;
+                cnt += __popcll(m);
             }
         }
     }
-#pragma unroll
-    for (int i = 0; i < MAXM; ++i) ids[i] = best[i] != 0ull ? key_id(best[i]) : -1;
+    wave_lds_sync();
+    if (cnt <= WAVE) {
+        rank_out(cand, cnt, top_m, lane, out);
+    } else {
+        u64 last = ~0ull;
+        for (int round = 0; round < top_m; ++round) {
+            u64 best = 0ull;
+            for (int l = lane; l < n_lists; l += WAVE) {
+                const int n = cnts[2 * l + kind];
+                for (int i = 0; i < n; ++i) {
+                    const u64 key = lists[(size_t)l * LCAP + i];
+                    best = (key < last && key > best) ? key : best;
+                }
+            }
+            last = wave_max_u(best);
+            if (lane == 0) out[round] = last;
+            if (last == 0ull) last = 1ull;
+        }
+    }
+    __syncthreads();
 }
 
 struct SeqArgs {
@@ -457,87 +523,37 @@ struct SeqArgs {
     dsd_accept_params prm;
     int k, V, S;
     double c;                // log2(e) / T exactly as slice_pass used it: (double)c_hi + (double)c_lo
-    int soft;                // slice_pass accumulated Z~ shares for the call-wide tau
-    int want_top;
-    int do_rows, do_nodes;   // phases (both in one launch unless another kernel has to run in between)
     int walk;                // 0: lossless mode -- key flags only; the walk kernel does the rest
     int32_t* accepted_len;
     int32_t* accepted_path;
     dsd_accept_stats st;
 };
 
-// One workgroup per sequence.
-//   rows:  wave w takes rows w, w+16, ...: log-sum-exp from the slice partials, Z~ of the row under
-//          the call-wide tau, NormMatch from the slices' candidate lists;
-//   nodes: thread i-1 takes node i: key rule, tau_i, P(y), the test u q(y) < P(y), statistics;
-//          then the tree walk for the accepted path and what the extra token is drawn from.
-#define SEQ_TPB 512
-#define DECIDE_TPB 128
-__global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
-    __shared__ int par[DSD_MAX_K + 1], acc[DSD_MAX_K + 1], dep[DSD_MAX_K + 1], ok[DSD_MAX_K + 1];
-    __shared__ double s_tau[DSD_MAX_K + 1], s_z[DSD_MAX_K + 1];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+// Sequence b by one workgroup of nt threads (all of them call; nt >= 64): thread i takes node i
+// (0 = the root): key rule, tau_i, P(y), the test u q(y) < P(y), statistics; then every node walks
+// up to the root for its depth and for whether it and all its ancestors passed; thread 0 picks the
+// accepted path and what the extra token is drawn from.  The tree lives in LDS.
+struct SeqLds {
+    int par[DSD_MAX_K + 1], acc[DSD_MAX_K + 1], dep[DSD_MAX_K + 1], ok[DSD_MAX_K + 1];
+    double tau[DSD_MAX_K + 1], z[DSD_MAX_K + 1];
+};
+__device__ inline void seq_body(const SeqArgs& p, const AcceptWs& ws, SeqLds& L, int b, int tid, int nt) {
     const int k = p.k, R = k + 1, S = p.S;
-    if (tid <= k) {
+    for (int i = tid; i <= k; i += nt) {
         int pr = 0;
-        if (tid > 0) {
-            pr = p.parent ? p.parent[tid - 1] : tid - 1;
-            pr = pr < 0 ? 0 : (pr > tid - 1 ? tid - 1 : pr);
+        if (i > 0) {
+            pr = p.parent ? p.parent[i - 1] : i - 1;
+            pr = pr < 0 ? 0 : (pr > i - 1 ? i - 1 : pr);
         }
-        par[tid] = pr;
+        L.par[i] = pr;
     }
     __syncthreads();
-    if (p.do_rows) {
-        for (int r = wave; r < R; r += SEQ_TPB / WAVE) {
-            const size_t ridx = (size_t)b * R + r;
-            float mf = -INFINITY;
-            for (int s = lane; s < S; s += WAVE) mf = fmaxf(mf, ws.part_m[ridx * S + s]);
-            mf = wave_max_f(mf);
-            const double m = (double)mf;
-            double sum = 0.0;
-            for (int s = lane; s < S; s += WAVE) {
-                const float ms = ws.part_m[ridx * S + s];
-                if (ms > -INFINITY) sum += ws.part_s[ridx * S + s] * exp2((double)ms - m);
-            }
-            sum = wave_sum_d(sum);
-            const double lse2 = m + log2(sum);            // log2 of sum_v 2^(x_v)
-            bool has_child = false;
-            for (int c = r + 1; c <= k; ++c) has_child = has_child || par[c] == r;
-            double z = 1.0, nm = 0.0;
-            if (has_child && p.soft) {
-                const double a = 1.0 - p.prm.tau;
-                z = 0.0;
-                for (int s = lane; s < S; s += WAVE) {
-                    const float ms = ws.part_m[ridx * S + s];
-                    if (ms > -INFINITY) z += ws.part_zs[ridx * S + s] * (a == 0.0 ? 1.0 : exp2(a * ((double)ms - lse2)));
-                }
-                z = wave_sum_d(z);
-            }
-            if (has_child && p.want_top) {
-                int idt[MAXM], idq[MAXM];
-                merge_top_lists(ws.part_top_t + ridx * S * p.prm.top_m, S, p.prm.top_m, lane, idt);
-                merge_top_lists(ws.part_top_q + ridx * S * p.prm.top_m, S, p.prm.top_m, lane, idq);
-                int mine = -2;
-#pragma unroll
-                for (int i = 0; i < MAXM; ++i) mine = (lane == i && i < p.prm.top_m) ? idt[i] : mine;
-                bool hit = false;
-#pragma unroll
-                for (int j = 0; j < MAXM; ++j) hit = hit || (j < p.prm.top_m && idq[j] >= 0 && idq[j] == mine);
-                nm = (double)__popcll(__ballot(hit)) / (double)p.prm.top_m;
-            }
-            if (lane == 0) {
-                ws.row_lse[ridx] = lse2 * 0.6931471805599453094;      // natural log
-                ws.row_z[ridx] = z;
-                if (p.want_top) ws.row_nm[ridx] = nm;
-            }
+    for (int i = tid; i <= k; i += nt) {
+        if (i == 0) {
+            L.acc[0] = 1;
+            continue;
         }
-    }
-    if (!p.do_nodes) return;
-    // rows written above are read below by other threads of this workgroup
-    __threadfence_block();
-    __syncthreads();
-    if (tid >= 1 && tid <= k) {
-        const int i = tid, pr = par[i];
+        const int pr = L.par[i];
         const size_t nidx = (size_t)b * k + i - 1, ridx = (size_t)b * R + pr;
         int y = p.tokens[nidx];
         y = y < 0 ? 0 : (y >= p.V ? p.V - 1 : y);
@@ -570,9 +586,9 @@ __global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
             const double p_y = soft_weight(ln_pt, q_y, tau) / z;
             const double u = (double)p.uniforms[(size_t)b * R + i];
             const bool a = u * q_y < p_y;
-            acc[i] = a ? 1 : 0;
-            s_tau[i] = tau;
-            s_z[i] = z;
+            L.acc[i] = a ? 1 : 0;
+            L.tau[i] = tau;
+            L.z[i] = z;
             if (p.st.key_flags) p.st.key_flags[nidx] = key ? 1 : 0;
             if (p.st.node_accept) p.st.node_accept[nidx] = a ? 1 : 0;
             if (p.st.ratio) p.st.ratio[nidx] = q_y > 0.0 ? p_y / q_y : (p_y > 0.0 ? INFINITY : 0.0);
@@ -580,17 +596,17 @@ __global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
         }
     }
     if (!p.walk) return;
-    if (tid == 0) acc[0] = 1;
-    if (p.accepted_path && tid < k) p.accepted_path[(size_t)b * k + tid] = -1;
+    if (p.accepted_path)
+        for (int i = tid; i < k; i += nt) p.accepted_path[(size_t)b * k + i] = -1;
     __syncthreads();
-    if (tid <= k) {
-        int d = 0, good = acc[tid];
-        for (int n = tid; n != 0; n = par[n]) {        // parents precede children: at most k steps
+    for (int i = tid; i <= k; i += nt) {
+        int d = 0, good = L.acc[i];
+        for (int n = i; n != 0; n = L.par[n]) {        // parents precede children: at most k steps
             ++d;
-            good &= acc[par[n]];
+            good &= L.acc[L.par[n]];
         }
-        dep[tid] = d;
-        ok[tid] = good;
+        L.dep[i] = d;
+        L.ok[i] = good;
     }
     __syncthreads();
     if (tid != 0) return;
@@ -599,21 +615,21 @@ __global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
         for (;;) {
             int nxt = 0;
             for (int c = vstar + 1; c <= k; ++c)
-                if (par[c] == vstar && acc[c]) { nxt = c; break; }
+                if (L.par[c] == vstar && L.acc[c]) { nxt = c; break; }
             if (!nxt) break;
             vstar = nxt;
         }
     } else {
         for (int c = 1; c <= k; ++c)
-            if (ok[c] && dep[c] > dep[vstar]) vstar = c;
+            if (L.ok[c] && L.dep[c] > L.dep[vstar]) vstar = c;
     }
-    const int a = dep[vstar];
+    const int a = L.dep[vstar];
     p.accepted_len[b] = a;
     if (p.accepted_path)
-        for (int n = vstar, j = a - 1; n != 0; n = par[n], --j) p.accepted_path[(size_t)b * k + j] = n;
+        for (int n = vstar, j = a - 1; n != 0; n = L.par[n], --j) p.accepted_path[(size_t)b * k + j] = n;
     int child = 0;
     for (int c = vstar + 1; c <= k; ++c)
-        if (par[c] == vstar) { child = c; break; }
+        if (L.par[c] == vstar) { child = c; break; }
     ws.draw_row[b] = vstar;
     if (!child) {
         ws.draw_mode[b] = 0;
@@ -621,8 +637,155 @@ __global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
         ws.draw_z[b] = 1.0;
     } else {
         ws.draw_mode[b] = 1;
-        ws.draw_tau[b] = s_tau[child];
-        ws.draw_z[b] = s_z[child];
+        ws.draw_tau[b] = L.tau[child];
+        ws.draw_z[b] = L.z[child];
+    }
+}
+
+#define SEQ_TPB 128
+#define DECIDE_TPB 128
+__global__ void __launch_bounds__(SEQ_TPB) seq_kernel(SeqArgs p, AcceptWs ws) {
+    __shared__ SeqLds L;
+    seq_body(p, ws, L, blockIdx.x, threadIdx.x, SEQ_TPB);
+}
+
+struct RowArgs {
+    const int32_t* parent;
+    int k, S, top_m;
+    double a;                // 1 - tau of the call
+    int soft, want_top;
+};
+
+// The same for a row of at most 64 slices whose lists already sit in registers, lane l holding the
+// n keys kk[] of slice l (0 beyond its list).
+__device__ inline void merge_top_regs(const u64 (&key)[LCAP], int top_m, int lane, u64* __restrict__ cand, u64* __restrict__ out) {
+    u64 h = 0ull;
+#pragma unroll
+    for (int i = 0; i < LCAP; ++i) h = key[i] > h ? key[i] : h;
+    const u64 thr = top_m <= 8 ? group_threshold<4, u64>(h, lane, top_m) : group_threshold<2, u64>(h, lane, top_m);
+    int cnt = 0;
+#pragma unroll
+    for (int i = 0; i < LCAP; ++i) {
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(key[i] != 0ull && key[i] >= thr);
+        if (m) {
+            const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+            if (((m >> lane) & 1ull) && pos < WAVE) cand[pos] = key[i];
+            cnt += __popcll(m);
+        }
+    }
+    wave_lds_sync();
+    if (cnt <= WAVE) {
+        rank_out(cand, cnt, top_m, lane, out);
+    } else {
+        u64 last = ~0ull;
+        for (int round = 0; round < top_m; ++round) {
+            u64 best = 0ull;
+#pragma unroll
+            for (int i = 0; i < LCAP; ++i) best = (key[i] < last && key[i] > best) ? key[i] : best;
+            last = wave_max_u(best);
+            if (lane == 0) out[round] = last;
+            if (last == 0ull) last = 1ull;
+        }
+    }
+    wave_lds_sync();
+}
+
+// One workgroup of three wavefronts per (row, sequence): wave 0 forms the log-sum-exp from the slice
+// partials and Z~ of the row under the call-wide tau, waves 1 and 2 the row's top_m of the logits and of
+// the draft row from the slices' candidate lists (NormMatch).  With at most 64 slices (a vocabulary of
+// up to 131072 ids) lane l takes slice l and everything a wave needs is requested before anything is
+// waited for: one round trip to memory and a few microseconds of arithmetic, the three side by side.
+#define ROW_TPB (3 * WAVE)
+__global__ void __launch_bounds__(ROW_TPB) row_merge_kernel(RowArgs p, AcceptWs ws) {
+    __shared__ u64 cand[2][WAVE], top[2][MAXM];
+    const int r = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int R = p.k + 1, S = p.S;
+    const size_t ridx = (size_t)b * R + r;
+    const bool one = S <= WAVE;
+    const int sl = lane < S ? lane : 0;
+    double lse2 = 0.0, z = 1.0;
+    if (wave == 0) {
+        float ms1 = -INFINITY;
+        double ss1 = 0.0, zs1 = 0.0;
+        if (one) {                                        // requests first
+            ms1 = ws.part_m[ridx * S + sl];
+            ss1 = ws.part_s[ridx * S + sl];
+            if (p.soft) zs1 = ws.part_zs[ridx * S + sl];
+            if (lane >= S) ms1 = -INFINITY;
+        }
+        const bool has_child = row_has_child(p.parent, p.k, r, lane);
+        float mf = -INFINITY;
+        if (one) mf = ms1;
+        else
+            for (int s = lane; s < S; s += WAVE) mf = fmaxf(mf, ws.part_m[ridx * S + s]);
+        mf = wave_max_f(mf);
+        const double m = (double)mf;
+        double sum = 0.0;
+        if (one) {
+            if (ms1 > -INFINITY) sum = ss1 * exp2((double)ms1 - m);
+        } else {
+            for (int s = lane; s < S; s += WAVE) {
+                const float ms = ws.part_m[ridx * S + s];
+                if (ms > -INFINITY) sum += ws.part_s[ridx * S + s] * exp2((double)ms - m);
+            }
+        }
+        sum = wave_sum_d(sum);
+        lse2 = m + log2(sum);                             // log2 of sum_v 2^(x_v)
+        if (has_child && p.soft) {
+            z = 0.0;
+            if (one) {
+                if (ms1 > -INFINITY) z = zs1 * (p.a == 0.0 ? 1.0 : exp2(p.a * ((double)ms1 - lse2)));
+            } else {
+                for (int s = lane; s < S; s += WAVE) {
+                    const float ms = ws.part_m[ridx * S + s];
+                    if (ms > -INFINITY) z += ws.part_zs[ridx * S + s] * (p.a == 0.0 ? 1.0 : exp2(p.a * ((double)ms - lse2)));
+                }
+            }
+            z = wave_sum_d(z);
+        }
+    } else if (p.want_top) {
+        const int kind = wave - 1;
+        const u64* lists = (kind ? ws.part_top_q : ws.part_top_t) + ridx * S * LCAP;
+        const int32_t* cnts = ws.part_cnt + ridx * S * 2;
+        int n1 = 0;
+        ulonglong2 kk[LCAP / 2];
+        if (one) {                                        // requests first
+            n1 = cnts[2 * sl + kind];
+            const ulonglong2* src = (const ulonglong2*)(lists + (size_t)sl * LCAP);
+#pragma unroll
+            for (int i = 0; i < LCAP / 2; ++i) kk[i] = src[i];
+        }
+        if (row_has_child(p.parent, p.k, r, lane)) {      // wave-uniform
+            if (one) {
+                u64 key[LCAP];
+                const int n = lane < S ? n1 : 0;
+#pragma unroll
+                for (int i = 0; i < LCAP; ++i) key[i] = i < n ? ((i & 1) ? kk[i / 2].y : kk[i / 2].x) : 0ull;
+                merge_top_regs(key, p.top_m, lane, cand[kind], top[kind]);
+            } else {
+                merge_top_lists(lists, cnts, kind, S, p.top_m, lane, cand[kind], top[kind]);
+            }
+        } else if (lane < MAXM) {
+            top[kind][lane] = 0ull;
+        }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    double nm = 0.0;
+    if (p.want_top) {
+        const u64 mine = lane < p.top_m ? top[0][lane] : 0ull;
+        bool hit = false;
+        for (int j = 0; j < p.top_m; ++j) {
+            const u64 o = top[1][j];
+            hit = hit || (mine != 0ull && o != 0ull && key_id(o) == key_id(mine));
+        }
+        nm = (double)__popcll(__ballot(hit)) / (double)p.top_m;
+    }
+    if (lane == 0) {
+        ws.row_lse[ridx] = lse2 * 0.6931471805599453094;          // natural log
+        ws.row_z[ridx] = z;
+        if (p.want_top) ws.row_nm[ridx] = nm;
     }
 }
 
@@ -641,6 +804,7 @@ __device__ inline void draw_weight(const float* __restrict__ logits, const float
     }
 }
 
+// Workgroup (slice, sequence): the slice's mass under the distribution the extra token is drawn from.
 __global__ void __launch_bounds__(TPB)
 draw_parts_kernel(const float* __restrict__ logits, const float* __restrict__ qp, AcceptWs ws, int R, int V, int S,
                   double inv_temp) {
@@ -670,6 +834,8 @@ draw_parts_kernel(const float* __restrict__ logits, const float* __restrict__ qp
     }
 }
 
+// One workgroup per sequence: the extra token from the slice masses: the slice whose cumulative mass
+// crosses u_0 * total, then the id inside it (that slice's weights once more).
 __global__ void __launch_bounds__(TPB)
 draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const float* __restrict__ uniforms,
                  AcceptWs ws, int R, int V, int S, double inv_temp, int32_t* __restrict__ next_token) {
@@ -1091,6 +1257,14 @@ greedy_decide_kernel(const int32_t* __restrict__ tokens, const int32_t* __restri
     next_token[b] = amax[vstar];
 }
 
+// v > 0 as hi + lo with lo > 0 (hi rounded down): products of a -inf exponent with both parts then stay -inf
+static void split_down(double v, float* hi, float* lo) {
+    float h = (float)v;
+    if (v > 0.0 && (double)h >= v) h = nextafterf(h, 0.0f);
+    *hi = h;
+    *lo = (float)(v - (double)h);
+}
+
 // Carves the scratch memory of one call out of [base, ...); returns the bytes used (base may be NULL to size it).
 static size_t accept_carve(AcceptWs& ws, char* base, size_t B, size_t k, size_t S, size_t top_m) {
     const size_t BR = B * (k + 1), BK = B * k;
@@ -1098,8 +1272,9 @@ static size_t accept_carve(AcceptWs& ws, char* base, size_t B, size_t k, size_t 
     ws.part_m = bump.take<float>(BR * S);
     ws.part_s = bump.take<double>(BR * S);
     ws.part_zs = bump.take<double>(BR * S);
-    ws.part_top_t = bump.take<u64>(BR * S * top_m);
-    ws.part_top_q = bump.take<u64>(BR * S * top_m);
+    ws.part_top_t = bump.take<u64>(BR * S * LCAP);
+    ws.part_top_q = bump.take<u64>(BR * S * LCAP);
+    ws.part_cnt = bump.take<int32_t>(BR * S * 2);
     ws.row_lse = bump.take<double>(BR);
     ws.row_z = bump.take<double>(BR);
     ws.row_nm = bump.take<double>(BR);
@@ -1155,22 +1330,23 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
 
     SliceArgs sa;
     sa.logits = logits; sa.qp = draft_probs; sa.parent = parent; sa.k = k; sa.V = V; sa.S = S; sa.top_m = prm->top_m;
-    const double c = 1.4426950408889634074 * inv_temp;
-    sa.c_hi = (float)c; sa.c_lo = (float)(c - (double)sa.c_hi);
     const double tau = lossless ? 0.0 : prm->tau;         // no relaxation under the lossless tree rule
-    const double a = 1.0 - tau;
-    sa.a_hi = (float)a; sa.a_lo = (float)(a - (double)sa.a_hi);
-    sa.t_hi = (float)tau; sa.t_lo = (float)(tau - (double)sa.t_hi);
+    split_down(1.4426950408889634074 * inv_temp, &sa.c_hi, &sa.c_lo);
+    split_down(1.0 - tau, &sa.a_hi, &sa.a_lo);
+    split_down(tau, &sa.t_hi, &sa.t_lo);
     sa.soft = (tau > 0.0 && !per_node_tau) ? 1 : 0;
     sa.tau_is_one = tau == 1.0 ? 1 : 0;
     sa.want_top = prm->norm_match_kind == DSD_NM_TOP_M ? 1 : 0;
+
+    RowArgs ra;
+    ra.parent = parent; ra.k = k; ra.S = S; ra.top_m = prm->top_m; ra.a = 1.0 - tau; ra.soft = sa.soft; ra.want_top = sa.want_top;
 
     SeqArgs q;
     q.logits = logits; q.qp = draft_probs; q.tokens = draft_tokens; q.parent = parent; q.uniforms = uniforms;
     q.prm = *prm;
     q.prm.tau = tau;
     if (lossless) q.prm.tau_override = nullptr;
-    q.k = k; q.V = V; q.S = S; q.c = (double)sa.c_hi + (double)sa.c_lo; q.soft = sa.soft; q.want_top = sa.want_top;
+    q.k = k; q.V = V; q.S = S; q.c = (double)sa.c_hi + (double)sa.c_lo;
     q.walk = lossless ? 0 : 1;
     q.accepted_len = accepted_len; q.accepted_path = accepted_path; q.st = st;
 
@@ -1178,22 +1354,14 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     ProfScope ps(ctx, DSD_KC_ACCEPT);
     if (vec) slice_pass_kernel<true><<<dim3(S, R, B), WAVE, 0, s>>>(sa, ws);
     else slice_pass_kernel<false><<<dim3(S, R, B), WAVE, 0, s>>>(sa, ws);
-    if (variants || per_node_tau) {
-        // something else has to look at the rows between their log-sum-exp and the nodes' tests
-        q.do_rows = 1; q.do_nodes = 0;
-        seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
-        if (variants) {
-            row_extra_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
-            row_extra_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->norm_match_kind == DSD_NM_OVERLAP ? 1 : 0);
-        }
-        if (per_node_tau)
-            node_z_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, parent, prm->tau_override, ws, k, V, S, inv_temp);
-        q.do_rows = 0; q.do_nodes = 1;
-        seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
-    } else {
-        q.do_rows = 1; q.do_nodes = 1;
-        seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
+    row_merge_kernel<<<dim3(R, B), ROW_TPB, 0, s>>>(ra, ws);
+    if (variants) {
+        row_extra_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, draft_probs, ws, R, V, S, inv_temp);
+        row_extra_merge_kernel<<<dim3(R, B), WAVE, 0, s>>>(ws, R, S, prm->norm_match_kind == DSD_NM_OVERLAP ? 1 : 0);
     }
+    if (per_node_tau)
+        node_z_kernel<<<dim3(S, k, B), TPB, 0, s>>>(logits, draft_probs, parent, prm->tau_override, ws, k, V, S, inv_temp);
+    seq_kernel<<<B, SEQ_TPB, 0, s>>>(q, ws);
     if (lossless) {
         lossless_walk_kernel<<<B, WALK_TPB, 0, s>>>(logits, draft_probs, draft_tokens, parent, uniforms, ws, k, V, inv_temp,
                                                       accepted_len, next_token, accepted_path, st);
