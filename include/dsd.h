@@ -209,6 +209,22 @@ int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, cons
                int B, int k, int V, int32_t* accepted_len, int32_t* next_token,
                int32_t* accepted_path, const dsd_accept_stats* stats);
 
+/* dsd_accept for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same results (bit for bit: the same kernels run),
+ * but the per-slice partials of the call live in a fixed 8 MiB array in the library's device image instead
+ * of the context's growing workspace, and the call issues nothing but kernel launches on the context's
+ * stream: no hipMalloc, hipFree, memset or event.  Per-kernel timing (dsd_profile_enable) does not see it.
+ * Errors: DSD_ESHAPE when the call needs more scratch than the array holds -- about
+ * B*(k+1)*ceil(V/2048)*560 bytes; B=16, k=8 and B=4, k=32 at V=128256 fit, use dsd_accept beyond;
+ * DSD_EUNSUPPORTED on a device index above 63.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads,
+ * two contexts) race and must be serialised by the caller.  Nothing in the array has to be cleared
+ * between calls: every word a kernel reads was written by an earlier kernel of the same call. */
+int dsd_accept_noalloc(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+                       const int32_t* parent, const float* uniforms, const dsd_accept_params* params,
+                       int B, int k, int V, int32_t* accepted_len, int32_t* next_token,
+                       int32_t* accepted_path, const dsd_accept_stats* stats);
+
 /* Advances every sequence by its accepted tokens (section 2.1: x_{1:i+k} = x_{1:i} (+) y_{i+1:i+k}):
  * in every layer the K/V rows that the last dsd_stage_verify wrote for the path's nodes become
  * slots len[b] .. len[b]+a-1, and len[b] += a.  accepted_len / accepted_path are device arrays

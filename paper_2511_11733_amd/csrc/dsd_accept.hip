@@ -1300,12 +1300,37 @@ size_t accept_scratch_bytes(int B, int k, int V, int top_m) {
     return full > greedy ? full : greedy;
 }
 
-// scratch: device memory of at least accept_scratch_bytes(B, k, V, top_m) bytes, 256-byte aligned; its contents
+// ---------------------------------------------------------------------------- scratch that nobody allocates
+// For callers that must not allocate (dsd_accept_noalloc): the partials of one call live in a fixed
+// array in the library's device image.  Every GPU the library runs on holds its own copy, at its own
+// address, until the process ends; the host-side name is only a handle, the address a kernel can use
+// comes from hipGetSymbolAddress, once per device, when a context is created there.
+#define ACCEPT_STATIC_SCRATCH_BYTES (8u << 20)
+#define ACCEPT_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[ACCEPT_STATIC_SCRATCH_BYTES];
+static char* g_static_scratch[ACCEPT_MAX_DEVICES];        // per device: device address of its copy of scratch[]
+
+// Called by dsd_create with `device` current.
+int accept_static_scratch_init(int device) {
+    if (device < 0 || device >= ACCEPT_MAX_DEVICES) return DSD_OK;      // such a device simply has no static scratch
+    if (g_static_scratch[device]) return DSD_OK;
+    void* ptr = nullptr;
+    DSD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) DSD_FAIL(DSD_EHIP, "hipGetSymbolAddress returned no address for the static scratch array");
+    g_static_scratch[device] = (char*)ptr;
+    return DSD_OK;
+}
+char* accept_static_scratch(int device, size_t* bytes) {
+    *bytes = ACCEPT_STATIC_SCRATCH_BYTES;
+    return (device >= 0 && device < ACCEPT_MAX_DEVICES) ? g_static_scratch[device] : nullptr;
+}
+
+// scratch_dev: device memory of at least accept_scratch_bytes(B, k, V, top_m) bytes, 256-byte aligned; its contents
 // need not be cleared (every word read by a kernel was written by an earlier kernel of the same call)
 int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                   const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k, int V,
                   int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path, const dsd_accept_stats* stats,
-                  char* scratch) {
+                  char* scratch_dev) {
     const int R = k + 1;
     const int S = (V + SLICE - 1) / SLICE;
     hipStream_t s = ctx->stream;
@@ -1313,7 +1338,7 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
     if (stats) st = *stats;
     if (B > 65535 || R > 65535) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d exceeds 65535", B);
     if (prm->temperature == 0.0) {
-        u64* part = (u64*)scratch;
+        u64* part = (u64*)scratch_dev;
         ProfScope ps(ctx, DSD_KC_ACCEPT);
         row_argmax_kernel<<<dim3(S, R, B), TPB, 0, s>>>(logits, part, R, V, S);
         greedy_decide_kernel<<<B, DECIDE_TPB, 0, s>>>(draft_tokens, parent, part, prm->tree_mode, k, S, accepted_len,
@@ -1322,7 +1347,7 @@ int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, c
         return DSD_OK;
     }
     AcceptWs ws;
-    accept_carve(ws, scratch, B, k, S, prm->top_m);
+    accept_carve(ws, scratch_dev, B, k, S, prm->top_m);
     const double inv_temp = 1.0 / prm->temperature;
     const bool lossless = prm->tree_mode == DSD_TREE_LOSSLESS;
     const bool variants = prm->norm_match_kind == DSD_NM_OVERLAP || prm->entropy_kind == DSD_H_ROW;

@@ -35,6 +35,7 @@ extern "C" int dsd_create(int device, void* hip_stream, dsd_ctx** out) {
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
         DSD_FAIL(DSD_EUNSUPPORTED, "dsd_create: device is %s, this library is built for gfx950 only",
                  prop.gcnArchName);
+    DSD_TRY(accept_static_scratch_init(device));         // address of this device's copy of the fixed scratch array
     dsd_ctx* c = new (std::nothrow) dsd_ctx();
     if (!c) DSD_FAIL(DSD_ENOMEM, "dsd_create: host allocation");
     c->device = device;
@@ -415,26 +416,56 @@ extern "C" int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, 
 }
 
 // ----------------------------------------------------------------------------- accept
+static int accept_check(const char* who, dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+                        const float* uniforms, const dsd_accept_params* p, int B, int k, int V, int32_t* accepted_len,
+                        int32_t* next_token) {
+    const bool greedy = p && p->temperature == 0.0;      // draft_probs and uniforms are not read then
+    if (!ctx || !logits || (!draft_probs && !greedy) || !draft_tokens || (!uniforms && !greedy) || !p || !accepted_len ||
+        !next_token)
+        DSD_FAIL(DSD_EINVAL, "%s: NULL argument", who);
+    if (B < 1 || k < 1 || k > DSD_MAX_K || V < 1) DSD_FAIL(DSD_ESHAPE, "%s: B=%d k=%d V=%d", who, B, k, V);
+    if (p->top_m < 1 || p->top_m > DSD_MAX_TOP_M || p->top_m > V)
+        DSD_FAIL(DSD_ESHAPE, "%s: top_m=%d (limit %d, V=%d)", who, p->top_m, DSD_MAX_TOP_M, V);
+    if (!(p->tau >= 0.0 && p->tau <= 1.0)) DSD_FAIL(DSD_EINVAL, "%s: tau=%g outside [0,1]", who, p->tau);
+    if ((p->norm_match_kind != DSD_NM_TOP_M && p->norm_match_kind != DSD_NM_OVERLAP) ||
+        (p->entropy_kind != DSD_H_TOKEN && p->entropy_kind != DSD_H_ROW))
+        DSD_FAIL(DSD_EINVAL, "%s: norm_match_kind=%d entropy_kind=%d", who, p->norm_match_kind, p->entropy_kind);
+    if (!(p->temperature >= 0.0)) DSD_FAIL(DSD_EINVAL, "%s: temperature=%g", who, p->temperature);
+    if (p->tree_mode != DSD_TREE_LONGEST && p->tree_mode != DSD_TREE_FIRST_ACCEPTED && p->tree_mode != DSD_TREE_LOSSLESS)
+        DSD_FAIL(DSD_EINVAL, "%s: tree_mode=%d", who, p->tree_mode);
+    return DSD_OK;
+}
+
 extern "C" int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                           const int32_t* parent, const float* uniforms, const dsd_accept_params* p, int B, int k,
                           int V, int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path,
                           const dsd_accept_stats* stats) {
-    const bool greedy = p && p->temperature == 0.0;      // draft_probs and uniforms are not read then
-    if (!ctx || !logits || (!draft_probs && !greedy) || !draft_tokens || (!uniforms && !greedy) || !p || !accepted_len ||
-        !next_token)
-        DSD_FAIL(DSD_EINVAL, "dsd_accept: NULL argument");
-    if (B < 1 || k < 1 || k > DSD_MAX_K || V < 1) DSD_FAIL(DSD_ESHAPE, "dsd_accept: B=%d k=%d V=%d", B, k, V);
-    if (p->top_m < 1 || p->top_m > DSD_MAX_TOP_M || p->top_m > V)
-        DSD_FAIL(DSD_ESHAPE, "dsd_accept: top_m=%d (limit %d, V=%d)", p->top_m, DSD_MAX_TOP_M, V);
-    if (!(p->tau >= 0.0 && p->tau <= 1.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: tau=%g outside [0,1]", p->tau);
-    if ((p->norm_match_kind != DSD_NM_TOP_M && p->norm_match_kind != DSD_NM_OVERLAP) ||
-        (p->entropy_kind != DSD_H_TOKEN && p->entropy_kind != DSD_H_ROW))
-        DSD_FAIL(DSD_EINVAL, "dsd_accept: norm_match_kind=%d entropy_kind=%d", p->norm_match_kind, p->entropy_kind);
-    if (!(p->temperature >= 0.0)) DSD_FAIL(DSD_EINVAL, "dsd_accept: temperature=%g", p->temperature);
-    if (p->tree_mode != DSD_TREE_LONGEST && p->tree_mode != DSD_TREE_FIRST_ACCEPTED && p->tree_mode != DSD_TREE_LOSSLESS)
-        DSD_FAIL(DSD_EINVAL, "dsd_accept: tree_mode=%d", p->tree_mode);
+    DSD_TRY(accept_check("dsd_accept", ctx, logits, draft_probs, draft_tokens, uniforms, p, B, k, V, accepted_len, next_token));
     DSD_HIP(hipSetDevice(ctx->device));
     DSD_TRY(dsd_ws_reserve(ctx, accept_scratch_bytes(B, k, V, p->top_m)));
     return accept_launch(ctx, logits, draft_probs, draft_tokens, parent, uniforms, p, B, k, V, accepted_len,
                          next_token, accepted_path, stats, ctx->ws);
+}
+
+extern "C" int dsd_accept_noalloc(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
+                                  const int32_t* parent, const float* uniforms, const dsd_accept_params* p, int B, int k,
+                                  int V, int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path,
+                                  const dsd_accept_stats* stats) {
+    DSD_TRY(accept_check("dsd_accept_noalloc", ctx, logits, draft_probs, draft_tokens, uniforms, p, B, k, V, accepted_len,
+                         next_token));
+    size_t have = 0;
+    char* scratch_dev = accept_static_scratch(ctx->device, &have);
+    if (!scratch_dev) DSD_FAIL(DSD_EUNSUPPORTED, "dsd_accept_noalloc: device %d has no static scratch", ctx->device);
+    const size_t need = accept_scratch_bytes(B, k, V, p->top_m);
+    if (need > have)
+        DSD_FAIL(DSD_ESHAPE, "dsd_accept_noalloc: B=%d k=%d V=%d top_m=%d need %zu bytes of scratch, the fixed array holds %zu; "
+                 "use dsd_accept", B, k, V, p->top_m, need, have);
+    DSD_HIP(hipSetDevice(ctx->device));
+    // per-kernel timing creates events: not on this path
+    const bool prof = ctx->prof_on;
+    ctx->prof_on = false;
+    const int rc = accept_launch(ctx, logits, draft_probs, draft_tokens, parent, uniforms, p, B, k, V, accepted_len,
+                                 next_token, accepted_path, stats, scratch_dev);
+    ctx->prof_on = prof;
+    return rc;
 }

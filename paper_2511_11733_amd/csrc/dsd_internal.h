@@ -203,6 +203,8 @@ int kv_export_launch(dsd_ctx* ctx, const dsd_kv* kv, int layer, int first, int n
 int kv_commit_launch(dsd_ctx* ctx, dsd_kv* kv, const int32_t* acc_len, const int32_t* acc_path, int B, int k);
 // accept (dsd_accept.hip)
 size_t accept_scratch_bytes(int B, int k, int V, int top_m);
+int accept_static_scratch_init(int device);                  // with `device` current; once per device
+char* accept_static_scratch(int device, size_t* bytes);      // device address of this device's static scratch (NULL if none)
 int accept_launch(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                   const int32_t* parent, const float* uniforms, const dsd_accept_params* prm, int B, int k,
                   int V, int32_t* accepted_len, int32_t* next_token, int32_t* accepted_path,

@@ -23,7 +23,7 @@ DSD_MAX_K, DSD_MAX_TOP_M = 64, 16
 EXPORTS = [
     "dsd_last_error", "dsd_create", "dsd_destroy", "dsd_set_stream", "dsd_weights_create", "dsd_weights_destroy",
     "dsd_kv_create", "dsd_kv_destroy", "dsd_kv_import", "dsd_kv_export", "dsd_kv_set_len", "dsd_kv_get_len",
-    "dsd_stage_verify", "dsd_accept", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read", "dsd_stream_probe",
+    "dsd_stage_verify", "dsd_accept", "dsd_accept_noalloc", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read", "dsd_stream_probe",
 ]
 KERNEL_CLASSES = ["qkv", "attn", "attn_combine", "oproj", "gateup", "down", "head", "accept", "other", "stage"]
 
@@ -79,6 +79,8 @@ def load() -> C.CDLL:
         "dsd_stage_verify": [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i64],
         "dsd_accept": [vp, vp, vp, vp, vp, vp, C.POINTER(AcceptParams), i32, i32, i32, vp, vp, vp,
                        C.POINTER(AcceptStats)],
+        "dsd_accept_noalloc": [vp, vp, vp, vp, vp, vp, C.POINTER(AcceptParams), i32, i32, i32, vp, vp, vp,
+                               C.POINTER(AcceptStats)],
         "dsd_kv_commit": [vp, vp, vp, vp, i32, i32],
         "dsd_profile_enable": [vp, i32],
         "dsd_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
@@ -256,6 +258,20 @@ def dsd_accept(ctx: Context, logits: torch.Tensor, draft_probs: torch.Tensor, dr
                               _ptr(next_token, torch.int32, "next_token"),
                               _ptr(accepted_path, torch.int32, "accepted_path"),
                               None if stats is None else C.byref(stats)), "dsd_accept")
+
+
+def dsd_accept_noalloc(ctx: Context, logits: torch.Tensor, draft_probs: torch.Tensor, draft_tokens: torch.Tensor,
+                       parent: Optional[torch.Tensor], uniforms: torch.Tensor, params: AcceptParams, B: int, k: int, V: int,
+                       accepted_len: torch.Tensor, next_token: torch.Tensor, accepted_path: Optional[torch.Tensor] = None,
+                       stats: Optional[AcceptStats] = None) -> None:
+    _check(ctx.lib.dsd_accept_noalloc(ctx.h, _ptr(logits, torch.float32, "logits"),
+                                      _ptr(draft_probs, torch.float32, "draft_probs"),
+                                      _ptr(draft_tokens, torch.int32, "draft_tokens"), _ptr(parent, torch.int32, "parent"),
+                                      _ptr(uniforms, torch.float32, "uniforms"), C.byref(params), B, k, V,
+                                      _ptr(accepted_len, torch.int32, "accepted_len"),
+                                      _ptr(next_token, torch.int32, "next_token"),
+                                      _ptr(accepted_path, torch.int32, "accepted_path"),
+                                      None if stats is None else C.byref(stats)), "dsd_accept_noalloc")
 
 
 def dsd_kv_commit(ctx: Context, kv: KVCache, accepted_len: torch.Tensor, accepted_path: Optional[torch.Tensor],
