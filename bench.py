@@ -111,15 +111,18 @@ def dominant_kernel(cfg, kern, per_layer, total_bytes):
     the gate/up GEMM (54 % of a layer's weight bytes)."""
     m = cfg.model
     M = cfg.B * cfg.k
-    if kern.get("stage", 0.0) > 0.0:
-        return ("stage", total_bytes, "stage_persist_kernel (all layers of the block)", "stage_persist_kernel")
     if M <= 10 and m.d // 16 <= 256:      # the library's switch-over between its two GEMM paths
         return ("gateup", per_layer["gateup"],
                 "gemm_skinny_kernel<1, 2, A_F32_GAIN, EPI_SWIGLU, 4> (RMSNorm + gate/up GEMM + SiLU*up, one launch)",
                 "gemm_skinny_kernel<1, 2, 0, 1")
     mt = (M + 15) // 16
     mt = {1: 2, 5: 6, 7: 8}.get(mt, mt)
-    twc = 8 if -(-(2 * (m.F // 16)) // 16) * 5 >= 256 * 4 else 4
+    # computing waves per workgroup as the library picks them: least work on the busiest of the 256 compute units
+    twc, best = 4, None
+    for t in range(4, 9):
+        cost = -(-(-(-(m.F // 16) // t)) // 256) * t
+        if best is None or cost <= best:
+            twc, best = t, cost
     return ("gateup", per_layer["gateup"],
             f"act_panel_kernel + gemm_tiled_kernel<{mt}, {twc}, TE_SWIGLU> (RMSNorm + gate/up GEMM + SiLU*up; the time "
             "is that of both launches)", f"gemm_tiled_kernel<{mt}, {twc}, 1>")

@@ -107,8 +107,7 @@ const char* dsd_last_error(void);
  * The context owns a workspace that grows on demand (allocation happens inside the first
  * call that needs more, which then synchronises).  dsd_destroy frees it.
  * Read from the environment here, for testing: DSD_PATH=simple (generic kernels also for bf16
- * models), DSD_PERSIST=1 (single-kernel form of the pass for up to 8 rows), DSD_NO_TILED
- * (no activation panels: one workgroup per column tile at every row count). */
+ * models), DSD_NO_TILED (no activation panels: one workgroup per column tile at every row count). */
 int dsd_create(int device, void* hip_stream, dsd_ctx** out);
 int dsd_destroy(dsd_ctx* ctx);
 int dsd_set_stream(dsd_ctx* ctx, void* hip_stream);
@@ -251,7 +250,6 @@ enum dsd_kernel_class {
     DSD_KC_HEAD,         /* final RMSNorm + LM head                          */
     DSD_KC_ACCEPT,       /* all kernels of dsd_accept                        */
     DSD_KC_OTHER,        /* row load / store                                 */
-    DSD_KC_STAGE,        /* the whole block of layers as one persistent kernel (<= 16 rows) */
     DSD_KC_COUNT
 };
 int dsd_profile_enable(dsd_ctx* ctx, int on);

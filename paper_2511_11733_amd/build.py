@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdsd.so")
-SOURCES = ["dsd_api.hip", "dsd_kv.hip", "dsd_simple.hip", "dsd_accept.hip", "dsd_stage_bf16.hip", "dsd_stage_persist.hip", "dsd_gemm_tiled.hip"]
+SOURCES = ["dsd_api.hip", "dsd_kv.hip", "dsd_simple.hip", "dsd_accept.hip", "dsd_stage_bf16.hip", "dsd_gemm_tiled.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unused-value"]
 

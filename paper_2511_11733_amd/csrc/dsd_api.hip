@@ -45,15 +45,8 @@ extern "C" int dsd_create(int device, void* hip_stream, dsd_ctx** out) {
     const char* p = getenv("DSD_PATH");
     c->force_simple = p && strcmp(p, "simple") == 0;
     c->prof_on = false;
-    // The single-kernel (persistent) form of the pass is opt-in: on this hardware its grid barriers cost
-    // more than the kernel boundaries they replace.
-    const char* pp = getenv("DSD_PERSIST");
-    c->no_persist = !(pp && strcmp(pp, "1") == 0);
     c->no_tiled = getenv("DSD_NO_TILED") != nullptr;
     c->n_cu = prop.multiProcessorCount;
-    c->bar_dev = nullptr;
-    c->bar_base = 0;
-    c->abort_host = nullptr;
     *out = c;
     return DSD_OK;
 }
@@ -64,8 +57,6 @@ extern "C" int dsd_destroy(dsd_ctx* ctx) {
     hipStreamSynchronize(ctx->stream);
     prof_drop(ctx);
     if (ctx->ws) hipFree(ctx->ws);
-    if (ctx->bar_dev) hipFree(ctx->bar_dev);
-    if (ctx->abort_host) hipHostFree(ctx->abort_host);
     delete ctx;
     return DSD_OK;
 }
@@ -236,7 +227,7 @@ extern "C" int dsd_weights_create(dsd_ctx* ctx, const dsd_model_desc* desc, cons
     dsd_weights* w = new (std::nothrow) dsd_weights();
     if (!w) DSD_FAIL(DSD_ENOMEM, "dsd_weights_create: host allocation");
     w->desc = *desc;
-    w->embed = w->gf = w->lm = w->lm_t = w->layer_table = nullptr;
+    w->embed = w->gf = w->lm = w->lm_t = nullptr;
     w->layers.resize(desc->n_layers);
     for (auto& l : w->layers) memset(&l, 0, sizeof(l));
     w->tiled = desc->dtype == DSD_BF16 && !ctx->force_simple && mfma_supported(desc);

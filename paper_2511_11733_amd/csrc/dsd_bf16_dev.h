@@ -1,5 +1,5 @@
-// Device-side building blocks of the bf16 verification pass, shared by the per-step kernels
-// (dsd_stage_bf16.hip) and the persistent stage kernel (dsd_stage_persist.hip).
+// Device-side building blocks of the bf16 verification pass, shared by its translation units
+// (dsd_stage_bf16.hip, dsd_gemm_tiled.hip).
 #pragma once
 
 #include "dsd_internal.h"
@@ -214,134 +214,6 @@ struct AttnArgs {
     int rows_pad;          // multiple of 16, >= k*G
     float scale_log2e;
 };
-
-// One wavefront: keys [run*keys_per_wave, +keys_per_wave) of (sequence b, kv head hk) against the
-// query rows [row0, row0 + 16*RT) of that kv head (row r = t*G + head-in-group).  S^T = K Q^T puts
-// keys on the M side, so the 8 scores a lane holds (tile 0 keys 4g..4g+3, tile 1 keys 4g..4g+3 of
-// row c) are exactly its share of the P^T operand of O^T = V^T P^T.
-template <int RT>
-__device__ __forceinline__ void attn_run(const AttnArgs& p, int b, int hk, int run, int row0, int lane) {
-    const int c = lane & 15, g = lane >> 4;
-    const int L = p.len[b];
-    const int nkeys = min(L + p.k, p.g.S);
-    const int rows = p.k * p.G;
-    const int j_begin = run * p.keys_per_wave;
-    const int j_end = min(j_begin + p.keys_per_wave, nkeys);
-    const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad + row0;
-
-    bf16x8 qh[RT][4], ql[RT][4];
-    uint64_t vis[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        const int r = row0 + rt * 16 + c;
-        const int t = r / p.G, hq = hk * p.G + r % p.G;
-        vis[rt] = 0;
-        if (r < rows) vis[rt] = p.mask ? p.mask[t] : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1ull));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if (r < rows) {
-                const float* src = p.q + ((size_t)(b * p.k + t) * p.Hq + hq) * 128 + j * 32 + g * 8;
-                const float4 v0 = *(const float4*)src, v1 = *(const float4*)(src + 4);
-                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
-                v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
-            }
-            split8(v, &qh[rt][j], &ql[rt][j]);
-        }
-    }
-    f32x4 o[8][RT];
-#pragma unroll
-    for (int h = 0; h < 8; ++h)
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) o[h][rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float mrow[RT], lrow[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        mrow[rt] = -INFINITY;
-        lrow[rt] = 0.f;
-    }
-    const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
-    const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
-
-    for (int j0 = j_begin; j0 < j_end; j0 += 32) {
-        f32x4 s[2][RT];
-#pragma unroll
-        for (int tl = 0; tl < 2; ++tl) {
-            bf16x8 kf[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                kf[j] = __builtin_bit_cast(bf16x8, *(const uint4*)(kbase + (size_t)(j0 + tl * 16) * 128 + j * 512 + lane * 8));
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    a = mfma16(kf[j], qh[rt][j], a);
-                    a = mfma16(kf[j], ql[rt][j], a);
-                }
-                s[tl][rt] = a;
-            }
-        }
-        bf16x8 vf[8];
-        const bf16_t* vblk = vbase + (size_t)(j0 >> 5) * (32 * 128) + lane * 8;
-#pragma unroll
-        for (int h = 0; h < 8; ++h) vf[h] = __builtin_bit_cast(bf16x8, *(const uint4*)(vblk + h * 512));
-
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = j0 + tl * 16 + g * 4 + i;
-                    bool ok = key < L;
-                    if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
-                    const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
-                    s[tl][rt][i] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-            const float mnew = fmaxf(mrow[rt], mx);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = exp2f(mrow[rt] - muse);      // 0 when mrow was -inf
-            mrow[rt] = mnew;
-            float pv[8];
-            float ps = 0.f;
-#pragma unroll
-            for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float e = exp2f(s[tl][rt][i] - muse);
-                    pv[tl * 4 + i] = e;
-                    ps += e;
-                }
-            lrow[rt] = lrow[rt] * alpha + ps;
-            bf16x8 ph, pl;
-            split8(pv, &ph, &pl);
-#pragma unroll
-            for (int h = 0; h < 8; ++h) {
-                o[h][rt] *= alpha;
-                o[h][rt] = mfma16(vf[h], ph, o[h][rt]);
-                o[h][rt] = mfma16(vf[h], pl, o[h][rt]);
-            }
-        }
-    }
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        float l = lrow[rt];
-        l += __shfl_xor(l, 16, WAVE);
-        l += __shfl_xor(l, 32, WAVE);
-        const int r = rt * 16 + c;
-        if (g == 0) {
-            p.part_ml[(unit + r) * 2] = mrow[rt];
-            p.part_ml[(unit + r) * 2 + 1] = l;
-        }
-#pragma unroll
-        for (int h = 0; h < 8; ++h) *(f32x4*)(p.part_o + (unit + r) * 128 + h * 16 + g * 4) = o[h][rt];
-    }
-}
 
 // Merge of the key runs of one query row r of (sequence b, kv head hk):
 //   out[m][hq*128 + e] = sum_runs 2^(m_run - M) O_run[e] / sum_runs 2^(m_run - M) l_run

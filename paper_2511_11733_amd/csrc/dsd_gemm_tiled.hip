@@ -24,6 +24,8 @@
 //     issued by hand (inline asm + explicit s_waitcnt counts, see gload16 / vm_wait); a read stream
 //     of this kind saturates HBM with 16 KiB in flight per compute unit, so the depth is set by the
 //     registers the row count leaves, not by latency.
+#include <stdlib.h>
+
 #include "dsd_bf16_dev.h"
 
 #define TP 4             // panel-fetching waves per workgroup
@@ -141,7 +143,7 @@ __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* 
 // the panel.  More computing waves per workgroup mean fewer workgroups fetching the same panel.  The
 // second launch bound is waves per SIMD: two resident workgroups for the smallest tiles.
 template <int MT, int TWC, int EPI>
-__global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 : 2)) gemm_tiled_kernel(TArgs p) {
+__global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 2)) gemm_tiled_kernel(TArgs p) {
     extern __shared__ uint4 lds[];                    // 2 panel buffers of 4*MT*64 uint4, a table of 128 floats
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
@@ -202,7 +204,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC == 8 ? 3 : (MT <= 3 ? 4 :
     // weight fragments in flight per wave: 16 (8 k-steps); 8 where the registers are the limit: up to 3
     // row tiles run four waves per SIMD (128 registers each), 8 computing waves with 6 or 8 row
     // tiles three (170 each).  A FIFO of 32 was measured at 8 row tiles: no faster (the fill takes longer).
-    constexpr int NF = (MT <= 3 || (TWC == 8 && MT > 4)) ? 8 : 16;
+    constexpr int NF = (MT <= 3 || (TWC > 4 && MT > 4)) ? 8 : 16;
     u32x4 fifo[NF];
     int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
 #pragma unroll
@@ -456,6 +458,26 @@ static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit)
 template <int EPI>
 static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, int ksplit) {
     const int mt = (p.M + 15) / 16;
+    if constexpr (EPI == TE_SWIGLU) {                    // gate/up: any number of computing waves from 4 to 8 (see choose_twc_pairs)
+        if (twc >= 5 && twc <= 7) {
+#define TILED_CASE(T)                                                                    \
+    case T:                                                                              \
+        switch (mt) {                                                                    \
+            case 1: case 2: return tiled_launch<2, T, EPI>(s, p, n_blocks, ksplit);      \
+            case 3: return tiled_launch<3, T, EPI>(s, p, n_blocks, ksplit);              \
+            case 4: return tiled_launch<4, T, EPI>(s, p, n_blocks, ksplit);              \
+            case 5: case 6: return tiled_launch<6, T, EPI>(s, p, n_blocks, ksplit);      \
+            case 7: case 8: return tiled_launch<8, T, EPI>(s, p, n_blocks, ksplit);      \
+            default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: %d rows", p.M);             \
+        }
+            switch (twc) {
+                TILED_CASE(5)
+                TILED_CASE(6)
+                TILED_CASE(7)
+            }
+#undef TILED_CASE
+        }
+    }
     if (twc == 8) {
         switch (mt) {
             case 1: case 2: return tiled_launch<2, 8, EPI>(s, p, n_blocks, ksplit);
@@ -488,6 +510,24 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static int choose_twc(int M, int n_tiles16, int n_cu, bool k_sliced) {
     if ((M + 15) / 16 > 4 && k_sliced) return 4;
     return (long)ceil_div(n_tiles16, 8 * NTW) * 5 >= (long)n_cu * 4 ? 8 : 4;
+}
+
+// Computing waves per workgroup of the gate/up GEMM (a wave owns one (gate, up) pair of column tiles):
+// the count from 4 to 8 that leaves the least work on the busiest compute unit; equal counts go to the larger workgroup (fewer fetches of
+// the panel).  F = 28672 on 256 compute units: 1792 pairs = 7 per unit exactly, one round of 256
+// workgroups of 7 (8 waves would leave 32 units idle: 179.9 against 174.8 us per layer at 48 rows).
+static int choose_twc_pairs(int n_pairs, int n_cu) {
+    int best = 4;
+    long best_cost = -1;
+    for (int twc = 4; twc <= 8; ++twc) {
+        const long n_wg = ceil_div(n_pairs, twc);
+        const long cost = ((n_wg + n_cu - 1) / n_cu) * twc;      // pairs on the busiest compute unit
+        if (best_cost < 0 || cost <= best_cost) {
+            best = twc;
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 // K split of a matrix with too few column blocks to fill the chip: the number of slices (a divisor
@@ -595,7 +635,7 @@ int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.n_ssq = K / 128; p.eps = eps; p.panel_out = (unsigned short*)panel_h; p.N = F; p.up_tile_off = F / 16;
     // fused SiLU*up needs the whole K in one workgroup: no K split
-    const int twc = choose_twc(M, 2 * (F / 16), ctx->n_cu, false);
+    const int twc = choose_twc_pairs(F / 16, ctx->n_cu);
     return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, twc, ceil_div(F / 16, twc * NTW / 2), 1);
 }
 

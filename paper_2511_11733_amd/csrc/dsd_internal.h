@@ -92,13 +92,8 @@ struct dsd_ctx {
     bool force_simple;  // DSD_PATH=simple: run the generic kernels also for bf16 models
     bool prof_on;
     std::vector<ProfRec> prof;
-    // persistent stage kernel: grid-barrier words and their bookkeeping
-    bool no_persist;               // true unless DSD_PERSIST=1: run one kernel per step
     bool no_tiled;                 // DSD_NO_TILED set: the one-workgroup-per-tile GEMMs at every row count (testing)
     int n_cu;
-    unsigned* bar_dev;             // [256] per-workgroup barrier flags, [256] abort word
-    unsigned bar_base;             // barriers passed so far
-    int* abort_host;               // pinned
 };
 
 // Brackets the launches of one scope with a pair of events when profiling is on.
@@ -133,7 +128,6 @@ struct dsd_weights {
     void* gf;
     void* lm;
     void* lm_t;
-    void* layer_table;  // device array of per-layer pointers for the persistent kernel
     std::vector<LayerW> layers;
     std::vector<void*> allocs;
 };
@@ -174,12 +168,6 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors);
 int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
                       const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B,
                       int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
-// persistent form for up to 16 rows (dsd_stage_persist.hip)
-int persist_supported(const dsd_model_desc* d);
-int persist_build_layer_table(dsd_weights* w);
-int persist_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
-                         const uint64_t* tree_mask, const int32_t* depth, int B, int k, void* hidden_out,
-                         float* logits, int64_t logits_seq_stride);
 // weight-streaming GEMMs for TILED_MIN_ROWS..128 rows (dsd_gemm_tiled.hip)
 #define TILED_MIN_ROWS 11
 int tiled_supported(const dsd_model_desc* d);

@@ -104,7 +104,6 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors) 
     DSD_HIP(hipMemcpyAsync(&n_bad, bad, 4, hipMemcpyDeviceToHost, ctx->stream));
     DSD_HIP(hipStreamSynchronize(ctx->stream));
     if (n_bad) DSD_FAIL(DSD_EUNSUPPORTED, "%d weight fragments hold values that are not finite or exceed 65504 in magnitude", n_bad);
-    if (persist_supported(&D)) DSD_TRY(persist_build_layer_table(w));
     return DSD_OK;
 }
 
@@ -256,54 +255,54 @@ static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks, int n_c
 }
 
 // ============================================================================ attention
-// One wavefront owns a run of keys of one (sequence, kv head) and RT tiles of 16 of its k*G query
-// rows; the partial (max, sum, O) of every run goes to scratch and attn_combine_kernel merges the
-// runs.  K and V never pass through registers on their way in: each step of 32 keys (8 KiB of K,
-// 8 KiB of V, already in MFMA operand order per lane) is fetched global -> LDS directly into one of
-// two stages private to the wave, one step ahead of the arithmetic, so that a wave needs no partner
-// to hide memory latency and no barrier.  The caches are stored in that operand order, so a step is
-// two contiguous 8 KiB pieces.  Stage layout: 16 fragments of 1 KiB (lane l at 16*l): K tile 0
-// features 0..31, 32..63, 64..95, 96..127, K tile 1 likewise, then V features 16h..16h+15.
-// With several row groups (more than RT*16 query rows per kv head, e.g. a 32-node tree) the waves
-// that walk the same run for different row groups sit in the same workgroup whenever the workgroup
-// size allows, so that the run's K and V come from HBM once and from the compute unit's caches the
-// second time (spread over workgroups they land on different XCDs, each with an L2 of its own):
-// wave w = (run in the workgroup) * n_rowgroups + rowgroup.  Otherwise blockIdx.x = (group of
-// blockDim.x/64 runs) * n_rowgroups + rowgroup.
+// A run of keys of one (sequence, kv head) is walked in steps of 32 keys by n_rg wavefronts at once,
+// each holding RT tiles of 16 of the k*G query rows (a row group); the partial (max, sum, O) of every
+// (run, row group) goes to scratch and attn_combine_kernel merges the runs.  K and V never pass
+// through registers on their way in: each step (8 KiB of K, 8 KiB of V, already in MFMA operand order
+// per lane) is fetched global -> LDS directly into one of two stages that the run's waves share,
+// one step ahead of the arithmetic, every wave bringing its share of the step's 16 fragments; one
+// workgroup barrier per step hands a stage over.  So K and V of a run come from memory once however
+// many query rows there are, and small row groups mean several waves per SIMD, whose matrix, vector
+// and LDS instructions overlap (one wave alone issues them one after the other).  The caches are
+// stored in operand order, so a step is two contiguous 8 KiB pieces.  Stage layout: 16 fragments of
+// 1 KiB (lane l at 16*l): K tile 0 features 0..31, 32..63, 64..95, 96..127, K tile 1 likewise, then V
+// features 16h..16h+15.  A workgroup holds rpw runs: wave w = (run in the workgroup) * n_rg + row group.
 #define ATT_STAGE_BYTES 16384
 
+// this wave's share of the fragments of the step at key j0: fragment f for f = rg, rg + n_rg, ...
 __device__ __forceinline__ void attn_fetch(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int j0,
-                                           unsigned stage, int lane) {
+                                           unsigned stage, int lane, int rg, int n_rg) {
     const bf16_t* kt = kbase + (size_t)j0 * 128 + lane * 8;           // two tiles of 16 keys, 4 fragments each
-#pragma unroll
-    for (int f = 0; f < 8; ++f) gload16_lds(stage + f * 1024, kt + f * 512);
     const bf16_t* vb = vbase + (size_t)(j0 >> 5) * (32 * 128) + lane * 8;
-#pragma unroll
-    for (int h = 0; h < 8; ++h) gload16_lds(stage + 8192 + h * 1024, vb + h * 512);
+    for (int f = rg; f < 16; f += n_rg) {
+        if (f < 8) gload16_lds(stage + f * 1024, kt + f * 512);
+        else gload16_lds(stage + f * 1024, vb + (f - 8) * 512);
+    }
 }
 
 template <int RT>
-__global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowgroups) {
-    extern __shared__ uint4 att_lds[];                // per wave: 2 stages of ATT_STAGE_BYTES
+__global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_rg, int rpw) {
+    extern __shared__ uint4 att_lds[];                // per run of the workgroup: 2 stages of ATT_STAGE_BYTES
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int wpw = blockDim.x >> 6, hk = blockIdx.y, b = blockIdx.z;
-    const bool together = wpw % n_rowgroups == 0;
-    const int rg = together ? wave % n_rowgroups : blockIdx.x % n_rowgroups;
-    const int run = together ? blockIdx.x * (wpw / n_rowgroups) + wave / n_rowgroups : (blockIdx.x / n_rowgroups) * wpw + wave;
-    if (run >= p.n_runs) return;
+    const int hk = blockIdx.y, b = blockIdx.z;
+    const int rg = wave % n_rg, rloc = wave / n_rg;
+    const int run = blockIdx.x * rpw + rloc;
     const int row0 = rg * RT * 16;
     const int L = p.len[b];
     const int nkeys = min(L + p.k, p.g.S);
     const int rows = p.k * p.G;
-    const int j_begin = run * p.keys_per_wave;
+    const bool in_grid = run < p.n_runs;
+    const int j_begin = min(run * p.keys_per_wave, nkeys);
     const int j_end = min(j_begin + p.keys_per_wave, nkeys);
+    // every wave of the workgroup makes as many turns (one barrier each) as the workgroup's first run has steps
+    const int jb0 = min(blockIdx.x * rpw * p.keys_per_wave, nkeys);
+    const int n_steps = (min(jb0 + p.keys_per_wave, nkeys) - jb0 + 31) >> 5;
     const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad + row0;
     const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
     const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
-    const uint4* stage_ptr = att_lds + (size_t)wave * (2 * ATT_STAGE_BYTES / 16);
+    const uint4* stage_ptr = att_lds + (size_t)rloc * (2 * ATT_STAGE_BYTES / 16);
     const unsigned stage_addr = (unsigned)(size_t)stage_ptr;      // low half of a flat LDS pointer = LDS address
-    if (j_begin < j_end) attn_fetch(kbase, vbase, j_begin, stage_addr, lane);
 
     bf16x8 qh[RT][4], ql[RT][4];
     uint64_t vis[RT];
@@ -338,14 +337,14 @@ __global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowg
     }
     // the loads of the queries above are the compiler's and complete by its own waits; from here on
     // the only vector memory operations in flight are the stage fetches
-    int st = 0;
-    for (int j0 = j_begin; j0 < j_end; j0 += 32, st ^= 1) {
-        if (j0 + 32 < j_end) {
-            attn_fetch(kbase, vbase, j0 + 32, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane);
-            vm_wait_all<16>();                        // this step's 16 fetches are older than those
-        } else {
-            vm_wait_all<0>();
-        }
+    vm_wait_all<0>();
+    if (j_begin < j_end) attn_fetch(kbase, vbase, j_begin, stage_addr, lane, rg, n_rg);
+    for (int step = 0; step < n_steps; ++step) {
+        const int j0 = j_begin + step * 32, st = step & 1;
+        vm_wait_all<0>();                             // this wave's share of the step has landed
+        __syncthreads();                              // so has everybody's; and the other stage is read no more
+        if (j0 + 32 < j_end) attn_fetch(kbase, vbase, j0 + 32, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane, rg, n_rg);
+        if (j0 >= j_end) continue;                    // a shorter run of the same workgroup: barriers only
         const uint4* sp = stage_ptr + st * (ATT_STAGE_BYTES / 16) + lane;
         f32x4 s[2][RT];
 #pragma unroll
@@ -421,6 +420,7 @@ __global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowg
             }
         }
     }
+    if (!in_grid) return;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         float l = lrow[rt];
@@ -444,8 +444,8 @@ __global__ void __launch_bounds__(256) attn_stream_kernel(AttnArgs p, int n_rowg
 }
 
 template <int RT>
-static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int waves_per_wg, int Hkv, int B) {
-    const size_t lds = (size_t)waves_per_wg * 2 * ATT_STAGE_BYTES;
+static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int rpw, int Hkv, int B) {
+    const size_t lds = (size_t)rpw * 2 * ATT_STAGE_BYTES;
     auto kern = attn_stream_kernel<RT>;
     // once per instantiation and process: the limit is a property of the function, and setting it
     // again on every call would put a non-stream call into a caller's graph capture
@@ -454,11 +454,8 @@ static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int waves_per
         DSD_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         raised = true;
     }
-    // same test as in the kernel: row groups of a run share a workgroup when they fit evenly
-    const int runs_per_wg = waves_per_wg % n_rg == 0 ? waves_per_wg / n_rg : waves_per_wg;
-    const int n_wg = waves_per_wg % n_rg == 0 ? (t.n_runs + runs_per_wg - 1) / runs_per_wg
-                                              : ((t.n_runs + waves_per_wg - 1) / waves_per_wg) * n_rg;
-    kern<<<dim3(n_wg, Hkv, B), waves_per_wg * 64, lds, s>>>(t, n_rg);
+    const int n_wg = (t.n_runs + rpw - 1) / rpw;
+    kern<<<dim3(n_wg, Hkv, B), n_rg * rpw * 64, lds, s>>>(t, n_rg, rpw);
     return DSD_OK;
 }
 
@@ -556,18 +553,19 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         }
         return DSD_OK;
     }
-    if (hidden_in && M <= 8 && w->layer_table && !ctx->no_persist) {
-        const int rc = persist_stage_verify(ctx, w, kv, hidden_in, tree_mask, depth, B, k, hidden_out, logits, logits_seq_stride);
-        if (rc != DSD_EUNSUPPORTED) return rc;      // else: one kernel per step
-    }
     if (!hidden_in && (!D.has_embed || !draft_tokens))
         DSD_FAIL(DSD_EINVAL, "bf16 path: neither hidden_in nor (embedding table, draft_tokens)");
     const int rows = k * G;
     const int n_rt = (rows + 15) / 16;       // 16-row tiles of query rows per kv head
     if (n_rt > 32) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: k*G = %d query rows per kv head exceed 512", rows);
-    // a wave takes at most 4 row tiles (registers); more rows are split into row groups
-    const int n_rg = (n_rt + 3) / 4;
-    const int RT = (n_rt + n_rg - 1) / n_rg;
+    // Row tiles per wave: one, so that a run's query rows spread over as many waves as possible (several waves
+    // per SIMD, the run's K/V staged once for all of them); up to 8 waves share a run.  Measured against two
+    // tiles per wave, attention per layer: 31.5 against 34.4 us (32-node tree, 128 rows per kv head), 54.5
+    // against 63.4 (batch 16, k = 8), 9.5 against 11.3 (batch 1, k = 5), 64.8 against 65.7 (70B shape, k = 6).
+    int RT = 1;
+    while ((n_rt + RT - 1) / RT > 8) ++RT;
+    if (RT > n_rt) RT = n_rt;
+    const int n_rg = (n_rt + RT - 1) / RT;
     // Which GEMM path.  One workgroup per column tile converting the activations itself
     // (gemm_skinny_kernel) wins for up to 10 rows when the residual GEMMs (d_model / 16 tiles) are exactly
     // one round of one workgroup per compute unit: d_model 4096 on 256 CUs, 107.6 against 114.4 us per
@@ -584,17 +582,20 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
     const int max_keys = std::min(max_len + k, g.S);
-    // Runs of keys per wave: LDS holds the stages of 4 waves per compute unit, so aim at that many
-    // waves over the whole grid (one round), in workgroups of 4 waves; small problems take shorter
-    // runs (at least 64 keys) in smaller workgroups so that more compute units take part.
+    // Runs of keys: aim at 8 waves per compute unit over the whole grid (one round, two waves per SIMD; 4, 10,
+    // 12 and 16 were measured slower at every workload); small problems take shorter runs (at least 64 keys)
+    // so that more compute units take part.
     const long units = (long)B * Hkv;
-    const long wave_slots = (long)ctx->n_cu * 4;
+    const long wave_slots = (long)ctx->n_cu * 8;
     long kpw = ((long)max_keys * units * n_rg + wave_slots - 1) / wave_slots;
     kpw = std::max(64L, (kpw + 31) / 32 * 32);
     const int keys_per_wave = (int)kpw;
     int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
+    // runs per workgroup: workgroups of about 4 waves (at most 8), when there are enough runs to go round
     const long n_waves = units * n_rg * n_runs;
-    const int att_waves_per_wg = n_waves >= wave_slots ? 4 : (n_waves * 2 >= wave_slots ? 2 : 1);
+    int rpw = std::max(1, 4 / n_rg);
+    if (n_waves < wave_slots / 2) rpw = 1;
+    rpw = std::min(rpw, n_runs);
     if (n_runs > MAX_RUNS) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: %d key runs", n_runs);
     const int rows_pad = RT * n_rg * 16;
 
@@ -667,10 +668,10 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         {
             ProfScope ps(ctx, DSD_KC_ATTN);
             switch (RT) {
-                case 1: DSD_TRY(attn_launch<1>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
-                case 2: DSD_TRY(attn_launch<2>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
-                case 3: DSD_TRY(attn_launch<3>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
-                default: DSD_TRY(attn_launch<4>(s, t, n_rg, att_waves_per_wg, Hkv, B)); break;
+                case 1: DSD_TRY(attn_launch<1>(s, t, n_rg, rpw, Hkv, B)); break;
+                case 2: DSD_TRY(attn_launch<2>(s, t, n_rg, rpw, Hkv, B)); break;
+                case 3: DSD_TRY(attn_launch<3>(s, t, n_rg, rpw, Hkv, B)); break;
+                default: DSD_TRY(attn_launch<4>(s, t, n_rg, rpw, Hkv, B)); break;
             }
         }
         {

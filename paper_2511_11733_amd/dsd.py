@@ -25,7 +25,7 @@ EXPORTS = [
     "dsd_kv_create", "dsd_kv_destroy", "dsd_kv_import", "dsd_kv_export", "dsd_kv_set_len", "dsd_kv_get_len",
     "dsd_stage_verify", "dsd_accept", "dsd_accept_noalloc", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read", "dsd_stream_probe",
 ]
-KERNEL_CLASSES = ["qkv", "attn", "attn_combine", "oproj", "gateup", "down", "head", "accept", "other", "stage"]
+KERNEL_CLASSES = ["qkv", "attn", "attn_combine", "oproj", "gateup", "down", "head", "accept", "other"]
 
 
 class DsdError(RuntimeError):

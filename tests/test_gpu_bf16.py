@@ -30,20 +30,17 @@ def mini(name, B, k, lens, tree=None, head=False, L=2, d=512, Hq=8, Hkv=2, F=153
     return cfg, m, w, K, Vv, hid, parent, list(lens)
 
 
-def check(case, simple=False, persist=False, no_tiled=False):
+def check(case, simple=False, no_tiled=False):
     cfg, m, w, K, V, hid, parent, lens = case
     ref = O.stage_forward(m, w.__getitem__, K, V, lens, hid, None, parent=parent)
     if simple:
         os.environ["DSD_PATH"] = "simple"
-    if persist:
-        os.environ["DSD_PERSIST"] = "1"
     if no_tiled:
         os.environ["DSD_NO_TILED"] = "1"
     try:
         st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
     finally:
         os.environ.pop("DSD_PATH", None)
-        os.environ.pop("DSD_PERSIST", None)
         os.environ.pop("DSD_NO_TILED", None)
     st.import_kv(K, V, lens)
     out, lg = st.verify(hidden=hid, parent=parent)
@@ -188,29 +185,27 @@ def test_wide_gqa_group_70b_like():
     check(mini("mini_70b", B=2, k=6, lens=[140, 200], Hq=16, Hkv=2, d=1024, F=2048))
 
 
-# ---- shapes the persistent single-kernel form accepts (K multiples of 2048, at most 16 rows)
-def test_persistent_mid_stage_chain():
-    check(mini("persist_mid", B=1, k=5, lens=[300], d=2048, Hq=16, Hkv=4, F=4096), persist=True)
-    check(mini("persist_mid8", B=2, k=4, lens=[77, 130], d=2048, Hq=16, Hkv=4, F=4096), persist=True)
+# ---- d_model 2048 (K a multiple of 2048), up to 10 rows: the one-workgroup-per-tile kernels at a narrower model
+def test_d2048_mid_stage_chain():
+    check(mini("d2048_mid", B=1, k=5, lens=[300], d=2048, Hq=16, Hkv=4, F=4096))
+    check(mini("d2048_mid8", B=2, k=4, lens=[77, 130], d=2048, Hq=16, Hkv=4, F=4096))
 
 
-def test_persistent_final_stage_tree():
-    check(mini("persist_tree", B=1, k=10, lens=[129], tree=((3, 2, 2), 10), head=True, d=2048, Hq=16, Hkv=4,
-               F=4096, V=4112), persist=False)
-    check(mini("persist_tree8", B=1, k=8, lens=[129], tree=((3, 2, 2), 8), head=True, d=2048, Hq=16, Hkv=4,
-               F=4096, V=4112), persist=True)
+def test_d2048_final_stage_tree():
+    check(mini("d2048_tree", B=1, k=10, lens=[129], tree=((3, 2, 2), 10), head=True, d=2048, Hq=16, Hkv=4,
+               F=4096, V=4112))
+    check(mini("d2048_tree8", B=1, k=8, lens=[129], tree=((3, 2, 2), 8), head=True, d=2048, Hq=16, Hkv=4,
+               F=4096, V=4112))
 
 
-def test_persistent_empty_context_and_k1():
-    check(mini("persist_empty", B=1, k=6, lens=[0], d=2048, Hq=16, Hkv=4, F=4096, L=1), persist=True)
-    check(mini("persist_k1", B=5, k=1, lens=[40, 41, 63, 64, 65], d=2048, Hq=16, Hkv=4, F=4096, L=3), persist=True)
+def test_d2048_empty_context_and_k1():
+    check(mini("d2048_empty", B=1, k=6, lens=[0], d=2048, Hq=16, Hkv=4, F=4096, L=1))
+    check(mini("d2048_k1", B=5, k=1, lens=[40, 41, 63, 64, 65], d=2048, Hq=16, Hkv=4, F=4096, L=3))
 
 
-def test_persistent_equals_per_step_kernels():
-    """Same inputs through the persistent kernel and through the one-kernel-per-step form."""
-    case = mini("persist_vs_steps", B=1, k=8, lens=[200], d=2048, Hq=16, Hkv=2, F=6144, head=True, V=4096)
-    check(case, persist=True)
-    check(case, persist=False)
+def test_d2048_one_kv_head_pair():
+    case = mini("d2048_gqa8", B=1, k=8, lens=[200], d=2048, Hq=16, Hkv=2, F=6144, head=True, V=4096)
+    check(case)
 
 
 def test_shape_errors():
