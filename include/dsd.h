@@ -162,11 +162,22 @@ int dsd_kv_get_len(dsd_ctx* ctx, const dsd_kv* kv, int32_t* host_len, int B);
  * drafted rows its mask allows.  Lengths are not advanced: see dsd_kv_commit.
  * Every sum is taken in a fixed order: the same call on the same inputs and cache contents
  * writes the same bits.  On the matrix-core path activations enter the projections as fp16
- * (11 significant bits or more); magnitudes beyond 65504 at those points saturate.
+ * (11 significant bits or more); magnitudes beyond 65504 at those points saturate and are counted:
+ * see dsd_stage_status.
  * Errors: DSD_ESHAPE if B > max_batch, k > DSD_MAX_K or max(len) + k > max_slots. */
 int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
                      const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth,
                      int B, int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
+
+/* Whether the dsd_stage_verify calls since the last check stayed inside the range of the matrix-core path.
+ * That path (bf16 models) feeds the projections with fp16 operands: the normalised rows, the attention
+ * output, SiLU(gate)*up and the attention's partial outputs are converted on the way, and a magnitude
+ * beyond 65504 (or a NaN) saturates there.  Every such conversion is counted on the device.  This call
+ * synchronises the context's stream, stores the count in *saturated (host, may be NULL), clears it, and
+ * returns DSD_EUNSUPPORTED if it was not zero: the outputs of the calls in between are then not the model's.
+ * (Section 2.1 asks of the verification pass that it scores the drafted window with the target model itself.)
+ * A caller checks once per round, after it has synchronised anyway; fp32 models never count anything. */
+int dsd_stage_status(dsd_ctx* ctx, int64_t* saturated);
 
 /* Algorithm 1, lines 2-16, for B sequences.
  *   logits       device float [B,k+1,V]: row 0 follows the committed context, row i follows node i

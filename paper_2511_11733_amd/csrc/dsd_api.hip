@@ -47,6 +47,12 @@ extern "C" int dsd_create(int device, void* hip_stream, dsd_ctx** out) {
     c->prof_on = false;
     c->no_tiled = getenv("DSD_NO_TILED") != nullptr;
     c->n_cu = prop.multiProcessorCount;
+    c->sat_dev = nullptr;
+    if (hipMalloc((void**)&c->sat_dev, 256) != hipSuccess || hipMemset(c->sat_dev, 0, 256) != hipSuccess) {
+        if (c->sat_dev) hipFree(c->sat_dev);
+        delete c;
+        DSD_FAIL(DSD_ENOMEM, "dsd_create: device allocation");
+    }
     *out = c;
     return DSD_OK;
 }
@@ -57,6 +63,7 @@ extern "C" int dsd_destroy(dsd_ctx* ctx) {
     hipStreamSynchronize(ctx->stream);
     prof_drop(ctx);
     if (ctx->ws) hipFree(ctx->ws);
+    if (ctx->sat_dev) hipFree(ctx->sat_dev);
     delete ctx;
     return DSD_OK;
 }
@@ -404,6 +411,20 @@ extern "C" int dsd_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, 
                                  logits_seq_stride);
     if (rc == DSD_OK) kv->last_k = k;
     return rc;
+}
+
+extern "C" int dsd_stage_status(dsd_ctx* ctx, int64_t* saturated) {
+    if (!ctx) DSD_FAIL(DSD_EINVAL, "dsd_stage_status: ctx is NULL");
+    DSD_HIP(hipSetDevice(ctx->device));
+    int n = 0;
+    DSD_HIP(hipMemcpyAsync(&n, ctx->sat_dev, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    DSD_HIP(hipStreamSynchronize(ctx->stream));
+    if (saturated) *saturated = n;
+    if (n == 0) return DSD_OK;
+    DSD_HIP(hipMemsetAsync(ctx->sat_dev, 0, sizeof(int), ctx->stream));
+    DSD_HIP(hipStreamSynchronize(ctx->stream));
+    DSD_FAIL(DSD_EUNSUPPORTED, "%d conversion(s) of activations to fp16 matrix-core operands met magnitudes beyond 65504 (or NaN) "
+             "since the last check: the results of those dsd_stage_verify calls are not valid", n);
 }
 
 // ----------------------------------------------------------------------------- accept

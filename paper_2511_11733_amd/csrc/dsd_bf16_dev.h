@@ -72,6 +72,18 @@ __device__ __forceinline__ f32x4 mfma16h(f16x8 a, f16x8 b, f32x4 c) {
     // operand and result layout as mfma16
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
+// Saturation is never silent: whoever turns an activation into an fp16 operand reports magnitudes
+// beyond the fp16 range (NaN too: !(x <= max)) into the context's counter, which dsd_stage_status reads.
+// `worst` is the largest |value| a thread has converted.
+__device__ __forceinline__ void report_saturation(int* __restrict__ sat, float worst) {
+    if (!(worst <= F16_MAX)) atomicAdd(sat, 1);
+}
+__device__ __forceinline__ float absmax8(const float* v, float m) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(v[i]));
+    return m;
+}
+
 // 8 bf16 gains (one 16-byte load) -> floats
 __device__ __forceinline__ void unpack_gain(uint4 gu, float* gf) {
     const unsigned gw[4] = {gu.x, gu.y, gu.z, gu.w};
@@ -101,6 +113,7 @@ struct GemmArgs {
     bf16_t* hidden_out;   // EPI_RESID, optional: the updated rows also go out in the model dtype (last layer of a block)
     float* hout;          // EPI_SWIGLU: [M][F]
     int up_tile_off;      // EPI_SWIGLU: F/16
+    int* sat;             // counter of activations that left the fp16 range on their way into an operand
     float* logits;        // EPI_LOGITS
     int rows_per_seq;
     int64_t seq_stride;
@@ -209,6 +222,7 @@ struct AttnArgs {
     int k, Hq, G;
     int keys_per_wave;     // multiple of 32
     int n_runs;            // runs per (sequence, kv head)
+    int* sat;              // counter of values that left the fp16 range
     float* part_o;         // [B][Hkv][n_runs][rows_pad][128]
     float* part_ml;        // [B][Hkv][n_runs][rows_pad][2]
     int rows_pad;          // multiple of 16, >= k*G
@@ -229,7 +243,8 @@ template <bool NORM16 = false>
 __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const float* __restrict__ part_o,
                                                  const float* __restrict__ part_ml, int n_runs, int rows_pad, int k,
                                                  int G, int Hq, int Hkv, int r, int hk, int b, float* wgt, float* red,
-                                                 unsigned short* __restrict__ panel = nullptr, int panel_mt = 0) {
+                                                 unsigned short* __restrict__ panel = nullptr, int panel_mt = 0,
+                                                 int* __restrict__ sat = nullptr) {
     const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
     const bool on = e < 128;
     const size_t u0 = (size_t)(b * Hkv + hk) * n_runs;
@@ -276,6 +291,7 @@ __device__ __forceinline__ void attn_combine_row(float* __restrict__ out, const 
         if (panel) {
             const int m = b * k + t, kk = hq * 128 + e;
             const size_t entry = ((size_t)(kk >> 5) * panel_mt + (m >> 4)) * 64 + (m & 15) + 16 * ((kk >> 3) & 3);
+            if (sat) report_saturation(sat, fabsf(num / den));
             const float v = __builtin_fminf(__builtin_fmaxf(num / den, -F16_MAX), F16_MAX);
             panel[entry * 8 + (kk & 7)] = __builtin_bit_cast(unsigned short, (_Float16)v);
         } else {

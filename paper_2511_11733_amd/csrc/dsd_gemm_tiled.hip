@@ -58,6 +58,7 @@ struct TArgs {
     int up_tile_off;     // TE_SWIGLU: F/16
     int rows_per_seq;    // TE_LOGITS
     int64_t seq_stride;
+    int* sat;            // TE_SWIGLU: counter of SiLU*up values that left the fp16 range
 };
 
 // fetching wave ks (0..3) brings k-step ks of a chunk into the panel buffer at LDS byte address buf:
@@ -249,6 +250,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
         for (int mt = 0; mt < MT; ++mt) rstd[mt] = *(const f32x4*)(rs + mt * 16 + g * 4);
     }
     float* part = p.out + (size_t)blockIdx.y * p.M * p.N;      // TE_PARTIAL: this K slice's own buffer
+    float worst = 0.f;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -267,6 +269,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
                         // m%16 + 16*((kk/8)%4), halfword kk%8
                         const float gate = acc[mt][nt][i] * rstd[mt][i], up = acc[mt][nt + 1][i] * rstd[mt][i];
                         const float hv = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+                        worst = fmaxf(worst, fabsf(hv));
                         const int kk = tile[nt] * 16 + c;
                         const size_t entry = ((size_t)(kk >> 5) * MT + mt) * 64 + (g * 4 + i) + 16 * ((kk >> 3) & 3);
                         p.panel_out[entry * 8 + (kk & 7)] =
@@ -279,6 +282,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
                     if (live[nt]) row[tile[nt] * 16 + c] = acc[mt][nt][i] * rstd[mt][i];
             }
         }
+    if (EPI == TE_SWIGLU) report_saturation(p.sat, worst);
 }
 
 // Activations -> panel.  Block (chunk, mt) of 4 waves: wave w handles k-step 4*chunk + w, lane
@@ -291,7 +295,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
 __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ panel, float* __restrict__ ssq,
                                                         float* __restrict__ a, const bf16_t* __restrict__ gain,
                                                         const float* __restrict__ part, int n_part, int M, int K,
-                                                        int MT) {
+                                                        int MT, int* __restrict__ sat) {
     __shared__ float s_q[4][16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4, mt = blockIdx.y;
@@ -346,6 +350,7 @@ __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ pane
             ssq[blockIdx.x * 128 + mt * 16 + threadIdx.x] =
                 ((s_q[0][threadIdx.x] + s_q[1][threadIdx.x]) + s_q[2][threadIdx.x]) + s_q[3][threadIdx.x];
     }
+    report_saturation(sat, absmax8(v, 0.f));
     panel[((size_t)ks * MT + mt) * 64 + lane] = __builtin_bit_cast(uint4, pack8h(v));
 }
 
@@ -580,7 +585,7 @@ int tiled_row_tiles(int M) { return mt_of(M); }
 static void make_panel(dsd_ctx* ctx, uint4* panel, float* ssq, float* a, const bf16_t* gain, const float* part,
                        int x_pending, int M, int K) {
     const int MT = mt_of(M);
-    act_panel_kernel<<<dim3(K / 128, MT), 256, 0, ctx->stream>>>(panel, ssq, a, gain, part, x_pending, M, K, MT);
+    act_panel_kernel<<<dim3(K / 128, MT), 256, 0, ctx->stream>>>(panel, ssq, a, gain, part, x_pending, M, K, MT, ctx->sat_dev);
 }
 
 // K-sliced GEMM: part[s][M][N] = slice s of a[M][K] W^T; returns the number of slices in *n_part
@@ -634,6 +639,7 @@ int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.n_ssq = K / 128; p.eps = eps; p.panel_out = (unsigned short*)panel_h; p.N = F; p.up_tile_off = F / 16;
+    p.sat = ctx->sat_dev;
     // fused SiLU*up needs the whole K in one workgroup: no K split
     const int twc = choose_twc_pairs(F / 16, ctx->n_cu);
     return tiled_dispatch<TE_SWIGLU>(ctx->stream, p, twc, ceil_div(F / 16, twc * NTW / 2), 1);

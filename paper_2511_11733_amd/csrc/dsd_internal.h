@@ -92,6 +92,7 @@ struct dsd_ctx {
     bool force_simple;  // DSD_PATH=simple: run the generic kernels also for bf16 models
     bool prof_on;
     std::vector<ProfRec> prof;
+    int* sat_dev;                  // activations that left the fp16 range on their way into a matrix-core operand (dsd_stage_status)
     bool no_tiled;                 // DSD_NO_TILED set: the one-workgroup-per-tile GEMMs at every row count (testing)
     int n_cu;
 };

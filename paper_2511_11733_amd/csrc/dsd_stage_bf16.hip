@@ -124,6 +124,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
     float ssq[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
+    float worst = 0.f;                                // largest |activation| this thread turned into an operand
 
     const uint4* wt[NT];
 #pragma unroll
@@ -167,6 +168,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
                     v[i] *= gf[i];
                 }
             }
+            worst = absmax8(v, worst);
             split8h(v, &ahi[mt], &alo[mt]);
         }
 #pragma unroll
@@ -178,6 +180,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
             }
     }
 
+    report_saturation(p.sat, worst);
     // partial tiles (and partial sums of squares) of all waves meet in LDS
     f32x4* red = (f32x4*)lds;                              // [nw][MT][NT][64]
     float* ssr = lds + (size_t)nw * MT * NT * 64 * 4;      // [nw][MT][16]
@@ -435,11 +438,14 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
         // themselves) and as fp16; (max, sum) stay fp32 and carry the run's weight
         const float inv_l = l > 0.f ? 1.0f / l : 0.f;
         unsigned short* po = (unsigned short*)p.part_o + (unit + r) * 128 + g * 4;
+        float worst = 0.f;
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
             const f32x4 v = o[h][rt] * inv_l;
+            worst = fmaxf(fmaxf(worst, fmaxf(fabsf(v[0]), fabsf(v[1]))), fmaxf(fabsf(v[2]), fabsf(v[3])));
             *(uint2*)(po + h * 16) = make_uint2(pack_f16(v[0], v[1]), pack_f16(v[2], v[3]));
         }
+        report_saturation(p.sat, worst);
     }
 }
 
@@ -462,11 +468,11 @@ static int attn_launch(hipStream_t s, const AttnArgs& t, int n_rg, int rpw, int 
 __global__ void __launch_bounds__(128) attn_combine_kernel(float* __restrict__ out, const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml, int n_runs, int rows_pad,
                                                           int k, int G, int Hq, int Hkv,
-                                                          unsigned short* __restrict__ panel, int panel_mt) {
+                                                          unsigned short* __restrict__ panel, int panel_mt, int* __restrict__ sat) {
     __shared__ float wgt[MAX_RUNS];
     __shared__ float red[4];
     attn_combine_row<true>(out, part_o, part_ml, n_runs, rows_pad, k, G, Hq, Hkv, blockIdx.x, blockIdx.y, blockIdx.z, wgt,
-                           red, panel, panel_mt);
+                           red, panel, panel_mt, sat);
 }
 
 // ============================================================================ small kernels
@@ -645,6 +651,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         bf16_t* kc = (bf16_t*)kv->k + (size_t)l * g.layer_elems;
         bf16_t* vc = (bf16_t*)kv->v + (size_t)l * g.layer_elems;
         GemmArgs a = GemmArgs();
+        a.sat = ctx->sat_dev;
         a.M = M;
         a.eps = D.rms_eps;
         // q, k, v = rmsnorm(x; g1) Wqkv^T, rotary, cache append
@@ -664,7 +671,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         AttnArgs t;
         t.q = q; t.kc = kc; t.vc = vc; t.g = g; t.len = kv->len_dev; t.mask = tree_mask; t.k = k; t.Hq = Hq; t.G = G;
         t.keys_per_wave = keys_per_wave; t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
-        t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
+        t.sat = ctx->sat_dev; t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
         {
             ProfScope ps(ctx, DSD_KC_ATTN);
             switch (RT) {
@@ -679,10 +686,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         // tiled path: straight into the operand panel of the output projection
         attn_combine_kernel<<<dim3(rows, Hkv, B), 128, 0, s>>>(att, part_o, part_ml, n_runs, t.rows_pad, k, G, Hq, Hkv,
                                                                tiled ? (unsigned short*)panel : nullptr,
-                                                               tiled ? tiled_row_tiles(M) : 0);
+                                                               tiled ? tiled_row_tiles(M) : 0, ctx->sat_dev);
         }
         // x += attn Wo^T
         a = GemmArgs();
+        a.sat = ctx->sat_dev;
         a.M = M; a.Wt = (const uint4*)W.wo_t; a.KS = qd / 32; a.a = att; a.xout = x; a.N = d;
         {
             ProfScope ps(ctx, DSD_KC_OPROJ);
@@ -691,6 +699,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         }
         // h = silu(b Wg^T) * (b Wu^T),  b = rmsnorm(x; g2)
         a = GemmArgs();
+        a.sat = ctx->sat_dev;
         a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)W.gu_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)W.g2;
         a.hout = h; a.N = F; a.up_tile_off = F / 16;
         {
@@ -703,6 +712,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         }
         // x += h Wd^T
         a = GemmArgs();
+        a.sat = ctx->sat_dev;
         a.M = M; a.Wt = (const uint4*)W.wd_t; a.KS = F / 32; a.a = h; a.xout = x; a.N = d;
         if (l == D.n_layers - 1) a.hidden_out = (bf16_t*)hidden_out;     // the block's output leaves with the last residual update
         {
@@ -720,6 +730,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     }
     if (logits) {
         GemmArgs a = GemmArgs();
+        a.sat = ctx->sat_dev;
         a.M = M; a.eps = D.rms_eps; a.Wt = (const uint4*)w->lm_t; a.KS = d / 32; a.x = x; a.gain = (const bf16_t*)w->gf;
         a.logits = logits; a.N = D.vocab; a.rows_per_seq = k; a.seq_stride = logits_seq_stride;
         ProfScope ps(ctx, DSD_KC_HEAD);

@@ -23,7 +23,7 @@ DSD_MAX_K, DSD_MAX_TOP_M = 64, 16
 EXPORTS = [
     "dsd_last_error", "dsd_create", "dsd_destroy", "dsd_set_stream", "dsd_weights_create", "dsd_weights_destroy",
     "dsd_kv_create", "dsd_kv_destroy", "dsd_kv_import", "dsd_kv_export", "dsd_kv_set_len", "dsd_kv_get_len",
-    "dsd_stage_verify", "dsd_accept", "dsd_accept_noalloc", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read", "dsd_stream_probe",
+    "dsd_stage_verify", "dsd_stage_status", "dsd_accept", "dsd_accept_noalloc", "dsd_kv_commit", "dsd_profile_enable", "dsd_profile_read", "dsd_stream_probe",
 ]
 KERNEL_CLASSES = ["qkv", "attn", "attn_combine", "oproj", "gateup", "down", "head", "accept", "other"]
 
@@ -77,6 +77,7 @@ def load() -> C.CDLL:
         "dsd_kv_set_len": [vp, vp, C.POINTER(C.c_int32), i32],
         "dsd_kv_get_len": [vp, vp, C.POINTER(C.c_int32), i32],
         "dsd_stage_verify": [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i64],
+        "dsd_stage_status": [vp, C.POINTER(C.c_int64)],
         "dsd_accept": [vp, vp, vp, vp, vp, vp, C.POINTER(AcceptParams), i32, i32, i32, vp, vp, vp,
                        C.POINTER(AcceptStats)],
         "dsd_accept_noalloc": [vp, vp, vp, vp, vp, vp, C.POINTER(AcceptParams), i32, i32, i32, vp, vp, vp,
@@ -145,6 +146,13 @@ class Context:
         cnt = (C.c_int64 * n)()
         _check(self.lib.dsd_profile_read(self.h, ms, cnt), "dsd_profile_read")
         return {KERNEL_CLASSES[i]: (ms[i], cnt[i]) for i in range(n)}
+
+    def stage_status(self) -> int:
+        """Synchronises; raises DsdError if activations left the fp16 range since the last check, else returns 0."""
+        n = C.c_int64()
+        rc = self.lib.dsd_stage_status(self.h, C.byref(n))
+        _check(rc, "dsd_stage_status")
+        return n.value
 
     def stream_probe(self, buf: torch.Tensor, mode: int, iters: int) -> float:
         """Average milliseconds of one launch of the bare read (mode 0) / copy (mode 1) kernel over buf."""

@@ -208,6 +208,56 @@ def test_d2048_one_kv_head_pair():
     check(case)
 
 
+def wide_ffn_case(name, B, k, spread):
+    """A block whose FFN intermediates SiLU(gate)*up are large: gate and up rows of spread `spread` (weights
+    N(0, (spread/sqrt(d))^2)), a down projection small enough to bring the result back to the size of the
+    residual stream.  The matrix-core path carries those intermediates as fp16 operands (limit 65504)."""
+    case = mini(name, B=B, k=k, lens=[40 + 7 * b for b in range(B)], L=2, d=512, F=1024)
+    cfg, m, w, K, V, hid, parent, lens = case
+    rng = np.random.default_rng(5)
+    for l in range(m.L):
+        for nm in ("wg", "wu"):
+            w[f"l{l}.{nm}"] = W.f32_to_bf16_bits((rng.standard_normal((m.F, m.d)) * spread / np.sqrt(m.d)).astype(np.float32))
+        w[f"l{l}.wd"] = W.f32_to_bf16_bits((rng.standard_normal((m.d, m.F)) / (spread * spread * np.sqrt(m.F))).astype(np.float32))
+    return case
+
+
+@pytest.mark.parametrize("B,k", [(1, 5), (4, 6)])          # both GEMM paths: up to 10 rows, 11 rows and more
+def test_large_ffn_intermediates_inside_the_fp16_range_keep_parity(B, k):
+    """SiLU(gate)*up up to about 3e4: inside the range, so parity with the oracle holds and nothing is counted."""
+    case = wide_ffn_case(f"ffn_big_{B * k}", B, k, spread=40.0)
+    cfg, m, w, K, V, hid, parent, lens = case
+    ref = O.stage_forward(m, w.__getitem__, K, V, lens, hid, None, want_taps=False)
+    st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
+    st.import_kv(K, V, lens)
+    out, _ = st.verify(hidden=hid)
+    H.assert_close(H.to_np64(out), ref.hidden, H.TOL["bf16"], f"{cfg.name} hidden")
+    assert st.ctx.stage_status() == 0
+
+
+@pytest.mark.parametrize("B,k", [(1, 5), (4, 6)])
+def test_ffn_intermediates_beyond_the_fp16_range_are_reported(B, k):
+    """SiLU(gate)*up in the 1e6 range: the fp16 operands saturate, the result is not the model's, and
+    dsd_stage_status says so (and is clean again afterwards)."""
+    case = wide_ffn_case(f"ffn_over_{B * k}", B, k, spread=400.0)
+    cfg, m, w, K, V, hid, parent, lens = case
+    bn = O.rms_norm(O.widen(hid), O.widen(w["l0.g2"]), m.eps)       # the order of magnitude, from the oracle's pieces
+    hmax = np.abs(O.silu(bn @ O.widen(w["l0.wg"]).T) * (bn @ O.widen(w["l0.wu"]).T)).max()
+    assert hmax > 2 * 65504
+    st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
+    st.import_kv(K, V, lens)
+    st.verify(hidden=hid)
+    with pytest.raises(H.D.DsdError, match="65504"):
+        st.ctx.stage_status()
+    assert st.ctx.stage_status() == 0                               # the count was cleared by the failing check
+    # an ordinary block on the same context afterwards: clean
+    cfg2, m2, w2, K2, V2, hid2, parent2, lens2 = mini("after_overflow", B=B, k=k, lens=[33] * B)
+    st2 = H.GpuStage(m2, w2, B, 33 + k + 3, ctx=st.ctx)
+    st2.import_kv(K2, V2, lens2)
+    st2.verify(hidden=hid2)
+    assert st.ctx.stage_status() == 0
+
+
 def test_shape_errors():
     case = mini("mini_err", B=2, k=4, lens=[10, 10])
     cfg, m, w, K, V, hid, parent, lens = case
