@@ -213,7 +213,11 @@ int dsd_stage_status(dsd_ctx* ctx, int64_t* saturated);
  *   accepted_path device int32 [B,k] node ids of the path, -1 padded; may be NULL
  *   stats         optional, may be NULL
  * Sums over the vocabulary are accumulated in fp64 from fp32 per-id terms; every quantity that
- * decides something by itself is fp64; no probability row is written to memory. */
+ * decides something by itself is fp64; no probability row is written to memory.  Under DSD_TREE_LOSSLESS
+ * a later sibling is tested against the residual max(0, p - q) / Z; a Z below 0.05 (target and draft
+ * nearly coincide) is summed in fp64 with the row renormalised in fp64, as is every later Z of the same
+ * node, so the reported ratios keep 1e-6 relative accuracy down to Z of about 1e-6; above 0.05 the fp32 terms bound
+ * the error of Z by 1e-7 / Z. */
 int dsd_accept(dsd_ctx* ctx, const float* logits, const float* draft_probs, const int32_t* draft_tokens,
                const int32_t* parent, const float* uniforms, const dsd_accept_params* params,
                int B, int k, int V, int32_t* accepted_len, int32_t* next_token,

@@ -983,6 +983,33 @@ __device__ inline float walk_p(const WalkChain& c, float p1, float q1, int id, f
     return p;
 }
 
+// sum over the WALK_TPB threads of the workgroup, to every thread (red: WALK_TPB / WAVE doubles of LDS)
+__device__ inline double walk_block_sum(double v, double* red, int lane, int wave) {
+    v = wave_sum_d(v);
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    double tot = 0.0;
+    for (int i = 0; i < WALK_TPB / WAVE; ++i) tot += red[i];
+    return tot;
+}
+// the chain of walk_p in fp64
+__device__ inline double walk_p_d(int n, const int* y, const double* inv_z, const double* q_scale, double p1, double q1, int id,
+                                  double* q_n) {
+    double p = p1;
+    bool removed = false;
+    for (int j = 0; j < n; ++j) {
+        const double qj = removed ? 0.0 : q1 * q_scale[j];
+        if (inv_z[j] > 0.0) p = fmax(p - qj, 0.0) * inv_z[j];
+        removed = removed || id == y[j];
+    }
+    *q_n = removed ? 0.0 : q1 * q_scale[n];
+    return p;
+}
+
+// A residual mass below this is summed again in fp64 (see the walk)
+#define WALK_SMALL_Z 0.05
+
 __global__ void __launch_bounds__(WALK_TPB)
 lossless_walk_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const int32_t* __restrict__ tokens,
                      const int32_t* __restrict__ parent, const float* __restrict__ uniforms, AcceptWs ws, int k, int V,
@@ -1024,13 +1051,15 @@ lossless_walk_kernel(const float* __restrict__ logits, const float* __restrict__
         lse = ws.row_lse[(size_t)b * R + v];
         n = 0;
         double removed_mass = 0.0;
+        double norm = 1.0;                            // 1 / sum_v exp(l_v / T - lse) in fp64, once a small Z asks for it
+        bool have_norm = false;
         int taken = 0;
         for (int c = v + 1; c <= k && !taken; ++c) {
             if (s_par[c] != v) continue;
             int y = tokens[(size_t)b * k + c - 1];
             y = y < 0 ? 0 : (y >= V ? V - 1 : y);
             // the child's own test, fp64, by every thread alike
-            double p = exp((double)logits[row + y] * inv_temp - lse);
+            double p = exp((double)logits[row + y] * inv_temp - lse) * norm;
             const double q1 = (double)qp[row + y];
             bool removed = false;
             for (int j = 0; j < n; ++j) {
@@ -1051,39 +1080,60 @@ lossless_walk_kernel(const float* __restrict__ logits, const float* __restrict__
                 break;
             }
             // rejected: Z_n = sum of the positive part of p_n - q_n
-            WalkChain ch{n, s_y, s_inv_z, s_q_scale};
-            double z = 0.0;
-            const bool vec = (V & 3) == 0 && (row & 3) == 0;      // rows start 16-byte aligned
-            const int step = vec ? 4 : 1;
-            for (int id = tid * step; id < V; id += WALK_TPB * step) {
-                float lv[4], qv[4];
-                if (vec) {
-                    const float4 l4 = *(const float4*)(logits + row + id), q4 = *(const float4*)(qp + row + id);
-                    lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w;
-                    qv[0] = q4.x; qv[1] = q4.y; qv[2] = q4.z; qv[3] = q4.w;
-                } else {
-                    lv[0] = logits[row + id];
-                    qv[0] = qp[row + id];
-                }
-                float zf = 0.f;                                   // at most 4 terms: exact enough before the fp64 sum
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (e < step) {
-                        const float p1 = expf((float)((double)lv[e] * inv_temp - lse));
-                        float qn_id;
-                        const float pn = walk_p(ch, p1, qv[e], id + e, &qn_id);
-                        zf += fmaxf(pn - qn_id, 0.f);
+            double tot = 0.0;
+            if (!have_norm) {                         // (after a small Z at this node every later one is summed in fp64)
+                WalkChain ch{n, s_y, s_inv_z, s_q_scale};
+                double z = 0.0;
+                const bool vec = (V & 3) == 0 && (row & 3) == 0;      // rows start 16-byte aligned
+                const int step = vec ? 4 : 1;
+                for (int id = tid * step; id < V; id += WALK_TPB * step) {
+                    float lv[4], qv[4];
+                    if (vec) {
+                        const float4 l4 = *(const float4*)(logits + row + id), q4 = *(const float4*)(qp + row + id);
+                        lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w;
+                        qv[0] = q4.x; qv[1] = q4.y; qv[2] = q4.z; qv[3] = q4.w;
+                    } else {
+                        lv[0] = logits[row + id];
+                        qv[0] = qp[row + id];
                     }
+                    float zf = 0.f;                                   // at most 4 terms: exact enough before the fp64 sum
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (e < step) {
+                            const float p1 = expf((float)((double)lv[e] * inv_temp - lse));
+                            float qn_id;
+                            const float pn = walk_p(ch, p1, qv[e], id + e, &qn_id);
+                            zf += fmaxf(pn - qn_id, 0.f);
+                        }
+                    }
+                    z += (double)zf;
                 }
-                z += (double)zf;
+                tot = walk_block_sum(z, s_red, lane, wave);
             }
-            z = wave_sum_d(z);
-            __syncthreads();                          // everyone is done with the chain arrays and s_red
-            if (lane == 0) s_red[wave] = z;
-            __syncthreads();
+            if (have_norm || tot < WALK_SMALL_Z) {    // workgroup-uniform
+                // Target and draft nearly coincide here (a good draft on peaked rows): the next sibling's p is
+                // the residual divided by this small Z, so the absolute error of the fp32 terms (1e-7 of p)
+                // and of the row's log-sum-exp would show up 1/Z times larger, here and, through the differences
+                // p - q inside the chain, in every later Z of this node.  In fp64, with the row renormalised by its
+                // own fp64 sum.
+                if (!have_norm) {
+                    double s1 = 0.0;
+                    for (int id = tid; id < V; id += WALK_TPB) s1 += exp((double)logits[row + id] * inv_temp - lse);
+                    s1 = walk_block_sum(s1, s_red, lane, wave);
+                    norm = s1 > 0.0 ? 1.0 / s1 : 1.0;
+                    have_norm = true;
+                }
+                double z64 = 0.0;
+                for (int id = tid; id < V; id += WALK_TPB) {
+                    const double p1 = exp((double)logits[row + id] * inv_temp - lse) * norm;
+                    double qn_id;
+                    const double pn = walk_p_d(n, s_y, s_inv_z_d, s_q_scale_d, p1, (double)qp[row + id], id, &qn_id);
+                    z64 += fmax(pn - qn_id, 0.0);
+                }
+                tot = walk_block_sum(z64, s_red, lane, wave);
+            }
+            __syncthreads();                          // everyone is done with the chain arrays
             if (tid == 0) {
-                double tot = 0.0;
-                for (int i = 0; i < WALK_TPB / WAVE; ++i) tot += s_red[i];
                 const double iz = tot > 0.0 ? 1.0 / tot : 0.0;
                 if (!removed) removed_mass += q1;
                 const double left = 1.0 - removed_mass;

@@ -104,19 +104,22 @@ extern "C" int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launche
 
 // ----------------------------------------------------------------------------- stream probe
 // What a bare stream over device memory reaches on this chip: the yardstick the weight-streaming
-// kernels are measured against besides the published peak.  Every thread keeps four 16-byte loads in
+// kernels are measured against besides the published peak.  Every thread keeps U 16-byte loads in
 // flight over a grid-stride walk; the read kernel folds what it loads into a word that it stores only
 // for a value that does not occur, so the loads cannot be dropped.
+template <int U>
 __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ p, size_t n, unsigned* __restrict__ sink) {
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     uint4 a = make_uint4(0, 0, 0, 0);
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const uint4 v0 = p[i], v1 = p[i + stride], v2 = p[i + 2 * stride], v3 = p[i + 3 * stride];
-        a.x ^= v0.x ^ v1.x ^ v2.x ^ v3.x;
-        a.y ^= v0.y ^ v1.y ^ v2.y ^ v3.y;
-        a.z ^= v0.z ^ v1.z ^ v2.z ^ v3.z;
-        a.w ^= v0.w ^ v1.w ^ v2.w ^ v3.w;
+    for (; i + (U - 1) * stride < n; i += U * stride) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a.x ^= v[u].x; a.y ^= v[u].y; a.z ^= v[u].z; a.w ^= v[u].w;
+        }
     }
     for (; i < n; i += stride) {
         const uint4 v = p[i];
@@ -142,13 +145,15 @@ extern "C" int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode,
     DSD_HIP(hipSetDevice(ctx->device));
     DSD_TRY(dsd_ws_reserve(ctx, 256));
     const size_t n = mode == 0 ? bytes / 16 : bytes / 32;      // mode 1: first half -> second half
-    const int grid = ctx->n_cu * 8;
+    // two workgroups of 256 threads per compute unit, four 16-byte loads per thread in flight (32 KiB per compute
+    // unit): the fastest of the grids and depths tried on 1 GiB (6.4 TB/s; 8 workgroups per unit: 5.3, 16 loads: 4.8)
+    const int grid = ctx->n_cu * 2;
     hipEvent_t e0, e1;
     DSD_HIP(hipEventCreate(&e0));
     DSD_HIP(hipEventCreate(&e1));
     for (int it = -2; it < iters; ++it) {
         if (it == 0) DSD_HIP(hipEventRecord(e0, ctx->stream));
-        if (mode == 0) stream_read_kernel<<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
+        if (mode == 0) stream_read_kernel<4><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
         else stream_copy_kernel<<<grid, 256, 0, ctx->stream>>>((uint4*)buf + n, (const uint4*)buf, n);
     }
     DSD_HIP(hipEventRecord(e1, ctx->stream));

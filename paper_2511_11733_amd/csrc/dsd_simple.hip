@@ -118,14 +118,16 @@ __global__ void rope_append_kernel(float* __restrict__ q, const float* __restric
     const int b = m / k, t = m % k;
     const int hd = g.hd, half = hd / 2;
     const int L = len[b];
-    const float pos = (float)(L + (depth ? depth[t] : t));
+    const double pos = (double)(L + (depth ? depth[t] : t));
     const int slot = L + t;
     const int nheads = Hq + g.Hkv;
     for (int i = threadIdx.x; i < nheads * half; i += blockDim.x) {
         const int h = i / half, e = i % half;
-        const float inv = powf(theta, -2.0f * (float)e / (float)hd);
-        float sn, cs;
-        sincosf(pos * inv, &sn, &cs);
+        // the angle in fp64: at position 8192 an fp32 product is off by about 5e-4 rad
+        const double inv = pow((double)theta, -2.0 * (double)e / (double)hd);
+        double snd, csd;
+        sincos(pos * inv, &snd, &csd);
+        const float sn = (float)snd, cs = (float)csd;
         if (h < Hq) {
             float* p = q + ((size_t)m * Hq + h) * hd;
             const float a = p[e], c = p[e + half];

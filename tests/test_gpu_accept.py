@@ -36,7 +36,7 @@ def make_rows(seed, B, k, V, parent=None, spread=1.28, noise=0.5, zero_frac=0.0)
     return lg, q, toks, u
 
 
-def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None, max_flagged_fraction=None):
+def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None, max_flagged_fraction=None, ratio_rtol=None):
     ora = O.accept(lg.astype(np.float64), q.astype(np.float64), toks, parent, u, H.oracle_prm(O, prm),
                    None if tau_override is None else tau_override.astype(np.float64))
     g = H.gpu_accept(ctx, torch.from_numpy(lg).to("cuda:0"), torch.from_numpy(q).to("cuda:0"), toks, parent, u, prm,
@@ -46,12 +46,13 @@ def run_case(ctx, lg, q, toks, parent, u, prm, what, tau_override=None, max_flag
     excused, near = st["excused_sequences"], st["flagged_accept"] + st["flagged_key"] + st["flagged_draw"]
     fin = np.isfinite(ora.ratio)
     # The reported ratios are fp64 over fp32 per-id terms: 1e-6 relative for the per-node rules.  In the
-    # lossless walk a later sibling's p is a residual max(0, p - q) / Z; Z sums fp32 terms whose absolute
-    # error is ~1e-7 of p, so its relative error is 1e-7 / Z, and Z (the mass on which target and draft
-    # disagree) is 1e-3 or less when peaked rows nearly coincide.  Decisions are protected by the
-    # oracle's near-tie margin of 1e-3 on the same ratio.
-    np.testing.assert_allclose(g["ratio"][fin], ora.ratio[fin], rtol=1e-4 if prm.get("tree_mode", 0) == 2 else 1e-6,
-                               err_msg=what)
+    # lossless walk a later sibling's p is a residual max(0, p - q) / Z; a Z of 0.05 or more is summed from
+    # fp32 terms whose absolute error is ~1e-7 of p, so its relative error stays below 1e-7 / 0.05 (the
+    # default bound here is looser than that needs); a smaller Z is summed again in fp64 (its own test
+    # asks for 1e-6).  Decisions are protected by the oracle's near-tie margin of 1e-3 on the same ratio.
+    if ratio_rtol is None:
+        ratio_rtol = 2e-5 if prm.get("tree_mode", 0) == 2 else 1e-6
+    np.testing.assert_allclose(g["ratio"][fin], ora.ratio[fin], rtol=ratio_rtol, err_msg=what)
     if prm.get("norm_match_kind", 0) == 1:      # a vocabulary-wide sum: fp32 terms on the GPU
         np.testing.assert_allclose(g["norm_match"], ora.norm_match, rtol=1e-6, err_msg=what)
     else:
@@ -191,6 +192,26 @@ def test_lossless_tree_rule(ctx):
     # draft rows with exact zeros, full-size vocabulary
     lg, q, toks, u = make_rows(24, 2, 10, 128256, parent=W.ranked_tree_parents((3, 2, 2), 10), zero_frac=0.5)
     run_case(ctx, lg, q, toks, W.ranked_tree_parents((3, 2, 2), 10), u, dict(tree_mode=2), "lossless, vocabulary 128256")
+
+
+@pytest.mark.parametrize("noise", [0.02, 0.05])
+def test_lossless_walk_with_a_draft_close_to_the_target_on_peaked_rows(ctx, noise):
+    """A good draft on rows like a trained model's: target and draft differ by a few per mille of total
+    variation, so after a rejection the next sibling is tested against a residual divided by a Z of 1e-3 .. 1e-2.
+    The walk sums such a Z again in fp64 with the row renormalised in fp64; ratios then agree with the oracle
+    to 1e-6 like everywhere else and no sequence needs the near-tie exception."""
+    parent = W.ranked_tree_parents((3, 2, 2), 10)
+    B, k, V = 8, len(parent), 50257
+    lg, q, toks, u = make_rows(int(noise * 1000), B, k, V, parent=parent, spread=6.0, noise=noise)
+    # make rejections happen although the draft is good: uniforms close to 1 for the first child of every node
+    u[:, 1:] = 1.0 - (1.0 - u[:, 1:]) * 0.02
+    ora, g, ex, near = run_case(ctx, lg, q, toks, parent, u, dict(tree_mode=2), f"lossless, draft noise {noise}", ratio_rtol=1e-6)
+    tested = ora.ratio != 0
+    assert ex == 0 and (~ora.node_accept[tested]).sum() >= 4, "the case must contain rejections"
+    pt = O.softmax_row(lg[0, 0].astype(np.float64), 1.0)
+    z = np.maximum(pt - q[0, 0].astype(np.float64), 0).sum()
+    print(f"noise {noise}: residual mass of a root row {z:.2e}, rejections {int((~ora.node_accept[tested]).sum())}")
+    assert z < 0.05
 
 
 def test_greedy_verification_at_temperature_zero(ctx):
