@@ -272,8 +272,10 @@ int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launches);
 
 /* Diagnostics: what a bare stream over device memory reaches on this device, the yardstick for a pass that
  * the paper's own argument (section 2.1, Fig. 1) makes memory bound.  buf: device, `bytes` long (a multiple
- * of 32, at least 1 MiB, 16-byte aligned), contents irrelevant.  mode 0: one kernel reads all of it;
- * mode 1: one kernel copies its first half onto its second half (bytes/2 read + bytes/2 written).
+ * of 32, at least 1 MiB, 16-byte aligned), contents irrelevant.  mode 0: one kernel reads all of it, the
+ * whole grid sweeping one contiguous front; mode 1: one kernel copies its first half onto its second half
+ * (bytes/2 read + bytes/2 written); mode 2: one kernel reads it the way the weight-streaming kernels do,
+ * every wave a contiguous stream of its own (bytes rounded down to whole streams of 16 KiB steps).
  * Runs 2 untimed + `iters` timed launches on the context's stream, synchronises, and returns the
  * average time of a launch in *ms_avg (host). */
 int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode, int iters, double* ms_avg);

@@ -127,6 +127,24 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
     }
     if ((a.x ^ a.y ^ a.z ^ a.w) == 0x9E3779B9u && a.x == 0x7F4A7C15u) *sink = a.y;
 }
+// The access pattern of the weight-streaming kernels: every wave walks a contiguous stream of its own,
+// 1 KiB per load instruction, U of them in flight (8 waves per compute unit)
+template <int U>
+__global__ void __launch_bounds__(256) stream_tiles_kernel(const uint4* __restrict__ p, size_t per_stream, unsigned* __restrict__ sink) {
+    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint4* q = p + wave * per_stream + (threadIdx.x & 63);
+    uint4 a = make_uint4(0, 0, 0, 0);
+    for (size_t i = 0; i + U * 64 <= per_stream; i += U * 64) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = q[i + u * 64];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a.x ^= v[u].x; a.y ^= v[u].y; a.z ^= v[u].z; a.w ^= v[u].w;
+        }
+    }
+    if ((a.x ^ a.y ^ a.z ^ a.w) == 0x9E3779B9u && a.x == 0x7F4A7C15u) *sink = a.y;
+}
 __global__ void __launch_bounds__(256) stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -140,7 +158,7 @@ __global__ void __launch_bounds__(256) stream_copy_kernel(uint4* __restrict__ ds
 extern "C" int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode, int iters, double* ms_avg) {
     if (!ctx || !buf || !ms_avg) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: NULL argument");
     if (bytes < (1u << 20) || (bytes & 31) || ((size_t)buf & 15)) DSD_FAIL(DSD_ESHAPE, "dsd_stream_probe: bytes=%zu", bytes);
-    if (mode != 0 && mode != 1) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: mode=%d", mode);
+    if (mode < 0 || mode > 2) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: mode=%d", mode);
     if (iters < 1 || iters > 1000) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: iters=%d", iters);
     DSD_HIP(hipSetDevice(ctx->device));
     DSD_TRY(dsd_ws_reserve(ctx, 256));
@@ -153,7 +171,10 @@ extern "C" int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode,
     DSD_HIP(hipEventCreate(&e1));
     for (int it = -2; it < iters; ++it) {
         if (it == 0) DSD_HIP(hipEventRecord(e0, ctx->stream));
-        if (mode == 0) stream_read_kernel<4><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
+        if (mode == 2) {
+            const size_t per_stream = (bytes / 16 / ((size_t)grid * 4)) & ~(size_t)1023;
+            stream_tiles_kernel<8><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, per_stream, (unsigned*)ctx->ws);
+        } else if (mode == 0) stream_read_kernel<4><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
         else stream_copy_kernel<<<grid, 256, 0, ctx->stream>>>((uint4*)buf + n, (const uint4*)buf, n);
     }
     DSD_HIP(hipEventRecord(e1, ctx->stream));

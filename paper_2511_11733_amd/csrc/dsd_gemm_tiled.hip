@@ -202,10 +202,10 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
         w[i] = p.Wt + ((size_t)(live[i] ? tile[i] : 0) * p.KS + ks0) * 64 + lane;
     }
 
-    // weight fragments in flight per wave: 16 (8 k-steps); 8 where the registers are the limit: up to 3
-    // row tiles run four waves per SIMD (128 registers each), 8 computing waves with 6 or 8 row
-    // tiles three (170 each).  A FIFO of 32 was measured at 8 row tiles: no faster (the fill takes longer).
-    constexpr int NF = (MT <= 3 || (TWC > 4 && MT > 4)) ? 8 : 16;
+    // weight fragments in flight per wave: 8 (4 k-steps), 32-64 KiB per compute unit.  Deeper does not help:
+    // 16 was measured 0.7 % slower per step at 128 rows, 32 no faster (the fill takes longer); a bare read
+    // stream is also fastest with about 32 KiB in flight per compute unit and loses a fifth with 256 KiB.
+    constexpr int NF = 8;
     u32x4 fifo[NF];
     int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
 #pragma unroll

@@ -296,11 +296,14 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
     const int nkeys = min(L + p.k, p.g.S);
     const int rows = p.k * p.G;
     const bool in_grid = run < p.n_runs;
-    const int j_begin = min(run * p.keys_per_wave, nkeys);
-    const int j_end = min(j_begin + p.keys_per_wave, nkeys);
+    // Steps of 32 keys are dealt out to the runs in turn: run r takes steps r, r + n_runs, ...  The runs of a
+    // (sequence, kv head) advance side by side, so what the chip reads at any moment is one contiguous piece
+    // per head rather than a stream per run.  (The online softmax does not care which keys a run holds.)
+    const int n_chunks = (nkeys + 31) >> 5;
     // every wave of the workgroup makes as many turns (one barrier each) as the workgroup's first run has steps
-    const int jb0 = min(blockIdx.x * rpw * p.keys_per_wave, nkeys);
-    const int n_steps = (min(jb0 + p.keys_per_wave, nkeys) - jb0 + 31) >> 5;
+    const int run0 = blockIdx.x * rpw;
+    const int n_steps = run0 < n_chunks ? (n_chunks - run0 + p.n_runs - 1) / p.n_runs : 0;
+    const int my_steps = (in_grid && run < n_chunks) ? (n_chunks - run + p.n_runs - 1) / p.n_runs : 0;
     const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad + row0;
     const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
     const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
@@ -341,13 +344,13 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
     // the loads of the queries above are the compiler's and complete by its own waits; from here on
     // the only vector memory operations in flight are the stage fetches
     vm_wait_all<0>();
-    if (j_begin < j_end) attn_fetch(kbase, vbase, j_begin, stage_addr, lane, rg, n_rg);
+    if (my_steps > 0) attn_fetch(kbase, vbase, run * 32, stage_addr, lane, rg, n_rg);
     for (int step = 0; step < n_steps; ++step) {
-        const int j0 = j_begin + step * 32, st = step & 1;
+        const int j0 = (step * p.n_runs + run) * 32, st = step & 1;
         vm_wait_all<0>();                             // this wave's share of the step has landed
         __syncthreads();                              // so has everybody's; and the other stage is read no more
-        if (j0 + 32 < j_end) attn_fetch(kbase, vbase, j0 + 32, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane, rg, n_rg);
-        if (j0 >= j_end) continue;                    // a shorter run of the same workgroup: barriers only
+        if (step + 1 < my_steps) attn_fetch(kbase, vbase, j0 + p.n_runs * 32, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane, rg, n_rg);
+        if (step >= my_steps) continue;               // a shorter run of the same workgroup: barriers only
         const uint4* sp = stage_ptr + st * (ATT_STAGE_BYTES / 16) + lane;
         f32x4 s[2][RT];
 #pragma unroll
