@@ -226,6 +226,7 @@ struct AttnArgs {
     float* part_o;         // [B][Hkv][n_runs][rows_pad][128]
     float* part_ml;        // [B][Hkv][n_runs][rows_pad][2]
     int rows_pad;          // multiple of 16, >= k*G
+    int row_base;          // first query row of this launch (a multiple of 16)
     float scale_log2e;
 };
 

@@ -291,7 +291,7 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
     const int hk = blockIdx.y, b = blockIdx.z;
     const int rg = wave % n_rg, rloc = wave / n_rg;
     const int run = blockIdx.x * rpw + rloc;
-    const int row0 = rg * RT * 16;
+    const int row0 = p.row_base + rg * RT * 16;
     const int L = p.len[b];
     const int nkeys = min(L + p.k, p.g.S);
     const int rows = p.k * p.G;
@@ -571,10 +571,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     // per SIMD, the run's K/V staged once for all of them); up to 8 waves share a run.  Measured against two
     // tiles per wave, attention per layer: 31.5 against 34.4 us (32-node tree, 128 rows per kv head), 54.5
     // against 63.4 (batch 16, k = 8), 9.5 against 11.3 (batch 1, k = 5), 64.8 against 65.7 (70B shape, k = 6).
-    int RT = 1;
-    while ((n_rt + RT - 1) / RT > 8) ++RT;
-    if (RT > n_rt) RT = n_rt;
-    const int n_rg = (n_rt + RT - 1) / RT;
+    // Beyond 8 tiles (128 rows per kv head) two tiles per wave; beyond 16 the rows go through in groups of 16
+    // tiles, one launch each (each streams K/V again: such windows, k*G > 256, are rare).
+    const int tiles_per_launch = std::min(n_rt, 16);
+    const int RT = tiles_per_launch > 8 ? 2 : 1;
+    const int n_rg = (tiles_per_launch + RT - 1) / RT;
     // Which GEMM path.  One workgroup per column tile converting the activations itself
     // (gemm_skinny_kernel) wins for up to 10 rows when the residual GEMMs (d_model / 16 tiles) are exactly
     // one round of one workgroup per compute unit: d_model 4096 on 256 CUs, 107.6 against 114.4 us per
@@ -606,7 +607,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     if (n_waves < wave_slots / 2) rpw = 1;
     rpw = std::min(rpw, n_runs);
     if (n_runs > MAX_RUNS) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: %d key runs", n_runs);
-    const int rows_pad = RT * n_rg * 16;
+    const int rows_pad = (n_rt + RT - 1) / RT * RT * 16;      // whole row groups
 
     const int n_qkv = (Hq + 2 * Hkv) * hd;
     const size_t kmax = (size_t)std::max(std::max(d, qd), F);
@@ -677,11 +678,11 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         t.sat = ctx->sat_dev; t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
         {
             ProfScope ps(ctx, DSD_KC_ATTN);
-            switch (RT) {
-                case 1: DSD_TRY(attn_launch<1>(s, t, n_rg, rpw, Hkv, B)); break;
-                case 2: DSD_TRY(attn_launch<2>(s, t, n_rg, rpw, Hkv, B)); break;
-                case 3: DSD_TRY(attn_launch<3>(s, t, n_rg, rpw, Hkv, B)); break;
-                default: DSD_TRY(attn_launch<4>(s, t, n_rg, rpw, Hkv, B)); break;
+            for (int tile0 = 0; tile0 < n_rt; tile0 += tiles_per_launch) {
+                t.row_base = tile0 * 16;
+                const int rg_here = (std::min(tiles_per_launch, n_rt - tile0) + RT - 1) / RT;
+                if (RT == 1) DSD_TRY(attn_launch<1>(s, t, rg_here, rpw, Hkv, B));
+                else DSD_TRY(attn_launch<2>(s, t, rg_here, rpw, Hkv, B));
             }
         }
         {

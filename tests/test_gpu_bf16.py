@@ -84,10 +84,13 @@ def test_max_rows_tree_32_nodes():
 
 
 def test_long_chains_three_and_four_row_groups():
-    """40 and 64 drafted rows per sequence: 160 and 256 query rows per kv head, i.e. three and four row
-    groups of 64 in the attention (three do not divide a workgroup's waves, four do), and k at its limit."""
+    """40 and 64 drafted rows per sequence: 160 and 256 query rows per kv head, i.e. five and eight waves of
+    two row tiles sharing every run's staged K/V, and k at its limit."""
     check(mini("mini_k40", B=2, k=40, lens=[70, 129], head=True, V=4112, L=1))
     check(mini("mini_k64", B=2, k=64, lens=[33, 64], L=1))
+    # 8 query heads per kv head and 40 drafted rows: 320 query rows per kv head, more than one attention launch
+    # holds (256): the rows go through in two groups, 16 tiles and 4 tiles
+    check(mini("mini_k40_g8", B=1, k=40, lens=[70], Hq=16, Hkv=2, d=1024, F=1536, L=1))
 
 
 def test_shapes_the_panel_path_does_not_take():
