@@ -99,7 +99,8 @@ enum { A_F32_GAIN = 0, A_F32 = 1 };
 enum { EPI_QKV = 0, EPI_SWIGLU = 1, EPI_RESID = 2, EPI_LOGITS = 3 };
 
 struct GemmArgs {
-    const uint4* Wt;      // tiled weights: fragment (tile nt, k-step ks) at (nt*KS + ks)*64 + lane
+    const uint4* Wt;      // tiled weights: fragment (tile nt, k-step ks) at (ks*NTA + nt)*64 + lane
+    int NTA;              // column tiles in the whole weight buffer
     int KS;               // K / 32
     int M;                // rows in use
     // A operand

@@ -44,7 +44,8 @@ __device__ __forceinline__ void vm_wait(u32x4& r) {
 enum { TE_PARTIAL = 0, TE_SWIGLU = 1, TE_LOGITS = 2 };
 
 struct TArgs {
-    const uint4* Wt;     // tiled weights
+    const uint4* Wt;     // tiled weights: fragment (tile nt, k-step ks) at (ks*NTA + nt)*64 + lane
+    int NTA;             // column tiles in the whole weight buffer
     int KS;              // K / 32
     int ks_per_split;    // k-steps per workgroup, multiple of 16
     int M;
@@ -73,10 +74,10 @@ __device__ __forceinline__ void tpanel_fetch(const TArgs& p, int ks_abs, unsigne
 
 // Next k-step of the weight stream; past the end of the slice (the last turn of refills, never
 // consumed) it stays on the last fragment.
-__device__ __forceinline__ void tadvance(const uint4* (&w)[NTW], int& left) {
+__device__ __forceinline__ void tadvance(const uint4* (&w)[NTW], int& left, size_t kstep) {
     if (left > 0) {
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) w[nt] += 64;
+        for (int nt = 0; nt < NTW; ++nt) w[nt] += kstep;
     }
     --left;
 }
@@ -84,7 +85,7 @@ __device__ __forceinline__ void tadvance(const uint4* (&w)[NTW], int& left) {
 // one chunk (4 k-steps) against FIFO slots S0 .. S0 + 4*NTW - 1
 template <int MT, int NF, int S0>
 __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restrict__ panel, f32x4 (&acc)[MT][NTW],
-                                         const uint4* (&w)[NTW], int& left, int lane) {
+                                         const uint4* (&w)[NTW], int& left, size_t kstep, int lane) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         f16x8 a[MT];
@@ -100,7 +101,7 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restr
             // refill one FIFO turn ahead; past the end of the slice keep re-reading the last fragment
             gload16(fifo[slot], w[nt]);
         }
-        tadvance(w, left);
+        tadvance(w, left, kstep);
     }
 }
 
@@ -112,7 +113,7 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restr
 // the refills of (ks, 0..nt-1) have not been issued yet: NF - 1 - nt younger loads.
 template <int MT, int NF, int S0>
 __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* __restrict__ panel,
-                                                f32x4 (&acc)[MT][NTW], const uint4* (&w)[NTW], int& left, int lane) {
+                                                f32x4 (&acc)[MT][NTW], const uint4* (&w)[NTW], int& left, size_t kstep, int lane) {
     constexpr int H = MT / 2;
     f16x8 a[2][H];                                    // [buffer][row tile of the half]
     auto fetch = [&](int buf, int ks, int half) {
@@ -136,7 +137,7 @@ __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* 
             for (int m = 0; m < H; ++m) acc[half * H + m][nt] = mfma16h(a[hs & 1][m], b, acc[half * H + m][nt]);
             if (half == 1) gload16(fifo[slot], w[nt]);
         }
-        if (half == 1) tadvance(w, left);
+        if (half == 1) tadvance(w, left, kstep);
     }
 }
 
@@ -199,7 +200,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
             live[i] = tile[i] < p.N / 16;
         }
         // dead tiles (ragged last column block) stream a valid tile and are not stored
-        w[i] = p.Wt + ((size_t)(live[i] ? tile[i] : 0) * p.KS + ks0) * 64 + lane;
+        w[i] = p.Wt + ((size_t)ks0 * p.NTA + (live[i] ? tile[i] : 0)) * 64 + lane;
     }
 
     // weight fragments in flight per wave: 8 (4 k-steps), 32-64 KiB per compute unit.  Deeper does not help:
@@ -208,11 +209,12 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
     constexpr int NF = 8;
     u32x4 fifo[NF];
     int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
+    const size_t kstep = (size_t)p.NTA * 64;          // from one k-step's fragment to the next
 #pragma unroll
     for (int i = 0; i < NF / NTW; ++i) {
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) gload16(fifo[i * NTW + nt], w[nt]);
-        tadvance(w, left);
+        tadvance(w, left, kstep);
     }
     f32x4 acc[MT][NTW];
 #pragma unroll
@@ -224,8 +226,8 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
     // ks_per_split is a multiple of 16 k-steps = 4 chunks
 #define TILED_CHUNK(Q)                                                                          \
     {                                                                                           \
-        if (MT >= 6) tconsume_halves<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
-        else tconsume<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, lane); \
+        if (MT >= 6) tconsume_halves<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, kstep, lane); \
+        else tconsume<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, kstep, lane); \
         __syncthreads();                                                                        \
     }
     for (int ch = 0; ch < nchunk; ch += 4) {
@@ -592,7 +594,7 @@ static void make_panel(dsd_ctx* ctx, uint4* panel, float* ssq, float* a, const b
 static int tiled_gemm_partial(dsd_ctx* ctx, const void* Wt, int M, int N, int K, const void* panel, float* part,
                               int* n_part) {
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = part; p.N = N;
+    p.Wt = (const uint4*)Wt; p.NTA = N / 16; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = part; p.N = N;
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     const int twc = choose_twc(M, N / 16, ctx->n_cu, true);
     const int nb = ceil_div(N / 16, twc * NTW);
@@ -637,7 +639,7 @@ int tiled_gemm_swiglu(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
+    p.Wt = (const uint4*)Wt; p.NTA = 2 * F / 16; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.n_ssq = K / 128; p.eps = eps; p.panel_out = (unsigned short*)panel_h; p.N = F; p.up_tile_off = F / 16;
     p.sat = ctx->sat_dev;
     // fused SiLU*up needs the whole K in one workgroup: no K split
@@ -652,7 +654,7 @@ int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     if ((K / 32) % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
     make_panel(ctx, (uint4*)panel, ssq, x, gain, part, x_pending, M, K);
     TArgs p = TArgs();
-    p.Wt = (const uint4*)Wt; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
+    p.Wt = (const uint4*)Wt; p.NTA = V / 16; p.KS = K / 32; p.ks_per_split = p.KS; p.M = M; p.panel = (const uint4*)panel; p.ssq = ssq;
     p.n_ssq = K / 128; p.eps = eps; p.out = logits; p.N = V; p.rows_per_seq = rows_per_seq; p.seq_stride = seq_stride;
     // A vocabulary gives several rounds of workgroups, each paying its pipeline fill and its epilogue with
     // the compute unit idle; 256-column workgroups (8 computing waves, a shorter weight FIFO to fit
