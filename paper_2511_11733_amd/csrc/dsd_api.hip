@@ -312,8 +312,7 @@ extern "C" int dsd_kv_create(dsd_ctx* ctx, const dsd_model_desc* desc, int max_b
     g.hd = desc->head_dim;
     g.S = (max_slots + 63) / 64 * 64;
     g.Bmax = max_batch;
-    g.head_elems = (size_t)g.S * g.hd;
-    g.layer_elems = (size_t)g.Bmax * g.Hkv * g.head_elems;
+    g.layer_elems = (size_t)g.Bmax * g.Hkv * g.S * g.hd;
     const size_t bytes = g.layer_elems * desc->n_layers * dsd_elem_size(desc->dtype);
     kv->k = kv->v = nullptr;
     kv->len_dev = nullptr;

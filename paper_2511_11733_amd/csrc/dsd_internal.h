@@ -50,32 +50,36 @@ template <> __device__ inline void st_f32<float>(float* p, float v) { *p = v; }
 template <> __device__ inline void st_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
 // ----------------------------------------------------------------------------- KV cache layout
-// Per layer, sequence and kv head, both caches are kept in the order in which the attention kernel's
-// matrix instructions take their operands, so that a wavefront fetches every operand fragment as
-// one contiguous 1 KiB (hd = 128) piece, lane l taking bytes 16l .. 16l+15:
-//   K : [S/16][hd/8][16][8]          tile of 16 slots; inside it feature group e/8, slot, feature e%8
-//   V : [S/32][hd/16][4][16][8]      block of 32 slots; inside it feature tile e/16, then the slot's
-//                                    place p = v_slot_perm(slot % 32) in the P*V product as p/8,
-//                                    feature e%16, p%8
+// Both caches are kept in the order in which the attention kernel's matrix instructions take their
+// operands, so that a wavefront fetches every operand fragment as one contiguous 1 KiB (hd = 128)
+// piece, lane l taking bytes 16l .. 16l+15.  Per layer the order is block of 32 slots, sequence, kv
+// head: [S/32][Bmax][Hkv][block], and inside a block
+//   K : [2][hd/8][16][8]             tile of 16 slots; inside it feature group e/8, slot, feature e%8
+//   V : [hd/16][4][16][8]            feature tile e/16, then the slot's place p = v_slot_perm(slot % 32)
+//                                    in the P*V product as p/8, feature e%16, p%8
+// Slot blocks come first because every (sequence, head) is walked from its first key on at about the
+// same pace: what the chip reads at any moment is then one advancing band of each cache, not a band
+// per head a whole sequence's cache apart (the same reason the weights are stored k-step major).
 // v_slot_perm is the order in which the score tiles of S^T = K Q^T hand their keys to the P*V
 // product: key 16*tile + 4g + i sits at reduction index 8g + 4*tile + i.
 // S (slots per sequence) is a multiple of 64.
 struct KvGeom {
     int Hkv, hd, S, Bmax;
-    size_t head_elems;   // S * hd
     size_t layer_elems;  // Bmax * Hkv * S * hd
 };
 __host__ __device__ inline int v_slot_perm(int s32) {
     const int tile = s32 >> 4, r = s32 & 15;
     return ((r >> 2) << 3) + (r & 3) + (tile << 2);
 }
+__host__ __device__ inline size_t kv_block_off(const KvGeom& g, int b, int h, int slot) {
+    return ((size_t)(slot >> 5) * (g.Bmax * g.Hkv) + (size_t)(b * g.Hkv + h)) * (size_t)(32 * g.hd);
+}
 __host__ __device__ inline size_t kv_k_off(const KvGeom& g, int b, int h, int slot, int e) {
-    return ((size_t)(b * g.Hkv + h) * g.S + (slot & ~15)) * g.hd + (size_t)(e >> 3) * 128 + (slot & 15) * 8 + (e & 7);
+    return kv_block_off(g, b, h, slot) + (size_t)(slot & 16) * g.hd + (size_t)(e >> 3) * 128 + (slot & 15) * 8 + (e & 7);
 }
 __host__ __device__ inline size_t kv_v_off(const KvGeom& g, int b, int h, int slot, int e) {
     const int p = v_slot_perm(slot & 31);
-    return (size_t)(b * g.Hkv + h) * g.head_elems + (size_t)(slot >> 5) * (g.hd * 32) + (size_t)(e >> 4) * 512 +
-           (p >> 3) * 128 + (e & 15) * 8 + (p & 7);
+    return kv_block_off(g, b, h, slot) + (size_t)(e >> 4) * 512 + (p >> 3) * 128 + (e & 15) * 8 + (p & 7);
 }
 
 // ----------------------------------------------------------------------------- handles

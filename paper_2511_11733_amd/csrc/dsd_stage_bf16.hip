@@ -278,9 +278,9 @@ static int gemm_dispatch(hipStream_t s, const GemmArgs& p, int n_blocks, int n_c
 
 // this wave's share of the fragments of the step at key j0: fragment f for f = rg, rg + n_rg, ...
 __device__ __forceinline__ void attn_fetch(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase, int j0,
-                                           unsigned stage, int lane, int rg, int n_rg) {
-    const bf16_t* kt = kbase + (size_t)j0 * 128 + lane * 8;           // two tiles of 16 keys, 4 fragments each
-    const bf16_t* vb = vbase + (size_t)(j0 >> 5) * (32 * 128) + lane * 8;
+                                           size_t block_stride, unsigned stage, int lane, int rg, int n_rg) {
+    const bf16_t* kt = kbase + (size_t)(j0 >> 5) * block_stride + lane * 8;   // two tiles of 16 keys, 4 fragments each
+    const bf16_t* vb = vbase + (size_t)(j0 >> 5) * block_stride + lane * 8;
     for (int f = rg; f < 16; f += n_rg) {
         if (f < 8) gload16_lds(stage + f * 1024, kt + f * 512);
         else gload16_lds(stage + f * 1024, vb + (f - 8) * 512);
@@ -309,8 +309,9 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
     const int n_steps = run0 < n_chunks ? (n_chunks - run0 + p.n_runs - 1) / p.n_runs : 0;
     const int my_steps = (in_grid && run < n_chunks) ? (n_chunks - run + p.n_runs - 1) / p.n_runs : 0;
     const size_t unit = ((size_t)(b * p.g.Hkv + hk) * p.n_runs + run) * p.rows_pad + row0;
-    const bf16_t* kbase = p.kc + kv_k_off(p.g, b, hk, 0, 0);
-    const bf16_t* vbase = p.vc + (size_t)(b * p.g.Hkv + hk) * p.g.head_elems;
+    const bf16_t* kbase = p.kc + kv_block_off(p.g, b, hk, 0);
+    const bf16_t* vbase = p.vc + kv_block_off(p.g, b, hk, 0);
+    const size_t block_stride = (size_t)p.g.Bmax * p.g.Hkv * (32 * 128);      // from a block of 32 keys to the next
     const uint4* stage_ptr = att_lds + (size_t)rloc * (2 * ATT_STAGE_BYTES / 16);
     const unsigned stage_addr = (unsigned)(size_t)stage_ptr;      // low half of a flat LDS pointer = LDS address
 
@@ -348,12 +349,12 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
     // the loads of the queries above are the compiler's and complete by its own waits; from here on
     // the only vector memory operations in flight are the stage fetches
     vm_wait_all<0>();
-    if (my_steps > 0) attn_fetch(kbase, vbase, run * 32, stage_addr, lane, rg, n_rg);
+    if (my_steps > 0) attn_fetch(kbase, vbase, run * 32, block_stride, stage_addr, lane, rg, n_rg);
     for (int step = 0; step < n_steps; ++step) {
         const int j0 = (step * p.n_runs + run) * 32, st = step & 1;
         vm_wait_all<0>();                             // this wave's share of the step has landed
         __syncthreads();                              // so has everybody's; and the other stage is read no more
-        if (step + 1 < my_steps) attn_fetch(kbase, vbase, j0 + p.n_runs * 32, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane, rg, n_rg);
+        if (step + 1 < my_steps) attn_fetch(kbase, vbase, j0 + p.n_runs * 32, block_stride, stage_addr + (st ^ 1) * ATT_STAGE_BYTES, lane, rg, n_rg);
         if (step >= my_steps) continue;               // a shorter run of the same workgroup: barriers only
         const uint4* sp = stage_ptr + st * (ATT_STAGE_BYTES / 16) + lane;
         f32x4 s[2][RT];
@@ -545,7 +546,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         // positions), so they go through in groups of up to 128 rows; every group streams the
         // weights once more, which at this many rows per weight byte is no longer the only cost.
         const int per = 128 / k;
-        const size_t seq_cache_bytes = (size_t)g.Hkv * g.head_elems * sizeof(bf16_t);
+        const size_t seq_cache_bytes = (size_t)g.Hkv * 32 * g.hd * sizeof(bf16_t);     // a sequence's share of a block of 32 slots
         const int64_t lstride = logits_seq_stride ? logits_seq_stride : (int64_t)k * D.vocab;
         for (int b0 = 0; b0 < B; b0 += per) {
             const int nb = std::min(per, B - b0);
