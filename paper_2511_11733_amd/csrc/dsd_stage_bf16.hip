@@ -315,6 +315,10 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
     const uint4* stage_ptr = att_lds + (size_t)rloc * (2 * ATT_STAGE_BYTES / 16);
     const unsigned stage_addr = (unsigned)(size_t)stage_ptr;      // low half of a flat LDS pointer = LDS address
 
+    // The first step is requested before anything else: its way from memory overlaps the queries'.  (The
+    // compiler counts only its own loads when it waits for a query; vector loads come back in order, so the
+    // older stage fetches it does not know about can only make such a wait longer than needed.)
+    if (my_steps > 0) attn_fetch(kbase, vbase, run * 32, block_stride, stage_addr, lane, rg, n_rg);
     bf16x8 qh[RT][4], ql[RT][4];
     uint64_t vis[RT];
 #pragma unroll
@@ -332,6 +336,10 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
                 v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
                 v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
             }
+            // the queries carry the softmax scale and log2(e): scores come out of the matrix
+            // instructions ready for exp2
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] *= p.scale_log2e;
             split8(v, &qh[rt][j], &ql[rt][j]);
         }
     }
@@ -346,10 +354,6 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
         mrow[rt] = -INFINITY;
         lrow[rt] = 0.f;
     }
-    // the loads of the queries above are the compiler's and complete by its own waits; from here on
-    // the only vector memory operations in flight are the stage fetches
-    vm_wait_all<0>();
-    if (my_steps > 0) attn_fetch(kbase, vbase, run * 32, block_stride, stage_addr, lane, rg, n_rg);
     for (int step = 0; step < n_steps; ++step) {
         const int j0 = (step * p.n_runs + run) * 32, st = step & 1;
         vm_wait_all<0>();                             // this wave's share of the step has landed
@@ -386,11 +390,7 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
 #pragma unroll
                 for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float v = s[tl][rt][i] * p.scale_log2e;
-                        s[tl][rt][i] = v;
-                        mx = fmaxf(mx, v);
-                    }
+                    for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[tl][rt][i]);
             } else {
 #pragma unroll
                 for (int tl = 0; tl < 2; ++tl)
@@ -399,33 +399,42 @@ __global__ void __launch_bounds__(512, 2) attn_stream_kernel(AttnArgs p, int n_r
                         const int key = j0 + tl * 16 + g * 4 + i;
                         bool ok = key < L;
                         if (!ok && key < nkeys) ok = (vis[rt] >> (key - L)) & 1ull;
-                        const float v = ok ? s[tl][rt][i] * p.scale_log2e : -INFINITY;
+                        const float v = ok ? s[tl][rt][i] : -INFINITY;
                         s[tl][rt][i] = v;
                         mx = fmaxf(mx, v);
                     }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
             mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-            const float mnew = fmaxf(mrow[rt], mx);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = exp2f(mrow[rt] - muse);      // 0 when mrow was -inf
-            mrow[rt] = mnew;
+            // The reference exponent of a row moves only when a score exceeds it by more than 2^8 (any
+            // reference gives the same softmax as long as nothing overflows; weights up to 256 are far
+            // from that), so after a row's first few steps the rescaling of its sums and outputs is
+            // skipped: one uniform branch instead of 34 multiplications.
+            if (__builtin_amdgcn_ballot_w64(mx > mrow[rt] + 8.0f) != 0) {
+                const float mnew = fmaxf(mrow[rt], mx);
+                const float alpha = __builtin_amdgcn_exp2f(mrow[rt] - ((mnew == -INFINITY) ? 0.f : mnew));   // 0 when mrow was -inf
+                mrow[rt] = mnew;
+                lrow[rt] *= alpha;
+#pragma unroll
+                for (int h = 0; h < 8; ++h) o[h][rt] *= alpha;
+            }
+            const float muse = (mrow[rt] == -INFINITY) ? 0.f : mrow[rt];
             float pv[8];
             float ps = 0.f;
 #pragma unroll
             for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float e = exp2f(s[tl][rt][i] - muse);
+                    // the bare instruction: results below 2^-126 become 0, which is what a weight that small is
+                    const float e = __builtin_amdgcn_exp2f(s[tl][rt][i] - muse);
                     pv[tl * 4 + i] = e;
                     ps += e;
                 }
-            lrow[rt] = lrow[rt] * alpha + ps;
+            lrow[rt] += ps;
             bf16x8 ph, pl;
             split8(pv, &ph, &pl);
 #pragma unroll
             for (int h = 0; h < 8; ++h) {
-                o[h][rt] *= alpha;
                 o[h][rt] = mfma16(vf[h], ph, o[h][rt]);
                 o[h][rt] = mfma16(vf[h], pl, o[h][rt]);
             }
