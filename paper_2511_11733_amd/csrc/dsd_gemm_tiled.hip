@@ -461,12 +461,11 @@ static int tiled_launch(hipStream_t s, const TArgs& p, int n_blocks, int ksplit)
     return DSD_OK;
 }
 
-// twc = computing waves per workgroup: 8 for up to 64 rows, and for the LM head at any row count
+// twc = computing waves per workgroup: 4 to 8 for the K-sliced GEMMs and gate/up (see choose_partial,
+// choose_twc_pairs), 4 or 8 for the LM head
 template <int EPI>
 static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, int ksplit) {
     const int mt = (p.M + 15) / 16;
-    if constexpr (EPI == TE_SWIGLU) {                    // gate/up: any number of computing waves from 4 to 8 (see choose_twc_pairs)
-        if (twc >= 5 && twc <= 7) {
 #define TILED_CASE(T)                                                                    \
     case T:                                                                              \
         switch (mt) {                                                                    \
@@ -477,45 +476,27 @@ static int tiled_dispatch(hipStream_t s, const TArgs& p, int twc, int n_blocks, 
             case 7: case 8: return tiled_launch<8, T, EPI>(s, p, n_blocks, ksplit);      \
             default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: %d rows", p.M);             \
         }
-            switch (twc) {
-                TILED_CASE(5)
-                TILED_CASE(6)
-                TILED_CASE(7)
-            }
+    if constexpr (EPI != TE_LOGITS) {
+        switch (twc) {
+            TILED_CASE(5)
+            TILED_CASE(6)
+            TILED_CASE(7)
+        }
+    }
+    switch (twc) {
+        TILED_CASE(4)
+        TILED_CASE(8)
+    }
 #undef TILED_CASE
-        }
-    }
-    if (twc == 8) {
-        switch (mt) {
-            case 1: case 2: return tiled_launch<2, 8, EPI>(s, p, n_blocks, ksplit);
-            case 3: return tiled_launch<3, 8, EPI>(s, p, n_blocks, ksplit);
-            case 4: return tiled_launch<4, 8, EPI>(s, p, n_blocks, ksplit);
-            // more row tiles with 8 computing waves: only the kernels that do not cut K (see choose_twc)
-            case 5: case 6:
-                if constexpr (EPI != TE_PARTIAL) return tiled_launch<6, 8, EPI>(s, p, n_blocks, ksplit);
-            case 7: case 8:
-                if constexpr (EPI != TE_PARTIAL) return tiled_launch<8, 8, EPI>(s, p, n_blocks, ksplit);
-            default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: 8 computing waves with %d rows", p.M);
-        }
-    }
-    switch (mt) {
-        case 1: case 2: return tiled_launch<2, 4, EPI>(s, p, n_blocks, ksplit);
-        case 3: return tiled_launch<3, 4, EPI>(s, p, n_blocks, ksplit);
-        case 4: return tiled_launch<4, 4, EPI>(s, p, n_blocks, ksplit);
-        case 5: case 6: return tiled_launch<6, 4, EPI>(s, p, n_blocks, ksplit);
-        case 7: case 8: return tiled_launch<8, 4, EPI>(s, p, n_blocks, ksplit);
-        default: DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: %d rows", p.M);
-    }
+    DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: %d computing waves", twc);
 }
 
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Column tiles (16 wide) per workgroup: 16 (8 computing waves) when the matrix is wide enough to give
-// about a workgroup per compute unit without cutting K, else 8.  More than 4 row tiles run 8
-// computing waves only in the kernels that do not cut K (gate/up, LM head): those are the ones with
-// several rounds of workgroups to halve.
-static int choose_twc(int M, int n_tiles16, int n_cu, bool k_sliced) {
-    if ((M + 15) / 16 > 4 && k_sliced) return 4;
+// Computing waves of an LM-head workgroup (2 column tiles each): 8 when the vocabulary is wide enough to
+// give about a workgroup per compute unit that way, else 4.  A vocabulary gives several rounds of
+// workgroups, each paying its pipeline fill and its epilogue; 8 waves halve the number of rounds.
+static int choose_twc_head(int n_tiles16, int n_cu) {
     return (long)ceil_div(n_tiles16, 8 * NTW) * 5 >= (long)n_cu * 4 ? 8 : 4;
 }
 
@@ -547,10 +528,10 @@ static int choose_twc_pairs(int n_pairs, int n_cu) {
 // the fixed part again.  The four constants are fitted to measured sweeps of the slice count at
 // 48 and 128 rows (d_model 4096 and 8192); the pick is within 1.5 us of the best there.
 // Returns 0 if K cannot be cut that way.
-static int choose_ksplit(int KS, int n_blocks, int slots, int n_cu, int cols_per_block, int M, int N) {
+static int choose_ksplit(int KS, int n_blocks, int slots, int n_cu, int cols_per_block, int M, int N, double* t_us) {
     if (KS % 16) return 0;
     const int units = KS / 16;
-    const double fixed_us = 3.0, chip_bytes_per_us = 5.4e6, cu_bytes_per_us = 28e3, reduce_bytes_per_us = 2.0e6;
+    const double fixed_us = 3.0, chip_bytes_per_us = 5.4e6, cu_bytes_per_us = 28e3, reduce_bytes_per_us = 3.0e6;
     int best = 1;
     double best_t = 1e30;
     for (int sp = 1; sp <= units && sp <= TILED_MAX_KSPLIT; ++sp) {
@@ -568,6 +549,7 @@ static int choose_ksplit(int KS, int n_blocks, int slots, int n_cu, int cols_per
             best = sp;
         }
     }
+    *t_us = best_t;
     return best;
 }
 // workgroups of the tiled kernel the chip holds at once: two per compute unit up to 3 row tiles
@@ -596,9 +578,21 @@ static int tiled_gemm_partial(dsd_ctx* ctx, const void* Wt, int M, int N, int K,
     TArgs p = TArgs();
     p.Wt = (const uint4*)Wt; p.NTA = N / 16; p.KS = K / 32; p.M = M; p.panel = (const uint4*)panel; p.out = part; p.N = N;
     if (p.KS % 16) DSD_FAIL(DSD_EUNSUPPORTED, "tiled GEMM: K=%d", K);
-    const int twc = choose_twc(M, N / 16, ctx->n_cu, true);
+    // computing waves per workgroup and K slices together: the pair with the smallest estimated time
+    // (ties go to the smaller workgroup).  E.g. 640 column tiles (QKV at d_model 8192) on 256 compute
+    // units: 5 waves x 4 slices = 256 workgroups, where 4 waves give 160 or 320.
+    int twc = 4, sp = 1;
+    double best_t = 1e30;
+    for (int t = 4; t <= 8; ++t) {
+        double t_us = 0;
+        const int sp_t = choose_ksplit(p.KS, ceil_div(N / 16, t * NTW), tiled_slots(M, t, ctx->n_cu), ctx->n_cu, t * NTW * 16, M, N, &t_us);
+        if (t_us < best_t) {
+            best_t = t_us;
+            twc = t;
+            sp = sp_t;
+        }
+    }
     const int nb = ceil_div(N / 16, twc * NTW);
-    const int sp = choose_ksplit(p.KS, nb, tiled_slots(M, twc, ctx->n_cu), ctx->n_cu, twc * NTW * 16, M, N);
     p.ks_per_split = p.KS / sp;
     *n_part = sp;
     return tiled_dispatch<TE_PARTIAL>(ctx->stream, p, twc, nb, sp);
@@ -659,6 +653,6 @@ int tiled_gemm_logits(dsd_ctx* ctx, const void* Wt, float* x, const bf16_t* gain
     // A vocabulary gives several rounds of workgroups, each paying its pipeline fill and its epilogue with
     // the compute unit idle; 256-column workgroups (8 computing waves, a shorter weight FIFO to fit
     // the registers) halve the number of rounds.  Measured at 128 rows, V = 128256: 254 -> 238 us.
-    const int twc = choose_twc(M, V / 16, ctx->n_cu, false);
+    const int twc = choose_twc_head(V / 16, ctx->n_cu);
     return tiled_dispatch<TE_LOGITS>(ctx->stream, p, twc, ceil_div(V / 16, twc * NTW), 1);
 }
