@@ -111,7 +111,7 @@ def dominant_kernel(cfg, kern, per_layer, total_bytes):
     the gate/up GEMM (54 % of a layer's weight bytes)."""
     m = cfg.model
     M = cfg.B * cfg.k
-    if M <= 10 and m.d // 16 <= 256:      # the library's switch-over between its two GEMM paths
+    if M <= 3 and m.d // 16 <= 256:       # the library's switch-over between its two GEMM paths
         return ("gateup", per_layer["gateup"],
                 "gemm_skinny_kernel<1, 2, A_F32_GAIN, EPI_SWIGLU, 4> (RMSNorm + gate/up GEMM + SiLU*up, one launch)",
                 "gemm_skinny_kernel<1, 2, 0, 1")
@@ -135,8 +135,11 @@ def committed_traffic(cfg_name, match):
     path = os.path.join(ROOT, "profiles", f"verify_step_{cfg_name}.txt")
     if not os.path.exists(path):
         return None, None
+    in_counters = False               # the kernel also has a line in the timing table further up
     for line in open(path):
-        if match in line:
+        if line.startswith("HBM byte counters"):
+            in_counters = True
+        if in_counters and match in line:
             parts = line.split()
             try:
                 return (float(parts[-2]) + float(parts[-1])) * 1e6, f"profiles/verify_step_{cfg_name}.txt"

@@ -1,9 +1,9 @@
-// Weight-streaming GEMM for 11..128 rows (B*k of the batched verification pass, section 2.1).
+// Weight-streaming GEMM for up to 128 rows (B*k of the batched verification pass, section 2.1).
 //
-// With this many rows the pass is still bound by streaming the weights once, but the activation
-// operand is no longer negligible: every weight fragment meets MT activation fragments (one fp16
-// plane of MT 16-row tiles; two planes, as the kernels for up to 10 rows use, would make the matrix
-// cores the bound at 128 rows).  So the activations are shared through LDS and only the weights
+// The pass is bound by streaming the weights once, but with many rows the activation operand is no
+// longer negligible: every weight fragment meets MT activation fragments (one fp16 plane of MT
+// 16-row tiles; two planes, as the one-workgroup-per-tile kernels use, would make the matrix cores
+// the bound at 128 rows).  So the activations are shared through LDS and only the weights
 // come straight from HBM into registers:
 //   * a workgroup of 4 (or 8) computing waves owns 128 (256) output columns, each wave two
 //     16-column tiles, over one contiguous slice of K (grid.y splits K when a matrix has too few

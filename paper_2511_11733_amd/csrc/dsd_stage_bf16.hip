@@ -11,10 +11,10 @@
 //     KV-cache append, SiLU*up, residual add, or fp32 logits;
 //   * RMSNorm never makes a pass of its own: x*g is applied while the A operand is loaded, the
 //     sum of squares is accumulated from those same loads, and 1/rms scales the output rows;
-//   * up to 10 rows, activations enter the matrix cores as a sum of two fp16 terms (hi + lo, two
+//   * in these kernels activations enter the matrix cores as a sum of two fp16 terms (hi + lo, two
 //     MFMAs per weight fragment, ~22 significant bits; the extra MFMA work is free while the pass is
-//     bandwidth bound); from 11 rows on as one fp16 term (11 bits, see dsd_gemm_tiled.hip).  Queries
-//     and attention weights meet the bf16 cache as hi + lo bf16;
+//     bandwidth bound); on the panel path (dsd_gemm_tiled.hip: most row counts) as one fp16 term
+//     (11 bits).  Queries and attention weights meet the bf16 cache as hi + lo bf16;
 //   * attention computes S^T = K Q^T so that the scores a lane holds are exactly the P^T operand
 //     of O^T = V^T P^T; V is cached transposed for that product (see KvGeom).
 #include <stdlib.h>
@@ -591,12 +591,13 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const int RT = tiles_per_launch > 8 ? 2 : 1;
     const int n_rg = (tiles_per_launch + RT - 1) / RT;
     // Which GEMM path.  One workgroup per column tile converting the activations itself
-    // (gemm_skinny_kernel) wins for up to 10 rows when the residual GEMMs (d_model / 16 tiles) are exactly
-    // one round of one workgroup per compute unit: d_model 4096 on 256 CUs, 107.6 against 114.4 us per
-    // layer at 5 rows; from 11 rows on the panel path wins there too (0.95 against 0.99 ms at 12 rows,
-    // 0.97 against 1.12 at 16).  Wider models leave that kernel a ragged second round, and the panel
-    // path wins at every row count: per layer at 5 rows 136.9 against 149.0 us (d_model 5120), 166.8
-    // against 182.4 (6144), 333.7 against 353.2 (8192).
+    // (gemm_skinny_kernel) wins only for up to 3 rows, and only when the residual GEMMs (d_model / 16
+    // tiles) are exactly one round of one workgroup per compute unit: d_model 4096 on 256 CUs, 0.826
+    // against 0.831 ms per step of 8 layers at 1 row; the panel path wins from there on (0.842 against
+    // 0.851 ms at 5 rows, 0.846 against 0.879 at 8, 0.858 against 0.931 at 10, 0.861 against 0.957
+    // at 11).  Wider models leave that kernel a ragged second round, and the panel path wins at every
+    // row count: per layer at 5 rows 136.9 against 149.0 us (d_model 5120), 166.8 against 182.4
+    // (6144), 333.7 against 353.2 (8192).
     const int tiled_min_rows = d / 16 <= ctx->n_cu ? TILED_MIN_ROWS : 1;
     const bool tiled = M >= tiled_min_rows && tiled_supported(&D) && !ctx->no_tiled;
     // The LM head takes the panel path at every row count: a vocabulary is a gigabyte of weights, and 256-column
@@ -739,7 +740,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
             else DSD_TRY((gemm_dispatch<1, A_F32, EPI_RESID>(s, a, d / 16, ctx->n_cu)));
         }
     }
-    // the block's output rows: up to 10 rows the last down projection's epilogue has written them; on the
+    // the block's output rows: off the panel path the last down projection's epilogue has written them; on the
     // panel path they leave with the sum of that projection's K slices
     if (hidden_out && tiled) {
         ProfScope ps(ctx, DSD_KC_OTHER);

@@ -112,9 +112,9 @@ def test_head_dim_64_in_bf16_takes_the_generic_kernels():
 
 
 def test_both_gemm_paths_on_the_same_case():
-    """15 and 40 rows through the panel GEMMs (the default from 11 rows on) and, with DSD_NO_TILED, through
-    the one-workgroup-per-tile kernels: each against the oracle."""
-    for name, B, k in (("both_m15", 3, 5), ("both_m40", 5, 8)):
+    """2, 5, 10, 15 and 40 rows through the default path (the panel GEMMs from 4 rows on) and, with DSD_NO_TILED,
+    through the one-workgroup-per-tile kernels: each against the oracle."""
+    for name, B, k in (("both_m2", 1, 2), ("both_m5", 1, 5), ("both_m10", 2, 5), ("both_m15", 3, 5), ("both_m40", 5, 8)):
         case = mini(name, B=B, k=k, lens=[90 + 13 * b for b in range(B)], head=True, V=4112, L=2)
         check(case)
         check(case, no_tiled=True)
@@ -188,7 +188,7 @@ def test_wide_gqa_group_70b_like():
     check(mini("mini_70b", B=2, k=6, lens=[140, 200], Hq=16, Hkv=2, d=1024, F=2048))
 
 
-# ---- d_model 2048 (K a multiple of 2048), up to 10 rows: the one-workgroup-per-tile kernels at a narrower model
+# ---- d_model 2048 (K a multiple of 2048), few rows at a narrower model
 def test_d2048_mid_stage_chain():
     check(mini("d2048_mid", B=1, k=5, lens=[300], d=2048, Hq=16, Hkv=4, F=4096))
     check(mini("d2048_mid8", B=2, k=4, lens=[77, 130], d=2048, Hq=16, Hkv=4, F=4096))
@@ -225,21 +225,35 @@ def wide_ffn_case(name, B, k, spread):
     return case
 
 
-@pytest.mark.parametrize("B,k", [(1, 5), (4, 6)])          # both GEMM paths: up to 10 rows, 11 rows and more
-def test_large_ffn_intermediates_inside_the_fp16_range_keep_parity(B, k):
+def stage_on_path(m, w, B, slots, no_tiled):
+    """A stage on a context of its own; no_tiled: the one-workgroup-per-tile GEMMs at every row count."""
+    if no_tiled:
+        os.environ["DSD_NO_TILED"] = "1"
+    try:
+        return H.GpuStage(m, w, B, slots)
+    finally:
+        os.environ.pop("DSD_NO_TILED", None)
+
+
+# both GEMM paths, and the panel path with two row-tile counts
+BOTH_PATHS = [(1, 5, False), (4, 6, False), (1, 5, True)]
+
+
+@pytest.mark.parametrize("B,k,no_tiled", BOTH_PATHS)
+def test_large_ffn_intermediates_inside_the_fp16_range_keep_parity(B, k, no_tiled):
     """SiLU(gate)*up up to about 3e4: inside the range, so parity with the oracle holds and nothing is counted."""
     case = wide_ffn_case(f"ffn_big_{B * k}", B, k, spread=40.0)
     cfg, m, w, K, V, hid, parent, lens = case
     ref = O.stage_forward(m, w.__getitem__, K, V, lens, hid, None, want_taps=False)
-    st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
+    st = stage_on_path(m, w, cfg.B, max(lens) + cfg.k + 3, no_tiled)
     st.import_kv(K, V, lens)
     out, _ = st.verify(hidden=hid)
     H.assert_close(H.to_np64(out), ref.hidden, H.TOL["bf16"], f"{cfg.name} hidden")
     assert st.ctx.stage_status() == 0
 
 
-@pytest.mark.parametrize("B,k", [(1, 5), (4, 6)])
-def test_ffn_intermediates_beyond_the_fp16_range_are_reported(B, k):
+@pytest.mark.parametrize("B,k,no_tiled", BOTH_PATHS)
+def test_ffn_intermediates_beyond_the_fp16_range_are_reported(B, k, no_tiled):
     """SiLU(gate)*up in the 1e6 range: the fp16 operands saturate, the result is not the model's, and
     dsd_stage_status says so (and is clean again afterwards)."""
     case = wide_ffn_case(f"ffn_over_{B * k}", B, k, spread=400.0)
@@ -247,7 +261,7 @@ def test_ffn_intermediates_beyond_the_fp16_range_are_reported(B, k):
     bn = O.rms_norm(O.widen(hid), O.widen(w["l0.g2"]), m.eps)       # the order of magnitude, from the oracle's pieces
     hmax = np.abs(O.silu(bn @ O.widen(w["l0.wg"]).T) * (bn @ O.widen(w["l0.wu"]).T)).max()
     assert hmax > 2 * 65504
-    st = H.GpuStage(m, w, cfg.B, max(lens) + cfg.k + 3)
+    st = stage_on_path(m, w, cfg.B, max(lens) + cfg.k + 3, no_tiled)
     st.import_kv(K, V, lens)
     st.verify(hidden=hid)
     with pytest.raises(H.D.DsdError, match="65504"):
@@ -281,7 +295,7 @@ def test_stage_replays_from_a_hip_graph():
     """Once the workspace has its size the call issues only kernels on the context's stream, so a caller
     may capture it; every replay (with eager work and synchronisations in between) must reproduce the
     eager result bit for bit: every sum on the path is taken in a fixed order (K slices of the GEMMs
-    from 11 rows on land in buffers of their own and are added up slice by slice), so two runs
+    on the panel path land in buffers of their own and are added up slice by slice), so two runs
     on the same inputs may not differ at all."""
     for name, B, k in (("graph_m5", 1, 5), ("graph_m40", 5, 8)):
         cfg, m, w, K, V, hid, parent, lens = mini(name, B=B, k=k, lens=[70 + 9 * b for b in range(B)], head=True,
