@@ -112,7 +112,8 @@ int dsd_create(int device, void* hip_stream, dsd_ctx** out);
 int dsd_destroy(dsd_ctx* ctx);
 int dsd_set_stream(dsd_ctx* ctx, void* hip_stream);
 
-/* Takes the layer block.  `tensors` is a host array of n_tensors device pointers in this order:
+/* Takes the layer block a node hosts (section 2.2: each node holds a contiguous shard of the
+ * target model's layers).  `tensors` is a host array of n_tensors device pointers in this order:
  *   [embed V x d]                                              if has_embed
  *   per layer: g1[d], Wq[Hq*hd x d], Wk[Hkv*hd x d], Wv[Hkv*hd x d], Wo[d x Hq*hd],
  *              g2[d], Wg[F x d], Wu[F x d], Wd[d x F]
@@ -129,11 +130,15 @@ int dsd_weights_create(dsd_ctx* ctx, const dsd_model_desc* desc, const void* con
 int dsd_weights_destroy(dsd_ctx* ctx, dsd_weights* w);
 
 /* KV cache for max_batch sequences of up to max_slots positions (committed + drafted) in
- * every layer of the block.  Lengths start at 0.  The storage layout is the library's. */
+ * every layer of the block: the state the single forward pass over the window of section 2.1
+ * reads (committed context) and extends (the k drafted rows).  Lengths start at 0.  The storage
+ * layout is the library's. */
 int dsd_kv_create(dsd_ctx* ctx, const dsd_model_desc* desc, int max_batch, int max_slots, dsd_kv** out);
 int dsd_kv_destroy(dsd_ctx* ctx, dsd_kv* kv);
 
-/* Loads positions [0, n_slots) of one layer from device arrays k, v of shape
+/* Brings in the keys and values of an already processed context (the prompt, or a cache kept
+ * elsewhere), which verification in section 2.1 presupposes: loads positions [0, n_slots) of one
+ * layer from device arrays k, v of shape
  * [B, Hkv, n_slots, hd] (desc dtype; keys already rotated).  Does not change lengths. */
 int dsd_kv_import(dsd_ctx* ctx, dsd_kv* kv, int layer, const void* k, const void* v, int B, int n_slots);
 /* Reads positions [first_slot, first_slot + n_slots) of one layer back into device arrays of
