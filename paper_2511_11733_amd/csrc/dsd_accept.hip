@@ -839,7 +839,7 @@ draw_parts_kernel(const float* __restrict__ logits, const float* __restrict__ qp
 __global__ void __launch_bounds__(TPB)
 draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp, const float* __restrict__ uniforms,
                  AcceptWs ws, int R, int V, int S, double inv_temp, int32_t* __restrict__ next_token) {
-    __shared__ double pre[TPB + 1];
+    __shared__ double pre[TPB / WAVE];
     __shared__ int sh_slice, sh_fallback, sh_best[TPB / WAVE], sh_last[TPB / WAVE];
     __shared__ double sh_before, sh_target;
     const int b = blockIdx.x;
@@ -916,16 +916,22 @@ draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
         }
         loc += w[j];
     }
-    pre[threadIdx.x + 1] = loc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        pre[0] = before < 0.0 ? 0.0 : before;
-        for (int t = 1; t <= TPB; ++t) pre[t] += pre[t - 1];
+    // mass before this thread's ids: scan over the lanes of a wave, then the waves before it, in thread order
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    double inc = loc;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        const double t = __shfl_up(inc, o, WAVE);
+        if (lane >= o) inc += t;
     }
+    if (lane == WAVE - 1) pre[wave] = inc;
     __syncthreads();
+    double start = before < 0.0 ? 0.0 : before;
+    for (int i = 0; i < wave; ++i) start += pre[i];
+    start += inc - loc;
     int found = 0x7FFFFFFF;
     if (before >= 0.0) {
-        double c = pre[threadIdx.x];
+        double c = start;
 #pragma unroll
         for (int j = 0; j < EPT; ++j) {
             c += w[j];
