@@ -311,7 +311,26 @@ __global__ void __launch_bounds__(256) act_panel_kernel(uint4* __restrict__ pane
             const float* ps = part + (size_t)row * K + kb;
             const size_t slice = (size_t)M * K;
             int sl = 0;
-            for (; sl + 4 <= n_part; sl += 4, ps += 4 * slice) {      // four slices in flight, added in slice order
+            // up to eight slices in flight (the usual counts, 4..8, then take one trip to memory), added in slice order
+            if (n_part >= 5 && n_part <= 8) {
+                float4 p0[8], p1[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (u < n_part) {
+                        p0[u] = *(const float4*)(ps + u * slice);
+                        p1[u] = *(const float4*)(ps + u * slice + 4);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (u < n_part) {
+                        v0.x += p0[u].x; v0.y += p0[u].y; v0.z += p0[u].z; v0.w += p0[u].w;
+                        v1.x += p1[u].x; v1.y += p1[u].y; v1.z += p1[u].z; v1.w += p1[u].w;
+                    }
+                }
+                sl = n_part;
+            }
+            for (; sl + 4 <= n_part; sl += 4, ps += 4 * slice) {
                 float4 p0[4], p1[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
