@@ -791,7 +791,7 @@ __global__ void __launch_bounds__(ROW_TPB) row_merge_kernel(RowArgs p, AcceptWs 
 
 // weight of id i in the distribution the extra token is drawn from; also P itself
 __device__ inline void draw_weight(const float* __restrict__ logits, const float* __restrict__ qp, size_t row, int i,
-                                   double inv_temp, double lse, int mode, double tau, double z, double* w,
+                                   double inv_temp, double lse, int mode, double tau, double inv_z, double* w,
                                    double* p) {
     const float ln_pt = (float)((double)logits[row + i] * inv_temp - lse);
     if (mode == 0) {
@@ -799,7 +799,7 @@ __device__ inline void draw_weight(const float* __restrict__ logits, const float
         *w = *p;
     } else {
         const float q = qp[row + i];
-        *p = (double)soft_weight_f(ln_pt, q, (float)tau) / z;
+        *p = (double)soft_weight_f(ln_pt, q, (float)tau) * inv_z;
         *w = fmax(*p - (double)q, 0.0);
     }
 }
@@ -811,7 +811,7 @@ draw_parts_kernel(const float* __restrict__ logits, const float* __restrict__ qp
     __shared__ double shd[TPB / WAVE];
     const int s = blockIdx.x, b = blockIdx.y;
     const int r = ws.draw_row[b], mode = ws.draw_mode[b];
-    const double tau = ws.draw_tau[b], z = ws.draw_z[b];
+    const double tau = ws.draw_tau[b], inv_z = 1.0 / ws.draw_z[b];   // one division per thread, a product per id
     const size_t row = ((size_t)b * R + r) * V;
     const double lse = ws.row_lse[(size_t)b * R + r];
     double sw = 0.0, sp = 0.0;
@@ -821,7 +821,7 @@ draw_parts_kernel(const float* __restrict__ logits, const float* __restrict__ qp
         const int i = base + threadIdx.x + j * TPB;
         if (i < V) {
             double w, p;
-            draw_weight(logits, qp, row, i, inv_temp, lse, mode, tau, z, &w, &p);
+            draw_weight(logits, qp, row, i, inv_temp, lse, mode, tau, inv_z, &w, &p);
             sw += w;
             sp += p;
         }
@@ -844,7 +844,7 @@ draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
     __shared__ double sh_before, sh_target;
     const int b = blockIdx.x;
     const int r = ws.draw_row[b], mode = ws.draw_mode[b];
-    const double tau = ws.draw_tau[b], z = ws.draw_z[b];
+    const double tau = ws.draw_tau[b], inv_z = 1.0 / ws.draw_z[b];   // one division per thread, a product per id
     const size_t row = ((size_t)b * R + r) * V;
     const double lse = ws.row_lse[(size_t)b * R + r];
     if (threadIdx.x < WAVE) {
@@ -910,7 +910,7 @@ draw_pick_kernel(const float* __restrict__ logits, const float* __restrict__ qp,
         w[j] = 0.0;
         if (i < V) {
             double ww, pp;
-            draw_weight(logits, qp, row, i, inv_temp, lse, mode, tau, z, &ww, &pp);
+            draw_weight(logits, qp, row, i, inv_temp, lse, mode, tau, inv_z, &ww, &pp);
             w[j] = fb ? pp : ww;
             if (w[j] > 0.0) lastpos = i;
         }
