@@ -286,6 +286,7 @@ def run_workload(args, name, want_inputs):
             buf.zero_()
             stream.synchronize()
             probe = {"bytes": 1 << 30, "read_GBps": (1 << 30) / ctx.stream_probe(buf, 0, 10) / 1e6,
+                     "read_nontemporal_GBps": (1 << 30) / ctx.stream_probe(buf, 3, 10) / 1e6,
                      "read_one_stream_per_wave_GBps": (1 << 30) / ctx.stream_probe(buf, 2, 10) / 1e6,
                      "copy_read_plus_write_GBps": (1 << 30) / ctx.stream_probe(buf, 1, 10) / 1e6,
                      "measured": "hip events on the library stream, average of 10 launches after 2 warm-up launches"}

@@ -279,8 +279,9 @@ int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launches);
  * the paper's own argument (section 2.1, Fig. 1) makes memory bound.  buf: device, `bytes` long (a multiple
  * of 32, at least 1 MiB, 16-byte aligned), contents irrelevant.  mode 0: one kernel reads all of it, the
  * whole grid sweeping one contiguous front; mode 1: one kernel copies its first half onto its second half
- * (bytes/2 read + bytes/2 written); mode 2: one kernel reads it the way the weight-streaming kernels do,
- * every wave a contiguous stream of its own (bytes rounded down to whole streams of 16 KiB steps).
+ * (bytes/2 read + bytes/2 written); mode 2: one kernel reads it with every wave walking a contiguous
+ * stream of its own (bytes rounded down to whole streams of 16 KiB steps); mode 3: as mode 0 with
+ * non-temporal loads, which is how the library's kernels read what they read once (weights, K/V).
  * Runs 2 untimed + `iters` timed launches on the context's stream, synchronises, and returns the
  * average time of a launch in *ms_avg (host). */
 int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode, int iters, double* ms_avg);

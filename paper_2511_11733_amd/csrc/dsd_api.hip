@@ -107,24 +107,21 @@ extern "C" int dsd_profile_read(dsd_ctx* ctx, double* ms_total, int64_t* launche
 // kernels are measured against besides the published peak.  Every thread keeps U 16-byte loads in
 // flight over a grid-stride walk; the read kernel folds what it loads into a word that it stores only
 // for a value that does not occur, so the loads cannot be dropped.
-template <int U>
+template <int U, bool NT>
 __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ p, size_t n, unsigned* __restrict__ sink) {
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t* q = (const u32x4_t*)p;
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    uint4 a = make_uint4(0, 0, 0, 0);
+    u32x4_t a = {0u, 0u, 0u, 0u};
     for (; i + (U - 1) * stride < n; i += U * stride) {
-        uint4 v[U];
+        u32x4_t v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+        for (int u = 0; u < U; ++u) v[u] = NT ? __builtin_nontemporal_load(q + i + u * stride) : q[i + u * stride];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            a.x ^= v[u].x; a.y ^= v[u].y; a.z ^= v[u].z; a.w ^= v[u].w;
-        }
+        for (int u = 0; u < U; ++u) a ^= v[u];
     }
-    for (; i < n; i += stride) {
-        const uint4 v = p[i];
-        a.x ^= v.x; a.y ^= v.y; a.z ^= v.z; a.w ^= v.w;
-    }
+    for (; i < n; i += stride) a ^= NT ? __builtin_nontemporal_load(q + i) : q[i];
     if ((a.x ^ a.y ^ a.z ^ a.w) == 0x9E3779B9u && a.x == 0x7F4A7C15u) *sink = a.y;
 }
 // The access pattern of the weight-streaming kernels: every wave walks a contiguous stream of its own,
@@ -158,11 +155,11 @@ __global__ void __launch_bounds__(256) stream_copy_kernel(uint4* __restrict__ ds
 extern "C" int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode, int iters, double* ms_avg) {
     if (!ctx || !buf || !ms_avg) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: NULL argument");
     if (bytes < (1u << 20) || (bytes & 31) || ((size_t)buf & 15)) DSD_FAIL(DSD_ESHAPE, "dsd_stream_probe: bytes=%zu", bytes);
-    if (mode < 0 || mode > 2) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: mode=%d", mode);
+    if (mode < 0 || mode > 3) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: mode=%d", mode);
     if (iters < 1 || iters > 1000) DSD_FAIL(DSD_EINVAL, "dsd_stream_probe: iters=%d", iters);
     DSD_HIP(hipSetDevice(ctx->device));
     DSD_TRY(dsd_ws_reserve(ctx, 256));
-    const size_t n = mode == 0 ? bytes / 16 : bytes / 32;      // mode 1: first half -> second half
+    const size_t n = mode == 1 ? bytes / 32 : bytes / 16;      // mode 1: first half -> second half
     // two workgroups of 256 threads per compute unit, four 16-byte loads per thread in flight (32 KiB per compute
     // unit): the fastest of the grids and depths tried on 1 GiB (6.4 TB/s; 8 workgroups per unit: 5.3, 16 loads: 4.8)
     const int grid = ctx->n_cu * 2;
@@ -174,7 +171,8 @@ extern "C" int dsd_stream_probe(dsd_ctx* ctx, void* buf, size_t bytes, int mode,
         if (mode == 2) {
             const size_t per_stream = (bytes / 16 / ((size_t)grid * 4)) & ~(size_t)1023;
             stream_tiles_kernel<8><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, per_stream, (unsigned*)ctx->ws);
-        } else if (mode == 0) stream_read_kernel<4><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
+        } else if (mode == 0) stream_read_kernel<4, false><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
+        else if (mode == 3) stream_read_kernel<4, true><<<grid, 256, 0, ctx->stream>>>((const uint4*)buf, n, (unsigned*)ctx->ws);
         else stream_copy_kernel<<<grid, 256, 0, ctx->stream>>>((uint4*)buf + n, (const uint4*)buf, n);
     }
     DSD_HIP(hipEventRecord(e1, ctx->stream));

@@ -208,6 +208,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, const int (&til
 __device__ __forceinline__ void gload16_lds(unsigned lds_addr, const void* ptr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(ptr) : "memory");
 }
+// The same for data that is read once (the K/V stream): marked non-temporal, so that it does not push what
+// is read again and again (queries, operand panels, partial results) out of the caches.
+__device__ __forceinline__ void gload16_lds_stream(unsigned lds_addr, const void* ptr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(lds_addr), "v"(ptr) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void vm_wait_all() {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");

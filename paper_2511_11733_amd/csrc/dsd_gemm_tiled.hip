@@ -33,7 +33,7 @@
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void gload16(u32x4& dst, const void* ptr) {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(ptr));
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(ptr));
 }
 // count = loads of ours issued after the one needed (vector memory returns in order; a smaller
 // count than the true number only waits longer)
@@ -281,7 +281,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
                 float* row = p.out + (size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N;
 #pragma unroll
                 for (int nt = 0; nt < NTW; ++nt)
-                    if (live[nt]) row[tile[nt] * 16 + c] = acc[mt][nt][i] * rstd[mt][i];
+                    if (live[nt]) __builtin_nontemporal_store(acc[mt][nt][i] * rstd[mt][i], &row[tile[nt] * 16 + c]);
             }
         }
     if (EPI == TE_SWIGLU) report_saturation(p.sat, worst);

@@ -141,7 +141,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_skinny_kernel(GemmArgs p) {
     for (int ks = wave; ks < p.KS; ks += nw) {
         f16x8 bfrag[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bfrag[nt] = __builtin_bit_cast(f16x8, wt[nt][(size_t)ks * p.NTA * 64]);
+        for (int nt = 0; nt < NT; ++nt) {             // weights are read once: non-temporal
+            typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+            bfrag[nt] = __builtin_bit_cast(f16x8, __builtin_nontemporal_load((const u32x4_t*)(wt[nt] + (size_t)ks * p.NTA * 64)));
+        }
         const int kb = ks * 32 + g * 8;
         f16x8 ahi[MT], alo[MT];
         float gf[8];
@@ -282,8 +285,8 @@ __device__ __forceinline__ void attn_fetch(const bf16_t* __restrict__ kbase, con
     const bf16_t* kt = kbase + (size_t)(j0 >> 5) * block_stride + lane * 8;   // two tiles of 16 keys, 4 fragments each
     const bf16_t* vb = vbase + (size_t)(j0 >> 5) * block_stride + lane * 8;
     for (int f = rg; f < 16; f += n_rg) {
-        if (f < 8) gload16_lds(stage + f * 1024, kt + f * 512);
-        else gload16_lds(stage + f * 1024, vb + (f - 8) * 512);
+        if (f < 8) gload16_lds_stream(stage + f * 1024, kt + f * 512);
+        else gload16_lds_stream(stage + f * 1024, vb + (f - 8) * 512);
     }
 }
 

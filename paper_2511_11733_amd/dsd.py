@@ -155,7 +155,8 @@ class Context:
         return n.value
 
     def stream_probe(self, buf: torch.Tensor, mode: int, iters: int) -> float:
-        """Average milliseconds of one launch of the bare read (mode 0) / copy (mode 1) kernel over buf."""
+        """Average milliseconds of one launch of the bare read (mode 0; 3: non-temporal loads; 2: one stream per
+        wave) / copy (mode 1) kernel over buf."""
         ms = C.c_double()
         _check(self.lib.dsd_stream_probe(self.h, _ptr(buf, None, "buf"), buf.numel() * buf.element_size(), mode, iters,
                                          C.byref(ms)), "dsd_stream_probe")
