@@ -93,7 +93,7 @@ __device__ __forceinline__ void tconsume(u32x4 (&fifo)[NF], const uint4* __restr
         for (int mt = 0; mt < MT; ++mt) a[mt] = __builtin_bit_cast(f16x8, panel[(ks * MT + mt) * 64 + lane]);
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
-            const int slot = S0 + ks * NTW + nt;
+            const int slot = (S0 + ks * NTW + nt) % NF;
             vm_wait<NF - 1>(fifo[slot]);
             const f16x8 b = __builtin_bit_cast(f16x8, fifo[slot]);
 #pragma unroll
@@ -127,7 +127,7 @@ __device__ __forceinline__ void tconsume_halves(u32x4 (&fifo)[NF], const uint4* 
         if (hs + 1 < 8) fetch((hs + 1) & 1, (hs + 1) >> 1, (hs + 1) & 1);
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
-            const int slot = S0 + ks * NTW + nt;
+            const int slot = (S0 + ks * NTW + nt) % NF;
             if (half == 0) {
                 if (nt == 0) vm_wait<NF - 1>(fifo[slot]);
                 else vm_wait<NF - 2>(fifo[slot]);
@@ -203,10 +203,11 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
         w[i] = p.Wt + ((size_t)ks0 * p.NTA + (live[i] ? tile[i] : 0)) * 64 + lane;
     }
 
-    // weight fragments in flight per wave: 8 (4 k-steps), 32-64 KiB per compute unit.  Deeper does not help:
-    // 16 was measured 0.7 % slower per step at 128 rows, 32 no faster (the fill takes longer); a bare read
-    // stream is also fastest with about 32 KiB in flight per compute unit and loses a fifth with 256 KiB.
-    constexpr int NF = 8;
+    // Weight fragments in flight per wave: as many as put about 32 KiB in flight per compute unit, where a bare
+    // read stream is fastest too (24-32 KiB: 7.1-7.4 TB/s; 64 KiB: 6.5; 256 KiB: 5.0): 8 (4 k-steps) for up to
+    // 5 computing waves, 4 from 6 waves on (LM head at 128 rows: 212 -> 186 us; with 4 for every workgroup
+    // size gate/up with 4 waves went from 55.5 to 63.9 us).  Deeper was never faster: 16 measured 0.7 % slower.
+    constexpr int NF = TWC >= 6 ? 4 : 8;
     u32x4 fifo[NF];
     int left = p.ks_per_split - 1;                    // k-steps the stream may still advance
     const size_t kstep = (size_t)p.NTA * 64;          // from one k-step's fragment to the next
@@ -222,8 +223,8 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     __syncthreads();
-    // a chunk consumes 4*NTW slots, so the FIFO turns every NF / (4*NTW) chunks (1, 2 or 4);
-    // ks_per_split is a multiple of 16 k-steps = 4 chunks
+    // a chunk consumes 4*NTW slots: the FIFO turns twice per chunk (NF = 4) or once (NF = 8), slot numbers are
+    // taken modulo NF; ks_per_split is a multiple of 16 k-steps = 4 chunks
 #define TILED_CHUNK(Q)                                                                          \
     {                                                                                           \
         if (MT >= 6) tconsume_halves<MT, NF, ((Q) * 4 * NTW) % NF>(fifo, lds + ((Q) & 1) * pbuf, acc, w, left, kstep, lane); \
