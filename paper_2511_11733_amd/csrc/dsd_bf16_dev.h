@@ -226,7 +226,6 @@ struct AttnArgs {
     const int32_t* len;
     const uint64_t* mask;
     int k, Hq, G;
-    int keys_per_wave;     // multiple of 32
     int n_runs;            // runs per (sequence, kv head)
     int* sat;              // counter of values that left the fp16 range
     float* part_o;         // [B][Hkv][n_runs][rows_pad][128]

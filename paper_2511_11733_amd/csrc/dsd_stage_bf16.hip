@@ -610,20 +610,16 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     int max_len = 0;
     for (int b = 0; b < B; ++b) max_len = std::max(max_len, kv->len_bound[b]);
     const int max_keys = std::min(max_len + k, g.S);
-    // Runs of keys: aim at 8 waves per compute unit over the whole grid (one round, two waves per SIMD; 4, 10,
-    // 12 and 16 were measured slower at every workload); small problems take shorter runs (at least 64 keys)
-    // so that more compute units take part.
+    // Runs of keys.  A workgroup is one run (its n_rg waves; two runs in a workgroup share its barrier and were
+    // measured 13 % slower), as many workgroups per compute unit as give at most 8 waves there, and a number of
+    // runs per (sequence, head) that makes the grid whole rounds of that: 8 runs at B = 16 (1024 workgroups of 2
+    // waves), at the 70B shape with B = 8 (512 of 3) and for a 32-node tree at B = 4 (256 of 8) -- with 6, 10 or 12
+    // runs each of the three is 5-25 % slower.  Small problems take shorter runs, of at least 64 keys.
     const long units = (long)B * Hkv;
-    const long wave_slots = (long)ctx->n_cu * 8;
-    long kpw = ((long)max_keys * units * n_rg + wave_slots - 1) / wave_slots;
-    kpw = std::max(64L, (kpw + 31) / 32 * 32);
-    const int keys_per_wave = (int)kpw;
-    int n_runs = (max_keys + keys_per_wave - 1) / keys_per_wave;
-    // runs per workgroup: workgroups of about 4 waves (at most 8), when there are enough runs to go round
-    const long n_waves = units * n_rg * n_runs;
-    int rpw = std::max(1, 4 / n_rg);
-    if (n_waves < wave_slots / 2) rpw = 1;
-    rpw = std::min(rpw, n_runs);
+    const long wg_per_cu = std::max(1, 8 / n_rg);
+    long runs_wanted = std::max(1L, wg_per_cu * ctx->n_cu / units);
+    int n_runs = (int)std::min(runs_wanted, (long)std::max(1, max_keys / 64));
+    const int rpw = 1;
     if (n_runs > MAX_RUNS) DSD_FAIL(DSD_EUNSUPPORTED, "bf16 path: %d key runs", n_runs);
     const int rows_pad = (n_rt + RT - 1) / RT * RT * 16;      // whole row groups
 
@@ -692,7 +688,7 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
         // attention
         AttnArgs t;
         t.q = q; t.kc = kc; t.vc = vc; t.g = g; t.len = kv->len_dev; t.mask = tree_mask; t.k = k; t.Hq = Hq; t.G = G;
-        t.keys_per_wave = keys_per_wave; t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
+        t.n_runs = n_runs; t.part_o = part_o; t.part_ml = part_ml;
         t.sat = ctx->sat_dev; t.rows_pad = rows_pad; t.scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
         {
             ProfScope ps(ctx, DSD_KC_ATTN);
