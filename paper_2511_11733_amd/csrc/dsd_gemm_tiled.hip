@@ -32,6 +32,10 @@
 #define NTW 2            // 16-column tiles per computing wave
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+// A weight fragment on its way into a FIFO register.  Weights are read once per pass: the load is marked
+// non-temporal, so that the stream does not push the operand panel, which every workgroup reads again and
+// again, out of the caches (a bare read runs at 6.9-7.4 TB/s that way against 6.3-6.5 with plain loads; the
+// gate/up GEMM at 48 rows went from 163 to 148 us).
 __device__ __forceinline__ void gload16(u32x4& dst, const void* ptr) {
     asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(ptr));
 }
@@ -282,6 +286,7 @@ __global__ void __launch_bounds__((TWC + TP) * 64, TWC > 4 ? 3 : (MT <= 3 ? 4 : 
                 float* row = p.out + (size_t)(m / p.rows_per_seq) * p.seq_stride + (size_t)(m % p.rows_per_seq) * p.N;
 #pragma unroll
                 for (int nt = 0; nt < NTW; ++nt)
+                    // tens of megabytes written once: past the caches (LM head 210 -> 196 us at 128 rows)
                     if (live[nt]) __builtin_nontemporal_store(acc[mt][nt][i] * rstd[mt][i], &row[tile[nt] * 16 + c]);
             }
         }
