@@ -111,10 +111,6 @@ def dominant_kernel(cfg, kern, per_layer, total_bytes):
     the gate/up GEMM (54 % of a layer's weight bytes)."""
     m = cfg.model
     M = cfg.B * cfg.k
-    if M <= 3 and m.d // 16 <= 256:       # the library's switch-over between its two GEMM paths
-        return ("gateup", per_layer["gateup"],
-                "gemm_skinny_kernel<1, 2, A_F32_GAIN, EPI_SWIGLU, 4> (RMSNorm + gate/up GEMM + SiLU*up, one launch)",
-                "gemm_skinny_kernel<1, 2, 0, 1")
     mt = (M + 15) // 16
     mt = {1: 2, 5: 6, 7: 8}.get(mt, mt)
     # computing waves per workgroup as the library picks them: least work on the busiest of the 256 compute units

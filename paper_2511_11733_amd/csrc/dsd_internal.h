@@ -173,8 +173,7 @@ int mfma_weights_tile(dsd_ctx* ctx, dsd_weights* w, const void* const* tensors);
 int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void* hidden_in,
                       const int32_t* draft_tokens, const uint64_t* tree_mask, const int32_t* depth, int B,
                       int k, void* hidden_out, float* logits, int64_t logits_seq_stride);
-// weight-streaming GEMMs for TILED_MIN_ROWS..128 rows (dsd_gemm_tiled.hip)
-#define TILED_MIN_ROWS 4
+// weight-streaming GEMMs for up to 128 rows (dsd_gemm_tiled.hip)
 int tiled_supported(const dsd_model_desc* d);
 // rope[m][e] = (cos, sin) of (len[m/k] + depth[m%k]) * theta^(-2e/128), e < 64, worked out in fp64
 void rope_table_launch(dsd_ctx* ctx, float2* rope, const int32_t* len, const int32_t* depth, int M, int k, float theta);

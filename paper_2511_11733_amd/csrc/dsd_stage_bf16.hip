@@ -593,16 +593,15 @@ int mfma_stage_verify(dsd_ctx* ctx, const dsd_weights* w, dsd_kv* kv, const void
     const int tiles_per_launch = std::min(n_rt, 16);
     const int RT = tiles_per_launch > 8 ? 2 : 1;
     const int n_rg = (tiles_per_launch + RT - 1) / RT;
-    // Which GEMM path.  One workgroup per column tile converting the activations itself
-    // (gemm_skinny_kernel) wins only for up to 3 rows, and only when the residual GEMMs (d_model / 16
-    // tiles) are exactly one round of one workgroup per compute unit: d_model 4096 on 256 CUs, 0.826
-    // against 0.831 ms per step of 8 layers at 1 row; the panel path wins from there on (0.842 against
-    // 0.851 ms at 5 rows, 0.846 against 0.879 at 8, 0.858 against 0.931 at 10, 0.861 against 0.957
-    // at 11).  Wider models leave that kernel a ragged second round, and the panel path wins at every
-    // row count: per layer at 5 rows 136.9 against 149.0 us (d_model 5120), 166.8 against 182.4
-    // (6144), 333.7 against 353.2 (8192).
-    const int tiled_min_rows = d / 16 <= ctx->n_cu ? TILED_MIN_ROWS : 1;
-    const bool tiled = M >= tiled_min_rows && tiled_supported(&D) && !ctx->no_tiled;
+    // Which GEMM path.  The panel path (dsd_gemm_tiled.hip) at every row count for every shape it takes; one
+    // workgroup per column tile converting the activations itself (gemm_skinny_kernel) for the others, and
+    // with DSD_NO_TILED for tests.  Measured at d_model 4096, ms per step of 8 layers, panel path against
+    // the other: 0.795 / 0.838 at 4 rows, 0.795 / 0.837 at 5; the other path's 1 to 3 rows take 0.817 to 0.829,
+    // more than the panel path's 4.  (Before the weights were read with non-temporal loads the other kernel
+    // won up to 3 rows, where d_model / 16 = 256 tiles are exactly one workgroup per compute unit.)  Wider
+    // models were always faster on the panel path: per layer at 5 rows 136.9 against 149.0 us (d_model 5120),
+    // 166.8 against 182.4 (6144), 333.7 against 353.2 (8192).
+    const bool tiled = tiled_supported(&D) && !ctx->no_tiled;
     // The LM head takes the panel path at every row count: a vocabulary is a gigabyte of weights, and 256-column
     // workgroups stream it faster than one workgroup per 16 columns (207 against 228 us at 5 rows, V = 128256).
     const bool tiled_head = logits && tiled_supported(&D) && !ctx->no_tiled;

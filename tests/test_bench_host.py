@@ -42,7 +42,7 @@ def test_traffic_is_read_from_the_counter_table_not_the_timing_table():
 
 def test_dominant_kernel_names_the_kernel_the_library_launches():
     """The name fragments must exist in the committed summaries of the same workloads (they are what the
-    traffic figure is looked up by), and the skinny kernel is named only below the 4-row switch-over."""
+    traffic figure is looked up by)."""
     for name in ("c2", "c3", "c4", "c5"):
         cfg = W.CONFIGS[name]
         _, _, label, match = bench.dominant_kernel(cfg, None, {"gateup": 1.0}, 0)
@@ -50,7 +50,7 @@ def test_dominant_kernel_names_the_kernel_the_library_launches():
         text = open(os.path.join(ROOT, "profiles", f"verify_step_{name}.txt")).read()
         assert match in text, (name, match)
     one_row = W.scaled(W.CONFIGS["c2"], name="one_row", B=1, k=1, C=64)
-    assert "gemm_skinny_kernel" in bench.dominant_kernel(one_row, None, {"gateup": 1.0}, 0)[3]
+    assert "gemm_tiled_kernel<2, 4, 1>" == bench.dominant_kernel(one_row, None, {"gateup": 1.0}, 0)[3]
 
 
 def test_thresholds_are_the_frozen_calibrated_ones():

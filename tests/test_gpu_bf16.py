@@ -112,7 +112,7 @@ def test_head_dim_64_in_bf16_takes_the_generic_kernels():
 
 
 def test_both_gemm_paths_on_the_same_case():
-    """2, 5, 10, 15 and 40 rows through the default path (the panel GEMMs from 4 rows on) and, with DSD_NO_TILED,
+    """2, 5, 10, 15 and 40 rows through the default path (the panel GEMMs) and, with DSD_NO_TILED,
     through the one-workgroup-per-tile kernels: each against the oracle."""
     for name, B, k in (("both_m2", 1, 2), ("both_m5", 1, 5), ("both_m10", 2, 5), ("both_m15", 3, 5), ("both_m40", 5, 8)):
         case = mini(name, B=B, k=k, lens=[90 + 13 * b for b in range(B)], head=True, V=4112, L=2)
