@@ -179,6 +179,19 @@ def test_empty_context():
     check(mini("mini_empty", B=2, k=6, lens=[0, 0]))
 
 
+def test_long_context_is_cut_into_hundreds_of_key_runs():
+    """One sequence with 20 000 cached positions and two kv heads: the attention takes the most runs per
+    (sequence, head) that runs of 64 keys allow (about 300), and the combine kernel merges them all."""
+    check(mini("mini_long", B=1, k=5, lens=[20000], L=1))
+
+
+def test_many_sequences_ragged_lengths():
+    """40 sequences x 8 kv heads = 320 (sequence, head) units, more than one per compute unit: few runs per
+    unit, and lengths from empty to several runs long in the same launch."""
+    lens = [(37 * b) % 700 for b in range(40)]
+    check(mini("mini_b40", B=40, k=3, lens=lens, Hq=8, Hkv=8, L=1))
+
+
 def test_k1_plain_decode_step():
     check(mini("mini_k1", B=5, k=1, lens=[40, 41, 63, 64, 65]))
 
